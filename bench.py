@@ -1,0 +1,160 @@
+"""Benchmark of the batched verification step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 13b] [--no-cpu-baseline]
+
+One step = one pass of the whole hot path over one synthetic batch that is already resident in
+HBM: spin_decompose (when the configuration decomposes), spin_verify_attn (schedule, stream K/V,
+QK^T, mask, online softmax, PV, join) for ONE attention layer, and spin_accept (rejection mode:
+row statistics, first-reject scan, residual / bonus draw).  Prints one JSON line.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+
+def cpu_baseline(cfg, batch, ab, budget_s=20.0):
+    """The float64 oracle, as it stands, timed on this machine's host cores on a bounded sample of
+    the same batch, scaled to whole-batch verified draft tokens/s."""
+    import numpy as np
+    import spin_inputs as si
+    from oracle import spin_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    t = batch.table
+    rng = np.random.default_rng(0)
+    n_tok = (t.prefix_len.astype(np.int64) + t.draft_len)
+    total_cells = float((n_tok * cfg.n_q_heads).sum())
+    kb, vb, qb = si.bf16_bits(batch.k_pool), si.bf16_bits(batch.v_pool), si.bf16_bits(batch.q)
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+    order = rng.permutation(t.n_req)
+    done_cells, t_attn, n_pairs = 0.0, 0.0, 0
+    for i in order:
+        h = int(rng.integers(cfg.n_q_heads))
+        t0 = time.perf_counter()
+        orc.verify_attention(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, cfg.page_size,
+                             qb, kb, vb, cfg.n_q_heads, cfg.n_kv_heads, scale, requests=[int(i)], heads=[h])
+        t_attn += time.perf_counter() - t0
+        done_cells += float(n_tok[i])
+        n_pairs += 1
+        if t_attn > budget_s * 0.6:
+            break
+    attn_full = t_attn * total_cells / done_cells
+    # acceptance on the first requests until the budget is used
+    nreq = 0
+    rows = 0
+    while nreq < t.n_req and rows < 48:
+        rows += int(t.draft_len[nreq]); nreq += 1
+    tl = ab.target_logits[: rows + nreq].cpu().numpy()
+    dl = ab.draft_logits[:rows].cpu().numpy()
+    t0 = time.perf_counter()
+    orc.accept_rejection(t.draft_len[:nreq], ab.draft_tokens[:rows].cpu().numpy(), tl, dl,
+                         ab.u_accept[:rows].cpu().numpy(), ab.u_sample[:nreq].cpu().numpy())
+    t_acc = time.perf_counter() - t0
+    acc_full = t_acc * t.n_req / nreq
+    value = t.n_rows / (attn_full + acc_full)
+    return {"value": value, "unit": "verified draft tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"attention: {n_pairs} random (request, head) pairs = {done_cells / total_cells:.3%} of the "
+                      f"batch's key-head rows in {t_attn:.1f} s; acceptance: first {nreq} of {t.n_req} requests in "
+                      f"{t_acc:.2f} s; both scaled linearly to the whole batch"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="13b")
+    ap.add_argument("--seed", type=int, default=3)
+    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2503_15921_amd as spin
+    import spin_inputs as si
+
+    cfg = si.CONFIGS[args.config]
+    dev = "cuda:0"
+    batch = si.make_verify_batch(cfg, args.seed, device=dev)
+    t = batch.table
+    ab = si.make_accept_batch(t.draft_len, cfg.vocab, cfg.logit_sigma, args.seed, device=dev)
+    ctx = spin.SpinContext(0)
+    if args.chunk:
+        ctx.set_chunk(args.chunk)
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    out = torch.empty_like(batch.q)
+    n_acc = torch.empty(t.n_req, dtype=torch.int32, device=dev)
+    nxt = torch.empty_like(n_acc)
+
+    def step():
+        subs = None
+        if cfg.q_split_width:
+            subs, _ = spin.decompose(t.prefix_len, t.draft_len, spin.DECOMP_Q_SPLIT, q_width=cfg.q_split_width)
+        ctx.verify_attn(tab, batch.k_pool, batch.v_pool, batch.q, out, cfg.n_q_heads, subs=subs)
+        ctx.accept(spin.ACCEPT_REJECTION, t.draft_len, ab.draft_tokens, ab.target_logits, ab.draft_logits,
+                   ab.u_accept, ab.u_sample, n_acc, nxt)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_begin(args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms, calls = ctx.profile_end()
+
+    ms_per_step = wall * 1e3 / args.steps
+    kv_bytes = si.algorithmic_kv_bytes(t, cfg.n_kv_heads, cfg.head_dim)
+    attn_ms = ms["attn"] / max(calls[0], 1)
+    achieved = kv_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    res = {
+        "metric": "verified draft tokens/sec + achieved KV HBM GB/s (% peak), batched verify step",
+        "value": t.n_rows / (ms_per_step * 1e-3),
+        "unit": "verified draft tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_req} requests, {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, "
+                               f"head_dim {cfg.head_dim}, prefix {cfg.prefix_dist} {cfg.prefix_lo}-{cfg.prefix_hi}, "
+                               f"draft {cfg.draft_dist} {cfg.draft_lo}-{cfg.draft_hi}, page {cfg.page_size}, "
+                               f"vocab {cfg.vocab}; one attention layer + one rejection-sampling accept",
+                   "seed": args.seed, "draft_rows": t.n_rows, "kv_tokens": t.kv_tokens(),
+                   "kv_gb_per_step": kv_bytes / 1e9, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS},
+        "kernel_ms": {"attn": attn_ms, "join": ms["join"] / max(calls[0], 1),
+                      "row_stats": ms["row_stats"] / max(calls[1], 1), "finish": ms["finish"] / max(calls[1], 1)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "verify_attn_kernel", "algorithmic_bytes_per_launch": kv_bytes},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg, batch, ab)
+    ctx.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

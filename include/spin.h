@@ -1,0 +1,224 @@
+/*
+ * spin.h -- C ABI of the batched verification step of speculative decoding on one MI355X.
+ *
+ * The step: every request of a batch brings its own number of draft (candidate) tokens from a
+ * small speculative model; the large model checks them all in one pass.  This library holds the
+ * data-parallel part of that pass:
+ *
+ *   spin_decompose    split requests into sub-requests                      (Sec. V-A)
+ *   spin_verify_attn  attention of each request's draft queries over its cached prefix plus a
+ *                     causal draft block, read through a page table, exact across sub-requests
+ *                                                                (Sec. II-A1 Eq. (2), Sec. V-A Eq. (13))
+ *   spin_accept       greedy-match or rejection-sampling acceptance of the draft tokens
+ *                                                                (verification phase, Sec. II-A2)
+ *
+ * Conventions
+ *   - Plain C, no exceptions cross this boundary.  Every function returns SPIN_OK (0) or a
+ *     negative SPIN_E* code; spin_last_error() gives the text of the last failure of a context.
+ *   - "host" pointers are ordinary CPU memory, read during the call and free to go when it
+ *     returns.  "device" pointers are HIP device memory of the context's GPU; the caller owns
+ *     them, the library never frees or resizes them and never writes to an input.
+ *   - Calls that take a stream only enqueue work on it (HIP stream handle passed as void*;
+ *     NULL = the default stream).  All errors the host can see are reported before anything is
+ *     launched.  Outputs are valid once the stream has been synchronised.
+ *   - Request i has prefix length p_i >= 0 (tokens whose K/V are cached and that ask nothing)
+ *     and draft length g_i >= 1 (tokens whose K/V are ALSO already in the cache, at positions
+ *     p_i .. p_i+g_i-1, and which each issue one query row).  Draft row t sees keys 0 .. p_i+t.
+ *   - One context must not be used from two host threads at once.
+ */
+#ifndef SPIN_H
+#define SPIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPIN_OK 0
+#define SPIN_EINVAL (-1)       /* null pointer, negative size, draft length < 1, ...            */
+#define SPIN_ETABLE (-2)       /* inconsistent request table / page table / sub-request tiling  */
+#define SPIN_ENOSPC (-3)       /* output capacity or reserved workspace too small               */
+#define SPIN_EUNSUPPORTED (-4) /* a shape or type this build has no kernel for                  */
+#define SPIN_EHIP (-5)         /* a HIP runtime call failed; text via spin_last_error           */
+
+#define SPIN_DTYPE_BF16 1
+
+typedef struct spin_ctx spin_ctx;
+
+/* Ragged request table.  All arrays are host memory.
+ *   prefix_len[n_req], draft_len[n_req]
+ *   q_offset[n_req+1]   first packed query/output row of each request; q_offset[0] = 0 and
+ *                       q_offset[i+1] - q_offset[i] = draft_len[i]
+ *   pt_offset[n_req+1]  first page-table entry of each request (non-decreasing)
+ *   page_table[pt_offset[n_req]]  physical page ids; request i needs at least
+ *                       ceil((p_i+g_i)/page_size) entries; token j of the request lives in page
+ *                       page_table[pt_offset[i] + j/page_size], slot j % page_size. */
+typedef struct spin_req_table {
+    int32_t n_req;
+    const int32_t* prefix_len;
+    const int32_t* draft_len;
+    const int32_t* q_offset;
+    const int32_t* pt_offset;
+    const int32_t* page_table;
+} spin_req_table;
+
+/* Paged K/V cache.  k_pool / v_pool are device pointers to bf16 elements.  Element (page, kv
+ * head, slot, c) sits at  page*page_stride + head*head_stride + slot*token_stride + c  (strides
+ * in elements, the head dimension is contiguous, token_stride >= head_dim and a multiple of 8,
+ * both pools 16-byte aligned).  The streaming kernels are tuned for
+ * [n_pages][n_kv_heads][page_size][head_dim].  page_size must be a power of two. */
+typedef struct spin_kv_desc {
+    const void* k_pool;
+    const void* v_pool;
+    int32_t n_pages;
+    int32_t page_size;
+    int32_t n_kv_heads;
+    int32_t head_dim;          /* 64 or 128 */
+    int64_t page_stride;
+    int64_t head_stride;
+    int64_t token_stride;
+    int32_t dtype;             /* SPIN_DTYPE_BF16 */
+} spin_kv_desc;
+
+/* A sub-request: a rectangle of its parent's (draft row x key) score matrix.  It refers to the
+ * parent's query rows and pages by offset; nothing is copied or replicated (the replicated Q
+ * rows of Sec. V-A exist only as these references).  Cells of the rectangle beyond the causal
+ * edge (key > p + row) hold nothing. */
+typedef struct spin_subreq {
+    int32_t parent;            /* index into the request table                  */
+    int32_t q_begin, q_len;    /* draft rows  [q_begin, q_begin+q_len)          */
+    int32_t kv_begin, kv_len;  /* keys        [kv_begin, kv_begin+kv_len)       */
+} spin_subreq;
+
+#define SPIN_DECOMP_NONE 0      /* one sub-request per request                                     */
+#define SPIN_DECOMP_Q_SPLIT 1   /* cut the draft block into pieces of q_width rows                 */
+#define SPIN_DECOMP_KV_SPLIT 2  /* Sec. V-A: rows of a KV tensor of length kv_len; the whole draft
+                                   block rides along with every piece                             */
+#define SPIN_DECOMP_KV_SEARCH 3 /* Sec. V-A: cap the tensor width (number of rows) at max_subreq,
+                                   pick the length L in [l_min, l_max] (multiples of l_step) with
+                                   the fewest padding tokens, ties to the larger L; then KV_SPLIT  */
+
+typedef struct spin_decomp_params {
+    int32_t policy;
+    int32_t q_width;     /* Q_SPLIT: draft rows per sub-request (>= 1)        */
+    int32_t kv_len;      /* KV_SPLIT: L (>= 1)                                */
+    int32_t max_subreq;  /* KV_SEARCH: width cap B                            */
+    int32_t l_min, l_max, l_step; /* KV_SEARCH: candidate lengths             */
+} spin_decomp_params;
+
+/* ---- lifetime ---------------------------------------------------------------------------- */
+
+/* Create a context on HIP device `device_id`.  Fails with SPIN_EHIP when no such device. */
+int spin_create(spin_ctx** out, int device_id);
+
+/* Allocate (or grow to) workspace for batches of up to max_req requests, max_rows draft rows in
+ * total, max_pages page-table entries, max_items work items and max_part_slots partial result
+ * rows.  This is the only call that allocates device or pinned memory; it synchronises the
+ * device.  spin_verify_attn / spin_accept return SPIN_ENOSPC when the reservation is too small
+ * and spin_required() then reports what the refused call needed. */
+int spin_reserve(spin_ctx* ctx, int64_t max_req, int64_t max_rows, int64_t max_pages,
+                 int64_t max_items, int64_t max_part_slots);
+
+/* Sizes the last call on this context that returned SPIN_ENOSPC would have needed (any pointer
+ * may be NULL). */
+int spin_required(spin_ctx* ctx, int64_t* req, int64_t* rows, int64_t* pages, int64_t* items,
+                  int64_t* part_slots);
+
+/* Wait for outstanding work of this context, free everything it owns. NULL is allowed. */
+void spin_destroy(spin_ctx* ctx);
+
+const char* spin_strerror(int code);
+
+/* Copy the text of the context's last error into buf (NUL-terminated, truncated to n). */
+int spin_last_error(spin_ctx* ctx, char* buf, size_t n);
+
+/* KV chunk length of the scheduler (keys per work item, multiple of 32; default 256).  Work
+ * items longer than this are cut so that the chip is filled evenly (the same split-and-rejoin
+ * as Eq. (13), used as a scheduler). */
+int spin_set_chunk(spin_ctx* ctx, int32_t keys_per_item);
+
+/* ---- decomposition (host only, no GPU needed) -------------------------------------------- */
+
+/* Sec. V-A.  Writes the sub-requests of `table` under `params` to out[0..cap) in the order
+ * parent ascending, then q_begin, then kv_begin, and their number to *n_out.  If cap is too
+ * small returns SPIN_ENOSPC with *n_out = the number needed (out may then be NULL).  With
+ * KV_SEARCH, *kv_len_out (may be NULL) receives the chosen L; SPIN_ENOSPC with *n_out = 0 if no
+ * candidate L fits under max_subreq.  Only prefix_len and draft_len of the table are read. */
+int spin_decompose(const spin_req_table* table, const spin_decomp_params* params,
+                   spin_subreq* out, int32_t cap, int32_t* n_out, int32_t* kv_len_out);
+
+/* The padding-token count and row count of the B x L KV tensor of Sec. V-A for a given L. */
+int spin_kv_padding(const spin_req_table* table, int32_t kv_len, int64_t* n_rows, int64_t* n_pad);
+
+/* Check that subs tile every request exactly once (every visible (draft row, key) cell of every
+ * request covered by exactly one sub-request).  SPIN_OK or SPIN_ETABLE.  Host only. */
+int spin_check_tiling(const spin_req_table* table, const spin_subreq* subs, int32_t n_sub);
+
+/* The scheduler's view of a batch, for inspection and tests (host only).  Work item k covers
+ * draft rows [q_begin, q_begin+q_len) x keys [kv_begin, kv_begin+kv_len) of `parent`, clipped
+ * at the causal edge like a sub-request.  `group` = n_q_heads / n_kv_heads.  Same cap/n_out
+ * protocol as spin_decompose.  subs == NULL means one sub-request per request. */
+int spin_schedule(const spin_req_table* table, const spin_subreq* subs, int32_t n_sub,
+                  int32_t page_size, int32_t group, int32_t keys_per_item,
+                  spin_subreq* items_out, int32_t cap, int32_t* n_out);
+
+/* ---- the verification step ---------------------------------------------------------------- */
+
+/* Sec. II-A1 Eq. (2) with the normalisation of Sec. V-A Eq. (13).
+ *   q_dev  device, bf16 [R][n_q_heads][head_dim], R = q_offset[n_req]   (read)
+ *   o_dev  device, bf16 [R][n_q_heads][head_dim]                         (every row written once)
+ *   subs   host, n_sub sub-requests that tile the batch exactly once, or NULL for none
+ *   softmax_scale  multiplies Q.K before exp; <= 0 selects 1/sqrt(head_dim); 1 is the literal
+ *                  formula of Eq. (2)
+ * Query head h uses KV head h / (n_q_heads / n_kv_heads).  Whatever the decomposition, the output
+ * of a draft row is its attention over ALL keys it may see in the original request.
+ * Errors: SPIN_EINVAL, SPIN_ETABLE (table or tiling inconsistent, page id outside the pool),
+ * SPIN_EUNSUPPORTED (head_dim, dtype, page size, group > 64), SPIN_ENOSPC (reserve more),
+ * SPIN_EHIP. */
+int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table,
+                     const spin_subreq* subs, int32_t n_sub, const void* q_dev, void* o_dev,
+                     int32_t n_q_heads, float softmax_scale, void* hip_stream);
+
+#define SPIN_ACCEPT_GREEDY 0
+#define SPIN_ACCEPT_REJECTION 1
+
+/* Verification phase of Sec. II-A2 (the paper prints no rule; this is the speculative-sampling
+ * rule of the works it builds on), float64 arithmetic on fp32 logits.
+ *   draft_len_host      host   int32 [n_req]
+ *   draft_tokens_dev    device int32 [R]
+ *   target_logits_dev   device fp32 [R+n_req][vocab]; request i owns rows q_offset[i]+i ..
+ *                       q_offset[i]+i+g_i, the last one being the bonus row
+ *   draft_logits_dev    device fp32 [R][vocab]            (REJECTION only, else may be NULL)
+ *   u_accept_dev        device fp64 [R]  in [0,1)         (REJECTION only)
+ *   u_sample_dev        device fp64 [n_req] in [0,1)      (REJECTION only)
+ *   n_accepted_dev      device int32 [n_req]  out: number of leading draft tokens kept, 0..g_i
+ *   next_token_dev      device int32 [n_req]  out: the token emitted after them
+ * GREEDY: draft token t is kept iff it equals the arg-max (lowest id on ties) of target row t;
+ * next token = arg-max of target row n.  REJECTION: with p, q the softmax of the target / draft
+ * row, token d_t is kept iff u_t*q(d_t) < p(d_t); on the first rejection the next token is the
+ * smallest k with sum_{x<=k} max(0,p-q)(x) > u'*Z (from p itself if Z = 0), otherwise the same
+ * inverse CDF on the bonus row's p. */
+int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft_len_host,
+                const int32_t* draft_tokens_dev, const float* target_logits_dev,
+                const float* draft_logits_dev, int32_t vocab, const double* u_accept_dev,
+                const double* u_sample_dev, int32_t* n_accepted_dev, int32_t* next_token_dev,
+                void* hip_stream);
+
+/* ---- measurement aid ------------------------------------------------------------------------ */
+
+/* Time the kernels of the next calls with HIP events recorded on the stream each call is given
+ * (nothing is synchronised until spin_profile_end).  spin_profile_begin arms up to max_calls
+ * calls of spin_verify_attn and as many of spin_accept; further calls run untimed.
+ * spin_profile_end waits for the recorded events and returns the summed durations in
+ * milliseconds: ms[0] attention kernels, ms[1] partial-join kernel, ms[2] logits row-statistics
+ * kernel, ms[3] acceptance scan / next-token kernel; calls[0] / calls[1] = timed calls of
+ * spin_verify_attn / spin_accept.  It disarms the context. */
+int spin_profile_begin(spin_ctx* ctx, int32_t max_calls);
+int spin_profile_end(spin_ctx* ctx, double ms[4], int32_t calls[2]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPIN_H */

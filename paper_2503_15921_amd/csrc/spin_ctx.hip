@@ -1,0 +1,450 @@
+// Context, workspace and the two GPU entry points of libspin (spin_verify_attn, spin_accept).
+// Host code only; the kernels are in spin_attn.hip and spin_accept.hip.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+
+#include "spin_device.h"
+
+namespace {
+
+constexpr int kStages = 4;   // pinned staging buffers cycled between calls
+
+inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+}  // namespace
+
+struct spin_ctx {
+    int device = 0;
+    std::string err;
+    int chunk = spin::kDefaultChunk;
+    // reserved capacities and what the last refused call needed
+    int64_t cap_req = 0, cap_rows = 0, cap_pages = 0, cap_items = 0, cap_slots = 0;
+    int64_t need_req = 0, need_rows = 0, need_pages = 0, need_items = 0, need_slots = 0;
+    // device workspace
+    char* d_blob = nullptr;        // tables of the current call (items, orders, offsets, page table)
+    size_t blob_bytes = 0;
+    float* d_part_o = nullptr;
+    float* d_part_ml = nullptr;
+    float* d_row_max = nullptr;    // acceptance row statistics
+    double* d_row_sum = nullptr;
+    int32_t* d_row_arg = nullptr;
+    int32_t* d_row_off = nullptr;
+    // pinned staging ring
+    char* h_stage[kStages] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ev[kStages] = {nullptr, nullptr, nullptr, nullptr};
+    bool ev_pending[kStages] = {false, false, false, false};
+    int stage = 0;
+    spin::Plan plan;
+    std::vector<int32_t> row_off_host;
+    // kernel timing (spin_profile_begin / _end): three events per timed call
+    std::vector<hipEvent_t> prof_attn, prof_accept;
+    int prof_attn_used = 0, prof_accept_used = 0;
+    bool prof_on = false;
+};
+
+namespace {
+
+int fail(spin_ctx* ctx, int code, const std::string& text) {
+    if (ctx) ctx->err = text;
+    return code;
+}
+
+int fail_hip(spin_ctx* ctx, hipError_t e, const char* where) {
+    if (ctx) ctx->err = std::string(where) + ": " + hipGetErrorString(e);
+    return SPIN_EHIP;
+}
+
+void free_profile(spin_ctx* c) {
+    for (hipEvent_t e : c->prof_attn) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->prof_accept) (void)hipEventDestroy(e);
+    c->prof_attn.clear();
+    c->prof_accept.clear();
+    c->prof_attn_used = c->prof_accept_used = 0;
+    c->prof_on = false;
+}
+
+// Events of the next timed call, or null when the context is not armed / has run out of slots.
+hipEvent_t* prof_slot(spin_ctx* c, std::vector<hipEvent_t>& pool, int& used) {
+    if (!c->prof_on || (size_t)(used + 1) * 3 > pool.size()) return nullptr;
+    hipEvent_t* p = pool.data() + (size_t)used * 3;
+    ++used;
+    return p;
+}
+
+void free_workspace(spin_ctx* c) {
+    if (c->d_blob) (void)hipFree(c->d_blob);
+    if (c->d_part_o) (void)hipFree(c->d_part_o);
+    if (c->d_part_ml) (void)hipFree(c->d_part_ml);
+    if (c->d_row_max) (void)hipFree(c->d_row_max);
+    if (c->d_row_sum) (void)hipFree(c->d_row_sum);
+    if (c->d_row_arg) (void)hipFree(c->d_row_arg);
+    if (c->d_row_off) (void)hipFree(c->d_row_off);
+    for (int s = 0; s < kStages; ++s)
+        if (c->h_stage[s]) (void)hipHostFree(c->h_stage[s]);
+    c->d_blob = nullptr;
+    c->d_part_o = c->d_part_ml = c->d_row_max = nullptr;
+    c->d_row_sum = nullptr;
+    c->d_row_arg = c->d_row_off = nullptr;
+    for (int s = 0; s < kStages; ++s) c->h_stage[s] = nullptr;
+}
+
+size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
+    return align16(items * sizeof(spin::Item)) + 3 * 16 + align16(items * 4) + align16((req + 1) * 4) +
+           align16(rows * 4) + align16(pages * 4) + 64;
+}
+
+// Next pinned staging buffer; waits until the copy that last used it has left the host.
+int next_stage(spin_ctx* c, char** out) {
+    c->stage = (c->stage + 1) % kStages;
+    const int s = c->stage;
+    if (c->ev_pending[s]) {
+        hipError_t e = hipEventSynchronize(c->ev[s]);
+        if (e != hipSuccess) return fail_hip(c, e, "hipEventSynchronize");
+        c->ev_pending[s] = false;
+    }
+    *out = c->h_stage[s];
+    return SPIN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int spin_create(spin_ctx** out, int device_id) {
+    if (!out) return SPIN_EINVAL;
+    *out = nullptr;
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess || device_id < 0 || device_id >= n) return SPIN_EHIP;
+    e = hipSetDevice(device_id);
+    if (e != hipSuccess) return SPIN_EHIP;
+    spin_ctx* c = new spin_ctx();
+    c->device = device_id;
+    for (int s = 0; s < kStages; ++s) {
+        e = hipEventCreateWithFlags(&c->ev[s], hipEventDisableTiming);
+        if (e != hipSuccess) {
+            for (int k = 0; k < s; ++k) (void)hipEventDestroy(c->ev[k]);
+            delete c;
+            return SPIN_EHIP;
+        }
+    }
+    *out = c;
+    return SPIN_OK;
+}
+
+void spin_destroy(spin_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+    free_workspace(ctx);
+    free_profile(ctx);
+    for (int s = 0; s < kStages; ++s)
+        if (ctx->ev[s]) (void)hipEventDestroy(ctx->ev[s]);
+    delete ctx;
+}
+
+int spin_last_error(spin_ctx* ctx, char* buf, size_t n) {
+    if (!ctx || !buf || n == 0) return SPIN_EINVAL;
+    snprintf(buf, n, "%s", ctx->err.c_str());
+    return SPIN_OK;
+}
+
+int spin_set_chunk(spin_ctx* ctx, int32_t keys_per_item) {
+    if (!ctx) return SPIN_EINVAL;
+    if (keys_per_item < 32 || keys_per_item > spin::kMaxChunk || keys_per_item % 32)
+        return fail(ctx, SPIN_EINVAL, "keys per item must be a multiple of 32 in 32..1024");
+    ctx->chunk = keys_per_item;
+    return SPIN_OK;
+}
+
+int spin_required(spin_ctx* ctx, int64_t* req, int64_t* rows, int64_t* pages, int64_t* items, int64_t* part_slots) {
+    if (!ctx) return SPIN_EINVAL;
+    if (req) *req = ctx->need_req;
+    if (rows) *rows = ctx->need_rows;
+    if (pages) *pages = ctx->need_pages;
+    if (items) *items = ctx->need_items;
+    if (part_slots) *part_slots = ctx->need_slots;
+    return SPIN_OK;
+}
+
+int spin_reserve(spin_ctx* ctx, int64_t max_req, int64_t max_rows, int64_t max_pages, int64_t max_items,
+                 int64_t max_part_slots) {
+    if (!ctx) return SPIN_EINVAL;
+    if (max_req < 0 || max_rows < 0 || max_pages < 0 || max_items < 0 || max_part_slots < 0)
+        return fail(ctx, SPIN_EINVAL, "negative size");
+    max_req = std::max(max_req, ctx->cap_req);
+    max_rows = std::max(max_rows, ctx->cap_rows);
+    max_pages = std::max(max_pages, ctx->cap_pages);
+    max_items = std::max(max_items, ctx->cap_items);
+    max_part_slots = std::max(max_part_slots, ctx->cap_slots);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+    e = hipDeviceSynchronize();
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipDeviceSynchronize");
+    free_workspace(ctx);
+    for (int s = 0; s < kStages; ++s) ctx->ev_pending[s] = false;
+    ctx->cap_req = ctx->cap_rows = ctx->cap_pages = ctx->cap_items = ctx->cap_slots = 0;
+    const size_t blob = blob_size(max_req, max_rows, max_pages, max_items);
+    const int64_t stat_rows = 2 * max_rows + max_req + 1;
+#define SPIN_TRY(call)                                   \
+    do {                                                 \
+        e = (call);                                      \
+        if (e != hipSuccess) {                           \
+            free_workspace(ctx);                         \
+            return fail_hip(ctx, e, #call);              \
+        }                                                \
+    } while (0)
+    SPIN_TRY(hipMalloc((void**)&ctx->d_blob, blob));
+    SPIN_TRY(hipMalloc((void**)&ctx->d_part_o, std::max<size_t>(16, (size_t)max_part_slots * spin::kPartRow * 4)));
+    SPIN_TRY(hipMalloc((void**)&ctx->d_part_ml, std::max<size_t>(16, (size_t)max_part_slots * 2 * 4)));
+    SPIN_TRY(hipMalloc((void**)&ctx->d_row_max, (size_t)stat_rows * 4));
+    SPIN_TRY(hipMalloc((void**)&ctx->d_row_sum, (size_t)stat_rows * 8));
+    SPIN_TRY(hipMalloc((void**)&ctx->d_row_arg, (size_t)stat_rows * 4));
+    SPIN_TRY(hipMalloc((void**)&ctx->d_row_off, (size_t)(max_req + 1) * 4));
+    for (int s = 0; s < kStages; ++s) SPIN_TRY(hipHostMalloc((void**)&ctx->h_stage[s], blob, hipHostMallocDefault));
+#undef SPIN_TRY
+    ctx->blob_bytes = blob;
+    ctx->cap_req = max_req;
+    ctx->cap_rows = max_rows;
+    ctx->cap_pages = max_pages;
+    ctx->cap_items = max_items;
+    ctx->cap_slots = max_part_slots;
+    return SPIN_OK;
+}
+
+int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table, const spin_subreq* subs,
+                     int32_t n_sub, const void* q_dev, void* o_dev, int32_t n_q_heads, float softmax_scale,
+                     void* hip_stream) {
+    if (!ctx) return SPIN_EINVAL;
+    if (!kv || !table) return fail(ctx, SPIN_EINVAL, "kv descriptor or request table is null");
+    if (kv->dtype != SPIN_DTYPE_BF16) return fail(ctx, SPIN_EUNSUPPORTED, "only bf16 K/V is supported");
+    if (kv->head_dim != 64 && kv->head_dim != 128) return fail(ctx, SPIN_EUNSUPPORTED, "head_dim must be 64 or 128");
+    if (kv->page_size < 1 || (kv->page_size & (kv->page_size - 1)))
+        return fail(ctx, SPIN_EUNSUPPORTED, "page_size must be a power of two");
+    if (kv->n_kv_heads < 1 || n_q_heads < 1 || n_q_heads % kv->n_kv_heads)
+        return fail(ctx, SPIN_EINVAL, "n_q_heads must be a positive multiple of n_kv_heads");
+    const int group = n_q_heads / kv->n_kv_heads;
+    if (group > spin::kMaxTileRows) return fail(ctx, SPIN_EUNSUPPORTED, "more than 64 query heads per KV head");
+    if (kv->n_pages < 0 || kv->token_stride < kv->head_dim || kv->token_stride % 8 || kv->page_stride % 8 ||
+        kv->head_stride % 8 || kv->page_stride < 0 || kv->head_stride < 0)
+        return fail(ctx, SPIN_EINVAL, "bad K/V strides (must be non-negative multiples of 8 elements)");
+    std::string err;
+    int rc = spin::validate_table(table, kv->page_size, kv->n_pages, true, err);
+    if (rc) return fail(ctx, rc, err);
+    if (table->n_req == 0) return SPIN_OK;
+    if (!kv->k_pool || !kv->v_pool || !q_dev || !o_dev) return fail(ctx, SPIN_EINVAL, "null device pointer");
+    if (((uintptr_t)kv->k_pool | (uintptr_t)kv->v_pool | (uintptr_t)q_dev) & 15)
+        return fail(ctx, SPIN_EINVAL, "K/V pools and Q must be 16-byte aligned");
+    if (std::isnan(softmax_scale) || std::isinf(softmax_scale)) return fail(ctx, SPIN_EINVAL, "softmax_scale is not finite");
+    if (subs || n_sub != 0) {
+        rc = spin::check_tiling(table, subs, n_sub, err);
+        if (rc) return fail(ctx, rc, err);
+    }
+    rc = spin::build_plan(table, subs, n_sub, kv->page_size, group, n_q_heads, ctx->chunk, ctx->plan, err);
+    if (rc) return fail(ctx, rc, err);
+    const spin::Plan& plan = ctx->plan;
+    const int64_t n_req = table->n_req, n_rows = table->q_offset[n_req], n_pages_used = table->pt_offset[n_req];
+    const int64_t n_items = (int64_t)plan.items.size();
+    if (n_req > ctx->cap_req || n_rows > ctx->cap_rows || n_pages_used > ctx->cap_pages || n_items > ctx->cap_items ||
+        plan.part_slots > ctx->cap_slots) {
+        ctx->need_req = n_req;
+        ctx->need_rows = n_rows;
+        ctx->need_pages = n_pages_used;
+        ctx->need_items = n_items;
+        ctx->need_slots = plan.part_slots;
+        return fail(ctx, SPIN_ENOSPC, "reserved workspace too small for this batch (see spin_required)");
+    }
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    // ---- stage the tables: [items | order x3 | item_begin | row_req | page_table]
+    char* h = nullptr;
+    rc = next_stage(ctx, &h);
+    if (rc) return rc;
+    size_t off = 0;
+    const size_t off_items = off;
+    memcpy(h + off, plan.items.data(), n_items * sizeof(spin::Item));
+    off = align16(off + n_items * sizeof(spin::Item));
+    size_t off_order[3];
+    int32_t n_in_class[3];
+    for (int c = 0; c < 3; ++c) {
+        off_order[c] = off;
+        n_in_class[c] = (int32_t)plan.order[c].size();
+        memcpy(h + off, plan.order[c].data(), plan.order[c].size() * 4);
+        off = align16(off + plan.order[c].size() * 4);
+    }
+    const size_t off_begin = off;
+    memcpy(h + off, plan.item_begin.data(), (n_req + 1) * 4);
+    off = align16(off + (n_req + 1) * 4);
+    const size_t off_rowreq = off;
+    memcpy(h + off, plan.row_req.data(), n_rows * 4);
+    off = align16(off + n_rows * 4);
+    const size_t off_pt = off;
+    memcpy(h + off, table->page_table, n_pages_used * 4);
+    off = align16(off + n_pages_used * 4);
+    if (off > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
+    e = hipMemcpyAsync(ctx->d_blob, h, off, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync");
+    e = hipEventRecord(ctx->ev[ctx->stage], stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    ctx->ev_pending[ctx->stage] = true;
+
+    // ---- launch
+    int pshift = 0;
+    while ((1 << pshift) < kv->page_size) ++pshift;
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)kv->head_dim);
+    spin::AttnParams ap;
+    ap.k_pool = (const uint16_t*)kv->k_pool;
+    ap.v_pool = (const uint16_t*)kv->v_pool;
+    ap.q = (const uint16_t*)q_dev;
+    ap.items = (const spin::Item*)(ctx->d_blob + off_items);
+    ap.order = nullptr;
+    ap.page_table = (const int32_t*)(ctx->d_blob + off_pt);
+    ap.part_o = ctx->d_part_o;
+    ap.part_ml = ctx->d_part_ml;
+    ap.page_stride = kv->page_stride;
+    ap.head_stride = kv->head_stride;
+    ap.token_stride = kv->token_stride;
+    ap.n_q_heads = n_q_heads;
+    ap.n_kv_heads = kv->n_kv_heads;
+    ap.group = group;
+    ap.page_shift = pshift;
+    ap.scale_log2 = scale * 1.4426950408889634f;
+    const int32_t* order_dev[3];
+    for (int c = 0; c < 3; ++c) order_dev[c] = (const int32_t*)(ctx->d_blob + off_order[c]);
+    spin::JoinParams jp;
+    jp.items = ap.items;
+    jp.item_begin = (const int32_t*)(ctx->d_blob + off_begin);
+    jp.row_req = (const int32_t*)(ctx->d_blob + off_rowreq);
+    jp.part_o = ctx->d_part_o;
+    jp.part_ml = ctx->d_part_ml;
+    jp.o = (uint16_t*)o_dev;
+    jp.n_q_heads = n_q_heads;
+    jp.group = group;
+    jp.row_base = 0;
+    hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used);
+    if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    e = spin::launch_attn(kv->head_dim, ap, order_dev, n_in_class, jp, (int)n_rows, stream, pe ? pe[1] : nullptr);
+    if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
+    if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    return SPIN_OK;
+}
+
+int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft_len_host,
+                const int32_t* draft_tokens_dev, const float* target_logits_dev, const float* draft_logits_dev,
+                int32_t vocab, const double* u_accept_dev, const double* u_sample_dev, int32_t* n_accepted_dev,
+                int32_t* next_token_dev, void* hip_stream) {
+    if (!ctx) return SPIN_EINVAL;
+    if (mode != SPIN_ACCEPT_GREEDY && mode != SPIN_ACCEPT_REJECTION) return fail(ctx, SPIN_EINVAL, "unknown mode");
+    if (n_req < 0 || vocab < 1) return fail(ctx, SPIN_EINVAL, "n_req < 0 or vocab < 1");
+    if (n_req == 0) return SPIN_OK;
+    if (!draft_len_host) return fail(ctx, SPIN_EINVAL, "draft_len is null");
+    ctx->row_off_host.resize(n_req + 1);
+    int64_t rows = 0;
+    for (int32_t i = 0; i < n_req; ++i) {
+        if (draft_len_host[i] < 1) return fail(ctx, SPIN_EINVAL, "draft_len < 1");
+        ctx->row_off_host[i] = (int32_t)rows;
+        rows += draft_len_host[i];
+        if (rows > INT32_MAX / 2) return fail(ctx, SPIN_EINVAL, "too many draft rows");
+    }
+    ctx->row_off_host[n_req] = (int32_t)rows;
+    if (!draft_tokens_dev || !target_logits_dev || !n_accepted_dev || !next_token_dev)
+        return fail(ctx, SPIN_EINVAL, "null device pointer");
+    if (mode == SPIN_ACCEPT_REJECTION && (!draft_logits_dev || !u_accept_dev || !u_sample_dev))
+        return fail(ctx, SPIN_EINVAL, "rejection mode needs draft logits and both uniform arrays");
+    if (n_req > ctx->cap_req || rows > ctx->cap_rows) {
+        ctx->need_req = std::max<int64_t>(n_req, ctx->cap_req);
+        ctx->need_rows = std::max<int64_t>(rows, ctx->cap_rows);
+        ctx->need_pages = ctx->cap_pages;
+        ctx->need_items = ctx->cap_items;
+        ctx->need_slots = ctx->cap_slots;
+        return fail(ctx, SPIN_ENOSPC, "reserved workspace too small for this batch (see spin_required)");
+    }
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    char* h = nullptr;
+    int rc = next_stage(ctx, &h);
+    if (rc) return rc;
+    memcpy(h, ctx->row_off_host.data(), (size_t)(n_req + 1) * 4);
+    e = hipMemcpyAsync(ctx->d_row_off, h, (size_t)(n_req + 1) * 4, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync");
+    e = hipEventRecord(ctx->ev[ctx->stage], stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    ctx->ev_pending[ctx->stage] = true;
+
+    spin::AcceptParams p;
+    p.row_off = ctx->d_row_off;
+    p.draft_tokens = draft_tokens_dev;
+    p.target_logits = target_logits_dev;
+    p.draft_logits = draft_logits_dev;
+    p.u_accept = u_accept_dev;
+    p.u_sample = u_sample_dev;
+    p.row_max = ctx->d_row_max;
+    p.row_sum = ctx->d_row_sum;
+    p.row_arg = ctx->d_row_arg;
+    p.n_accepted = n_accepted_dev;
+    p.next_token = next_token_dev;
+    p.n_req = n_req;
+    p.n_rows = (int32_t)rows;
+    p.vocab = vocab;
+    p.mode = mode;
+    hipEvent_t* pe = prof_slot(ctx, ctx->prof_accept, ctx->prof_accept_used);
+    if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    e = spin::launch_accept(p, stream, pe ? pe[1] : nullptr);
+    if (e != hipSuccess) return fail_hip(ctx, e, "acceptance launch");
+    if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    return SPIN_OK;
+}
+
+int spin_profile_begin(spin_ctx* ctx, int32_t max_calls) {
+    if (!ctx || max_calls < 0) return SPIN_EINVAL;
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+    free_profile(ctx);
+    for (int k = 0; k < 2; ++k) {
+        std::vector<hipEvent_t>& pool = k ? ctx->prof_accept : ctx->prof_attn;
+        for (int64_t i = 0; i < (int64_t)max_calls * 3; ++i) {
+            hipEvent_t ev;
+            e = hipEventCreate(&ev);
+            if (e != hipSuccess) {
+                free_profile(ctx);
+                return fail_hip(ctx, e, "hipEventCreate");
+            }
+            pool.push_back(ev);
+        }
+    }
+    ctx->prof_on = true;
+    return SPIN_OK;
+}
+
+int spin_profile_end(spin_ctx* ctx, double ms[4], int32_t calls[2]) {
+    if (!ctx || !ms || !calls) return SPIN_EINVAL;
+    for (int k = 0; k < 4; ++k) ms[k] = 0.0;
+    calls[0] = ctx->prof_attn_used;
+    calls[1] = ctx->prof_accept_used;
+    int rc = SPIN_OK;
+    for (int k = 0; k < 2 && rc == SPIN_OK; ++k) {
+        std::vector<hipEvent_t>& pool = k ? ctx->prof_accept : ctx->prof_attn;
+        const int used = k ? ctx->prof_accept_used : ctx->prof_attn_used;
+        for (int i = 0; i < used; ++i) {
+            hipEvent_t* p = pool.data() + (size_t)i * 3;
+            hipError_t e = hipEventSynchronize(p[2]);
+            float a = 0.f, b = 0.f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&a, p[0], p[1]);
+            if (e == hipSuccess) e = hipEventElapsedTime(&b, p[1], p[2]);
+            if (e != hipSuccess) { rc = fail_hip(ctx, e, "reading profile events"); break; }
+            ms[2 * k] += a;
+            ms[2 * k + 1] += b;
+        }
+    }
+    free_profile(ctx);
+    return rc;
+}
+
+}  // extern "C"

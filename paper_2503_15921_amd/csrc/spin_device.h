@@ -1,0 +1,65 @@
+// Kernel parameter blocks and launch entry points shared by the HIP translation units of
+// libspin.  Internal; the C ABI is include/spin.h.
+#ifndef SPIN_DEVICE_H
+#define SPIN_DEVICE_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "spin_internal.h"
+
+namespace spin {
+
+// Floats per partial output row: 8 (head dim within a 16-byte chunk) x 16 (chunk), whatever
+// the head dim; head dim 64 uses the first 8 chunks.
+constexpr int kPartRow = 128;
+
+struct AttnParams {
+    const uint16_t* k_pool;
+    const uint16_t* v_pool;
+    const uint16_t* q;
+    const Item* items;
+    const int32_t* order;
+    const int32_t* page_table;
+    float* part_o;     // [slots][kPartRow]
+    float* part_ml;    // [slots][2]: running max (log2 domain), sum
+    int64_t page_stride, head_stride, token_stride;   // elements
+    int32_t n_q_heads, n_kv_heads, group, page_shift;
+    float scale_log2;  // softmax scale * log2(e)
+};
+
+struct JoinParams {
+    const Item* items;
+    const int32_t* item_begin;
+    const int32_t* row_req;
+    const float* part_o;
+    const float* part_ml;
+    uint16_t* o;
+    int32_t n_q_heads, group, row_base;
+};
+
+// ev_mid (may be null) is recorded between the attention kernels and the join kernel.
+hipError_t launch_attn(int head_dim, const AttnParams& base, const int32_t* const order_dev[3],
+                       const int32_t n_in_class[3], const JoinParams& jp, int n_rows, hipStream_t stream,
+                       hipEvent_t ev_mid);
+
+struct AcceptParams {
+    const int32_t* row_off;        // [n_req+1] first draft row of each request (device)
+    const int32_t* draft_tokens;   // [R]
+    const float* target_logits;    // [R+n_req][V]
+    const float* draft_logits;     // [R][V] or null
+    const double* u_accept;        // [R]
+    const double* u_sample;        // [n_req]
+    float* row_max;                // [2R+n_req] target rows first, then draft rows
+    double* row_sum;
+    int32_t* row_arg;
+    int32_t* n_accepted;
+    int32_t* next_token;
+    int32_t n_req, n_rows, vocab, mode;
+};
+
+// ev_mid (may be null) is recorded between the two kernels.
+hipError_t launch_accept(const AcceptParams& p, hipStream_t stream, hipEvent_t ev_mid);
+
+}  // namespace spin
+#endif

@@ -1,0 +1,167 @@
+"""CPU-only tests of libspin's host side: the library loads and exports what include/spin.h declares,
+spin_decompose / spin_kv_padding agree with the oracle, spin_check_tiling accepts exactly the exact
+tilings, the scheduler's work items tile every request once, and error codes come back as documented.
+No GPU call is made here."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2503_15921_amd as spin
+from oracle import spin_oracle as orc
+from test_oracle_decompose import assert_exact_tiling
+from test_oracle_attention import random_rectangles
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "spin.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(spin_[a-z_]+)\s*\(", header))
+    assert {"spin_verify_attn", "spin_decompose", "spin_accept"} <= declared
+    lib = spin.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    from paper_2503_15921_amd.binding import EXPORTS
+    assert declared == set(EXPORTS)
+
+
+def test_strerror():
+    lib = spin.load_library()
+    assert lib.spin_strerror(0) == b"ok"
+    for code in (spin.EINVAL, spin.ETABLE, spin.ENOSPC, spin.EUNSUPPORTED, spin.EHIP):
+        assert len(lib.spin_strerror(code)) > 3
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_decompose_matches_oracle(seed):
+    rng = np.random.default_rng(seed)
+    B = int(rng.integers(1, 20))
+    prefix = rng.integers(0, 500, size=B); draft = rng.integers(1, 17, size=B)
+    for w in (1, 3, 4, 16):
+        got, _ = spin.decompose(prefix, draft, spin.DECOMP_Q_SPLIT, q_width=w)
+        np.testing.assert_array_equal(got, orc.decompose_q_split(prefix, draft, w))
+    for L in (1, 16, 37, 128, 4096):
+        got, Lout = spin.decompose(prefix, draft, spin.DECOMP_KV_SPLIT, kv_len=L)
+        np.testing.assert_array_equal(got, orc.decompose_kv_split(prefix, draft, L))
+        assert Lout == L
+        assert spin.kv_padding(prefix, draft, L) == orc.kv_padding(prefix, draft, L)
+    got, _ = spin.decompose(prefix, draft, spin.DECOMP_NONE)
+    np.testing.assert_array_equal(got, orc.decompose_kv_split(prefix, draft, 1 << 20))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_kv_search_matches_oracle(seed):
+    rng = np.random.default_rng(50 + seed)
+    B = int(rng.integers(1, 16))
+    prefix = rng.integers(0, 400, size=B); draft = rng.integers(1, 9, size=B)
+    step = int(rng.choice([1, 16]))
+    l_min, l_max = int(rng.integers(1, 64)), int((prefix + draft).max())
+    for max_rows in (B, B + 2, 4 * B):
+        want = orc.search_kv_length(prefix, draft, max_rows, l_min, l_max, step)
+        if want is None:
+            with pytest.raises(spin.SpinError) as e:
+                spin.decompose(prefix, draft, spin.DECOMP_KV_SEARCH, max_subreq=max_rows, l_min=l_min,
+                               l_max=l_max, l_step=step)
+            assert e.value.code == spin.ENOSPC
+        else:
+            got, L = spin.decompose(prefix, draft, spin.DECOMP_KV_SEARCH, max_subreq=max_rows, l_min=l_min,
+                                    l_max=l_max, l_step=step)
+            assert L == want
+            np.testing.assert_array_equal(got, orc.decompose_kv_split(prefix, draft, want))
+            assert len(got) <= max_rows
+
+
+def test_decompose_capacity_protocol():
+    prefix = np.array([10, 20]); draft = np.array([8, 3])
+    with pytest.raises(spin.SpinError) as e:
+        spin.decompose(prefix, draft, spin.DECOMP_Q_SPLIT, q_width=2, cap=3)
+    assert e.value.code == spin.ENOSPC
+    got, _ = spin.decompose(prefix, draft, spin.DECOMP_Q_SPLIT, q_width=2, cap=6)
+    assert len(got) == 6
+
+
+def test_decompose_rejects_bad_input():
+    for kwargs in (dict(policy=spin.DECOMP_Q_SPLIT, q_width=0), dict(policy=spin.DECOMP_KV_SPLIT, kv_len=0),
+                   dict(policy=99), dict(policy=spin.DECOMP_KV_SEARCH, max_subreq=0, l_min=1, l_max=4)):
+        with pytest.raises(spin.SpinError) as e:
+            spin.decompose(np.array([4]), np.array([2]), **kwargs)
+        assert e.value.code == spin.EINVAL
+    with pytest.raises(spin.SpinError) as e:
+        spin.decompose(np.array([4]), np.array([0]), spin.DECOMP_NONE)       # draft length < 1
+    assert e.value.code == spin.EINVAL
+    with pytest.raises(spin.SpinError):
+        spin.decompose(np.array([-1]), np.array([1]), spin.DECOMP_NONE)
+
+
+def test_check_tiling_accepts_exact_and_rejects_broken():
+    rng = np.random.default_rng(3)
+    prefix = rng.integers(0, 30, size=5); draft = rng.integers(1, 7, size=5)
+    good = [orc.decompose_q_split(prefix, draft, 2), orc.decompose_kv_split(prefix, draft, 7),
+            np.array([(i,) + r for i in range(5) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))])]
+    for subs in good:
+        assert_exact_tiling(prefix, draft, subs)
+        assert spin.check_tiling(prefix, draft, subs) == 0
+        # order must not matter
+        assert spin.check_tiling(prefix, draft, subs[rng.permutation(len(subs))]) == 0
+        # drop one piece -> a hole; duplicate one -> an overlap
+        assert spin.check_tiling(prefix, draft, subs[1:]) == spin.ETABLE
+        assert spin.check_tiling(prefix, draft, np.concatenate([subs, subs[:1]])) == spin.ETABLE
+    bad = good[1].copy(); bad[0, 4] += 1000                      # sticks out of its parent
+    assert spin.check_tiling(prefix, draft, bad) == spin.ETABLE
+    bad = good[1].copy(); bad[0, 0] = 77                         # unknown parent
+    assert spin.check_tiling(prefix, draft, bad) == spin.ETABLE
+    # a piece wholly beyond the causal edge is legal and covers nothing
+    p, g = 4, 3
+    subs = np.array([[0, 0, 3, 0, 7], ])
+    assert spin.check_tiling([p], [g], subs) == 0
+    subs = np.array([[0, 0, 1, 0, 5], [0, 1, 2, 0, 7], [0, 0, 1, 5, 2]])   # last one: row 0, keys 5..6 -> invisible
+    assert spin.check_tiling([p], [g], subs) == 0
+
+
+@pytest.mark.parametrize("group,chunk,page", [(1, 64, 16), (1, 256, 16), (8, 256, 16), (4, 32, 4), (1, 1024, 1)])
+def test_scheduler_items_tile_every_request(group, chunk, page):
+    rng = np.random.default_rng(group * 1000 + chunk)
+    prefix = rng.integers(0, 700, size=7); draft = rng.integers(1, 17, size=7)
+    decomps = [None, orc.decompose_q_split(prefix, draft, 4), orc.decompose_kv_split(prefix, draft, 100),
+               np.array([(i,) + r for i in range(7) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))])]
+    for subs in decomps:
+        items = spin.schedule(prefix, draft, subs, page, group, chunk)
+        assert_exact_tiling(prefix, draft, items)
+        for parent, qb, ql, kb, kl in items:
+            assert ql * group <= 64
+            assert 1 <= kl <= chunk
+            assert (kb + kl - 1) // page - kb // page + 1 <= 72
+            assert kb // chunk == (kb + kl - 1) // chunk or kl <= chunk    # never longer than one chunk
+        # parent-sorted: the join kernel walks a contiguous range per request
+        assert list(items[:, 0]) == sorted(items[:, 0])
+
+
+def test_scheduler_rejoins_row_bands_sharing_a_prefix():
+    # width-4 pieces of a 16-row draft block all start at key 0: they are streamed as one band, so
+    # the item count equals that of the undivided request
+    prefix = np.array([1000, 300]); draft = np.array([16, 2])
+    whole = spin.schedule(prefix, draft, None, 16, 1, 256)
+    split = spin.schedule(prefix, draft, orc.decompose_q_split(prefix, draft, 4), 16, 1, 256)
+    np.testing.assert_array_equal(whole, split)
+    kv = spin.schedule(prefix, draft, orc.decompose_kv_split(prefix, draft, 100), 16, 1, 256)
+    np.testing.assert_array_equal(whole, kv)
+
+
+def test_scheduler_rejects_inexact_tiling():
+    prefix = np.array([40]); draft = np.array([4])
+    subs = orc.decompose_kv_split(prefix, draft, 16)[:-1]
+    with pytest.raises(spin.SpinError) as e:
+        spin.schedule(prefix, draft, subs, 16, 1, 256)
+    assert e.value.code == spin.ETABLE
+
+
+def test_create_without_gpu_reports_hip_error():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible")
+    with pytest.raises(spin.SpinError) as e:
+        spin.SpinContext(0)
+    assert e.value.code == spin.EHIP
