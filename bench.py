@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--seed", type=int, default=3)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="instead of the step, run a plain 1 GiB device copy per step (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (use --gpus 1)", file=sys.stderr)
@@ -92,6 +94,16 @@ def main():
 
     cfg = si.CONFIGS[args.config]
     dev = "cuda:0"
+    if args.calib_copy:
+        # known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE: each step reads 1 GiB and writes 1 GiB
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.warmup + args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calib_copy_bytes_read_per_step": 1 << 30, "calib_copy_bytes_written_per_step": 1 << 30,
+                          "steps": args.warmup + args.steps}))
+        return
     batch = si.make_verify_batch(cfg, args.seed, device=dev)
     t = batch.table
     ab = si.make_accept_batch(t.draft_len, cfg.vocab, cfg.logit_sigma, args.seed, device=dev)
