@@ -134,9 +134,9 @@ const char* spin_strerror(int code);
 /* Copy the text of the context's last error into buf (NUL-terminated, truncated to n). */
 int spin_last_error(spin_ctx* ctx, char* buf, size_t n);
 
-/* KV chunk length of the scheduler (keys per work item, multiple of 32; default 256).  Work
- * items longer than this are cut so that the chip is filled evenly (the same split-and-rejoin
- * as Eq. (13), used as a scheduler). */
+/* KV chunk length of the scheduler (keys per work item: a multiple of 32 in 32..2048, or 0 for
+ * the default of 1024).  Key ranges longer than this are cut so that the chip is filled evenly
+ * (the same split-and-rejoin as Eq. (13), used as a scheduler). */
 int spin_set_chunk(spin_ctx* ctx, int32_t keys_per_item);
 
 /* ---- decomposition (host only, no GPU needed) -------------------------------------------- */
@@ -199,7 +199,8 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
  * next token = arg-max of target row n.  REJECTION: with p, q the softmax of the target / draft
  * row, token d_t is kept iff u_t*q(d_t) < p(d_t); on the first rejection the next token is the
  * smallest k with sum_{x<=k} max(0,p-q)(x) > u'*Z (from p itself if Z = 0), otherwise the same
- * inverse CDF on the bonus row's p. */
+ * inverse CDF on the bonus row's p.  A draft token id outside [0, vocab) is never kept.
+ * Errors: SPIN_EINVAL, SPIN_EUNSUPPORTED (vocab > 1048576), SPIN_ENOSPC (reserve more), SPIN_EHIP. */
 int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft_len_host,
                 const int32_t* draft_tokens_dev, const float* target_logits_dev,
                 const float* draft_logits_dev, int32_t vocab, const double* u_accept_dev,

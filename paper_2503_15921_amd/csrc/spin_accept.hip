@@ -18,7 +18,8 @@
 namespace spin {
 
 constexpr int kStatThreads = 256;
-constexpr int kFinishThreads = 256;
+constexpr int kFinishThreads = 1024;
+constexpr int kMaxRuns = 4096;   // (step, wavefront) runs of 256 ids kept in LDS: vocabularies up to 1M ids
 
 struct MaxArg {
     float v;
@@ -96,108 +97,209 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(AcceptParams P)
 }
 
 __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptParams P) {
+    constexpr int kWaves = kFinishThreads / 64;
     __shared__ int s_n;
-    __shared__ double s_scan[kFinishThreads];
-    __shared__ int s_last[kFinishThreads];
-    __shared__ int s_hit;
+    __shared__ double s_run[kMaxRuns];
+    __shared__ int s_last[kWaves];
+    __shared__ double s_total, s_before;
+    __shared__ int s_cross;
     const int req = blockIdx.x;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r0 = P.row_off[req];
     const int g = P.row_off[req + 1] - r0;
     const int base = r0 + req;                  // first target row of the request
     const int n_target = P.n_rows + P.n_req;
     const int V = P.vocab;
 
-    if (tid == 0) {
-        int n = 0;
-        for (; n < g; ++n) {
-            const int d = P.draft_tokens[r0 + n];
-            if (d < 0 || d >= V) break;         // a token outside the vocabulary is never kept
-            if (P.mode == SPIN_ACCEPT_GREEDY) {
-                if (d != P.row_arg[base + n]) break;
-            } else {
-                const double p = exp((double)P.target_logits[(int64_t)(base + n) * V + d] - (double)P.row_max[base + n]) /
-                                 P.row_sum[base + n];
-                const int dr = n_target + r0 + n;
-                const double q = exp((double)P.draft_logits[(int64_t)(r0 + n) * V + d] - (double)P.row_max[dr]) /
-                                 P.row_sum[dr];
-                if (!(P.u_accept[r0 + n] * q < p)) break;
+    // ---- first-reject scan: wavefront 0 tests 64 draft rows at a time, one per lane
+    if (wave == 0) {
+        int n = g;
+        for (int t0 = 0; t0 < g; t0 += 64) {
+            const int t = t0 + lane;
+            bool keep = true;
+            if (t < g) {
+                const int d = P.draft_tokens[r0 + t];
+                if (d < 0 || d >= V) {
+                    keep = false;               // a token outside the vocabulary is never kept
+                } else if (P.mode == SPIN_ACCEPT_GREEDY) {
+                    keep = d == P.row_arg[base + t];
+                } else {
+                    const double p = exp((double)P.target_logits[(int64_t)(base + t) * V + d] - (double)P.row_max[base + t]) /
+                                     P.row_sum[base + t];
+                    const int dr = n_target + r0 + t;
+                    const double q = exp((double)P.draft_logits[(int64_t)(r0 + t) * V + d] - (double)P.row_max[dr]) /
+                                     P.row_sum[dr];
+                    keep = P.u_accept[r0 + t] * q < p;
+                }
+            }
+            const unsigned long long rejected = __ballot(!keep);
+            if (rejected) {
+                n = t0 + __ffsll((long long)rejected) - 1;
+                break;
             }
         }
-        s_n = n;
-        P.n_accepted[req] = n;
-        if (P.mode == SPIN_ACCEPT_GREEDY) P.next_token[req] = P.row_arg[base + n];
+        if (lane == 0) {
+            s_n = n;
+            P.n_accepted[req] = n;
+            if (P.mode == SPIN_ACCEPT_GREEDY) P.next_token[req] = P.row_arg[base + n];
+        }
     }
     __syncthreads();
     if (P.mode == SPIN_ACCEPT_GREEDY) return;
 
+    // ---- next token: inverse CDF over the residual max(0, p - q), or over the bonus row's p.
+    // The vocabulary is walked in steps of 4 * kFinishThreads ids; in a step thread t owns the four
+    // ids step*4T + 4t .. +3 (16-byte loads, consecutive lanes read consecutive memory), so wavefront
+    // w owns a contiguous run of 256 ids.  Pass 1 leaves the mass of every (step, wavefront) run in
+    // LDS; a scan over those finds the run that holds u' * Z; its wavefront recomputes the run and
+    // scans inside it.
     const int n = s_n;
     const float* tl = P.target_logits + (int64_t)(base + n) * V;
-    const double tmax = (double)P.row_max[base + n], tsum = P.row_sum[base + n];
+    const double tmax = (double)P.row_max[base + n], tinv = 1.0 / P.row_sum[base + n];
     const bool residual = n < g;
-    const float* dl = residual ? P.draft_logits + (int64_t)(r0 + n) * V : nullptr;
+    const float* dl = residual ? P.draft_logits + (int64_t)(r0 + n) * V : tl;
     const double dmax = residual ? (double)P.row_max[n_target + r0 + n] : 0.0;
-    const double dsum = residual ? P.row_sum[n_target + r0 + n] : 1.0;
+    const double dinv = residual ? 1.0 / P.row_sum[n_target + r0 + n] : 1.0;
+    const bool vec = (V % 4 == 0) && (((reinterpret_cast<uintptr_t>(tl) | reinterpret_cast<uintptr_t>(dl)) & 15) == 0);
+    const int n_steps = (V + 4 * kFinishThreads - 1) / (4 * kFinishThreads);
+    const int n_runs = n_steps * kWaves;
 
-    // thread t owns the contiguous id range [lo, hi)
-    const int per = (V + kFinishThreads - 1) / kFinishThreads;
-    const int lo = min(V, tid * per), hi = min(V, lo + per);
     bool use_residual = residual;
     for (int attempt = 0; attempt < 2; ++attempt) {
-        auto mass = [&](int x) -> double {
-            const double p = exp((double)tl[x] - tmax) / tsum;
-            if (!use_residual) return p;
-            const double q = exp((double)dl[x] - dmax) / dsum;
-            const double r = p - q;
-            return r > 0.0 ? r : 0.0;
+        // masses of the four ids starting at x0 (zero beyond the vocabulary)
+        auto mass4 = [&](int x0, double m[4]) {
+            float a[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, b[4] = {0.f, 0.f, 0.f, 0.f};
+            if (vec && x0 + 3 < V) {
+                const float4 va = *reinterpret_cast<const float4*>(tl + x0);
+                a[0] = va.x; a[1] = va.y; a[2] = va.z; a[3] = va.w;
+                if (use_residual) {
+                    const float4 vb = *reinterpret_cast<const float4*>(dl + x0);
+                    b[0] = vb.x; b[1] = vb.y; b[2] = vb.z; b[3] = vb.w;
+                }
+            } else {
+                for (int j = 0; j < 4; ++j)
+                    if (x0 + j < V) {
+                        a[j] = tl[x0 + j];
+                        if (use_residual) b[j] = dl[x0 + j];
+                    }
+            }
+            for (int j = 0; j < 4; ++j) {
+                double v = 0.0;
+                if (x0 + j < V) {
+                    v = exp((double)a[j] - tmax) * tinv;
+                    if (use_residual) {
+                        v -= exp((double)b[j] - dmax) * dinv;
+                        v = v > 0.0 ? v : 0.0;
+                    }
+                }
+                m[j] = v;
+            }
         };
-        double seg = 0.0;
         int last = -1;
-        for (int x = lo; x < hi; ++x) {
-            const double m = mass(x);
-            seg += m;
-            if (m > 0.0) last = x;
+        for (int st = 0; st < n_steps; ++st) {
+            const int x0 = st * 4 * kFinishThreads + 4 * tid;
+            double m[4];
+            mass4(x0, m);
+            double run = (m[0] + m[1]) + (m[2] + m[3]);
+            for (int j = 0; j < 4; ++j)
+                if (m[j] > 0.0) last = x0 + j;
+            for (int off = 32; off > 0; off >>= 1) run += __shfl_xor(run, off);
+            if (lane == 0) s_run[st * kWaves + wave] = run;
         }
-        s_scan[tid] = seg;
-        s_last[tid] = last;
-        if (tid == 0) s_hit = -1;
+        for (int off = 32; off > 0; off >>= 1) last = max(last, __shfl_xor(last, off));
+        if (lane == 0) s_last[wave] = last;
         __syncthreads();
-        // inclusive scan over the 256 segment sums (Hillis-Steele, float64)
-        for (int off = 1; off < kFinishThreads; off <<= 1) {
-            const double add = tid >= off ? s_scan[tid - off] : 0.0;
-            __syncthreads();
-            s_scan[tid] += add;
-            __syncthreads();
+        // wavefront 0 scans the run masses in id order: lane L takes a contiguous slice of them
+        if (wave == 0) {
+            const int per = (n_runs + 63) / 64;
+            const int lo = min(n_runs, lane * per), hi = min(n_runs, lo + per);
+            double mine = 0.0;
+            for (int k = lo; k < hi; ++k) mine += s_run[k];
+            double incl = mine;
+            for (int off = 1; off < 64; off <<= 1) {
+                const double up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            const double total = __shfl(incl, 63);
+            const double thr = P.u_sample[req] * total;
+            double excl = __shfl_up(incl, 1);
+            if (lane == 0) excl = 0.0;
+            if (lane == 0) {
+                s_total = total;
+                s_cross = -1;
+            }
+            // exactly the lanes where the running sum first passes the threshold look inside their slice
+            if (incl > thr && !(excl > thr)) {
+                double run = excl;
+                int k = lo;
+                for (; k < hi; ++k) {
+                    if (run + s_run[k] > thr) break;
+                    run += s_run[k];
+                }
+                if (k == hi) k = hi - 1;             // summation orders may differ in the last bit
+                // several lanes can only get here when the sums are not monotone by rounding: lowest wins
+                const unsigned long long who = __ballot(1);
+                if (lane == __ffsll((long long)who) - 1) {
+                    s_cross = k;
+                    s_before = run;
+                }
+            }
         }
-        const double total = s_scan[kFinishThreads - 1];
+        __syncthreads();
+        const double total = s_total;
         if (use_residual && !(total > 0.0)) {   // p == q up to rounding: draw from p instead
             use_residual = false;
             __syncthreads();
             continue;
         }
-        const double thr = P.u_sample[req] * total;
-        const double incl = s_scan[tid];
-        const double excl = tid > 0 ? s_scan[tid - 1] : 0.0;
-        // the first segment whose inclusive sum passes the threshold holds the answer
-        if (incl > thr && !(excl > thr)) {
-            double run = excl;
-            int k = -1;
-            for (int x = lo; x < hi; ++x) {
-                run += mass(x);
-                if (run > thr) { k = x; break; }
+        const int cross = s_cross;
+        if (cross < 0) {                         // u'*Z at or beyond the total: last id with mass
+            if (tid == 0) {
+                int k = -1;
+                for (int w = 0; w < kWaves; ++w) k = max(k, s_last[w]);
+                P.next_token[req] = k >= 0 ? k : V - 1;
             }
-            // run may fall short of incl by rounding of the two summation orders
-            if (k < 0) k = last >= 0 ? last : hi - 1;
-            s_hit = k;
+            break;
         }
-        __syncthreads();
-        if (tid == 0) {
-            int k = s_hit;
-            if (k < 0) {                         // u'*Z at or beyond the total: last id with mass
-                for (int t = kFinishThreads - 1; t >= 0 && k < 0; --t) k = s_last[t];
-                if (k < 0) k = V - 1;
+        if (wave == cross % kWaves) {
+            const int x0 = (cross / kWaves) * 4 * kFinishThreads + 4 * tid;
+            const double thr = P.u_sample[req] * total;
+            double m[4];
+            mass4(x0, m);
+            const double mine = (m[0] + m[1]) + (m[2] + m[3]);
+            double incl = mine;
+            for (int off = 1; off < 64; off <<= 1) {
+                const double up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
             }
-            P.next_token[req] = k;
+            incl += s_before;
+            double excl = __shfl_up(incl, 1);
+            if (lane == 0) excl = s_before;
+            const bool hit = incl > thr && !(excl > thr);
+            int k = 0x7fffffff;
+            if (hit) {
+                double run = excl;
+                k = -1;
+                for (int j = 0; j < 4; ++j) {
+                    run += m[j];
+                    if (run > thr) { k = x0 + j; break; }
+                }
+                if (k < 0)
+                    for (int j = 3; j >= 0 && k < 0; --j)
+                        if (m[j] > 0.0) k = x0 + j;
+                if (k < 0) k = min(x0, V - 1);
+            }
+            const unsigned long long who = __ballot(hit);
+            if (who) {
+                if (lane == __ffsll((long long)who) - 1) P.next_token[req] = k;
+            } else {
+                // the recomputed run fell short of its first sum by rounding: its last id with mass
+                int lastpos = -1;
+                for (int j = 0; j < 4; ++j)
+                    if (m[j] > 0.0) lastpos = x0 + j;
+                for (int off = 32; off > 0; off >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, off));
+                if (lane == 0) P.next_token[req] = lastpos >= 0 ? lastpos : min(x0, V - 1);
+            }
         }
         break;
     }

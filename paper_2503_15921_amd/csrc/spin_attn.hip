@@ -129,7 +129,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
             *(u32x4*)&sK[(f / DCH) * LROW + (f % DCH) * 8] = Kr[i];
         }
         __syncthreads();
-        if (kb + 32 < k1) load_k(kb + 32);
+        load_k(kb + 32);   // past the item's end this re-reads its last key row (clamped): harmless
 
         // ---- S^T = K Q^T
         f32x4 S[2][NT];
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
             for (int kp = 0; kp < 4; ++kp)
                 Vt[jd][kp] = __builtin_amdgcn_perm(Vr[2 * kp + 1][jd >> 1], Vr[2 * kp][jd >> 1], sel);
         }
-        if (kb + 32 < k1) load_v(kb + 32);
+        load_v(kb + 32);
 #pragma unroll
         for (int jd = 0; jd < 8; ++jd) {
             const bf16x8 a = __builtin_bit_cast(bf16x8, Vt[jd]);
@@ -227,37 +227,45 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 // Join the pieces of one (packed row, query head): Eq. (13) -- one denominator over all tokens
 // of the original request.  With piece s holding (m_s, l_s, N_s) where l_s = sum of exp2(score -
 // m_s) and N_s the matching weighted value sum:  O = sum_s 2^(m_s-M) N_s / sum_s 2^(m_s-M) l_s.
+// One wavefront per (row, head); lane (chunk, jp) owns head dims chunk*8 + 2*jp and +1, which the
+// attention kernel left at partial elements (2*jp)*16 + chunk and (2*jp+1)*16 + chunk.
+constexpr int kJoinWaves = 4;
+
 template <int D>
-__global__ __launch_bounds__(D) void join_partials_kernel(JoinParams P) {
-    const int h = blockIdx.x, r = blockIdx.y + P.row_base;
-    const int dim = threadIdx.x;
+__global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinParams P) {
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * kJoinWaves + (threadIdx.x >> 6);
+    if (w >= (int64_t)P.n_rows * P.n_q_heads) return;
+    const int r = (int)(w / P.n_q_heads), h = (int)(w - (int64_t)r * P.n_q_heads);
     const int G = P.group;
     const int kvh = h / G, hg = h - kvh * G;
     const int req = P.row_req[r];
     const int kb = P.item_begin[req], ke = P.item_begin[req + 1];
-    const int e = (dim & 7) * 16 + (dim >> 3);   // where the attention kernel put this head dim
+    const int chunk = lane & 15, jp = lane >> 4;
+    const int e0 = (2 * jp) * 16 + chunk;
+    const bool active = chunk * 8 < D;
 
-    float M = kNegBig;
+    float M = kNegBig, den = 0.f, n0 = 0.f, n1 = 0.f;
+#pragma unroll 4
     for (int k = kb; k < ke; ++k) {
         const Item it = P.items[k];
         const int tl = r - it.q_row0;
         if (tl < 0 || tl >= it.n_q) continue;
         const int64_t slot = (int64_t)it.part_base + (int64_t)kvh * (it.n_q * G) + tl * G + hg;
-        M = fmaxf(M, P.part_ml[slot * 2]);
+        const float m = P.part_ml[slot * 2], l = P.part_ml[slot * 2 + 1];
+        const float o0 = P.part_o[slot * kPartRow + e0], o1 = P.part_o[slot * kPartRow + e0 + 16];
+        const float Mn = fmaxf(M, m);
+        const float a = fast_exp2(M - Mn), b = fast_exp2(m - Mn);
+        den = den * a + l * b;
+        n0 = n0 * a + o0 * b;
+        n1 = n1 * a + o1 * b;
+        M = Mn;
     }
-    float num = 0.f, den = 0.f;
-    for (int k = kb; k < ke; ++k) {
-        const Item it = P.items[k];
-        const int tl = r - it.q_row0;
-        if (tl < 0 || tl >= it.n_q) continue;
-        const int64_t slot = (int64_t)it.part_base + (int64_t)kvh * (it.n_q * G) + tl * G + hg;
-        const float w = fast_exp2(P.part_ml[slot * 2] - M);
-        den += w * P.part_ml[slot * 2 + 1];
-        num += w * P.part_o[slot * kPartRow + e];
+    if (active) {
+        const float inv = 1.0f / den;
+        uint32_t* op = reinterpret_cast<uint32_t*>(P.o + ((int64_t)r * P.n_q_heads + h) * D + chunk * 8 + 2 * jp);
+        *op = pack_bf16(n0 * inv, n1 * inv);
     }
-    const float o = num / den;
-    const bf16x2 ob = {(__bf16)o, (__bf16)0.f};
-    P.o[((int64_t)r * P.n_q_heads + h) * D + dim] = (uint16_t)(__builtin_bit_cast(uint32_t, ob) & 0xffffu);
 }
 
 template <int D>
@@ -281,16 +289,11 @@ static hipError_t launch_attn_d(const AttnParams& base, const int32_t* const ord
         if (e != hipSuccess) return e;
     }
     if (n_rows > 0) {
-        // grid.y carries the packed row; slice it if a batch ever has more rows than a grid allows
-        for (int r0 = 0; r0 < n_rows; r0 += 65535) {
-            JoinParams q = jp;
-            const int nr = n_rows - r0 < 65535 ? n_rows - r0 : 65535;
-            q.row_base = r0;
-            dim3 grid(jp.n_q_heads, nr), block(D);
-            hipLaunchKernelGGL((join_partials_kernel<D>), grid, block, 0, stream, q);
-            hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return e;
-        }
+        const int64_t waves = (int64_t)n_rows * jp.n_q_heads;
+        dim3 grid((unsigned)((waves + kJoinWaves - 1) / kJoinWaves)), block(64 * kJoinWaves);
+        hipLaunchKernelGGL((join_partials_kernel<D>), grid, block, 0, stream, jp);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }

@@ -25,14 +25,16 @@ struct spin_ctx {
     int64_t cap_req = 0, cap_rows = 0, cap_pages = 0, cap_items = 0, cap_slots = 0;
     int64_t need_req = 0, need_rows = 0, need_pages = 0, need_items = 0, need_slots = 0;
     // device workspace
-    char* d_blob = nullptr;        // tables of the current call (items, orders, offsets, page table)
+    char* d_blob[kStages] = {nullptr, nullptr, nullptr, nullptr};   // tables of a call (items, orders, offsets, page table)
     size_t blob_bytes = 0;
+    hipStream_t copy_stream = nullptr;   // table uploads run here, beside the previous call's kernels
+    hipEvent_t ev_done[kStages] = {nullptr, nullptr, nullptr, nullptr};   // kernels reading d_blob[s] have finished
+    bool done_pending[kStages] = {false, false, false, false};
     float* d_part_o = nullptr;
     float* d_part_ml = nullptr;
     float* d_row_max = nullptr;    // acceptance row statistics
     double* d_row_sum = nullptr;
     int32_t* d_row_arg = nullptr;
-    int32_t* d_row_off = nullptr;
     // pinned staging ring
     char* h_stage[kStages] = {nullptr, nullptr, nullptr, nullptr};
     hipEvent_t ev[kStages] = {nullptr, nullptr, nullptr, nullptr};
@@ -76,20 +78,19 @@ hipEvent_t* prof_slot(spin_ctx* c, std::vector<hipEvent_t>& pool, int& used) {
 }
 
 void free_workspace(spin_ctx* c) {
-    if (c->d_blob) (void)hipFree(c->d_blob);
+    for (int s = 0; s < kStages; ++s)
+        if (c->d_blob[s]) (void)hipFree(c->d_blob[s]);
     if (c->d_part_o) (void)hipFree(c->d_part_o);
     if (c->d_part_ml) (void)hipFree(c->d_part_ml);
     if (c->d_row_max) (void)hipFree(c->d_row_max);
     if (c->d_row_sum) (void)hipFree(c->d_row_sum);
     if (c->d_row_arg) (void)hipFree(c->d_row_arg);
-    if (c->d_row_off) (void)hipFree(c->d_row_off);
     for (int s = 0; s < kStages; ++s)
         if (c->h_stage[s]) (void)hipHostFree(c->h_stage[s]);
-    c->d_blob = nullptr;
     c->d_part_o = c->d_part_ml = c->d_row_max = nullptr;
     c->d_row_sum = nullptr;
-    c->d_row_arg = c->d_row_off = nullptr;
-    for (int s = 0; s < kStages; ++s) c->h_stage[s] = nullptr;
+    c->d_row_arg = nullptr;
+    for (int s = 0; s < kStages; ++s) c->h_stage[s] = c->d_blob[s] = nullptr;
 }
 
 size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
@@ -124,13 +125,13 @@ int spin_create(spin_ctx** out, int device_id) {
     if (e != hipSuccess) return SPIN_EHIP;
     spin_ctx* c = new spin_ctx();
     c->device = device_id;
-    for (int s = 0; s < kStages; ++s) {
-        e = hipEventCreateWithFlags(&c->ev[s], hipEventDisableTiming);
-        if (e != hipSuccess) {
-            for (int k = 0; k < s; ++k) (void)hipEventDestroy(c->ev[k]);
-            delete c;
-            return SPIN_EHIP;
-        }
+    bool ok = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
+    for (int s = 0; s < kStages && ok; ++s)
+        ok = hipEventCreateWithFlags(&c->ev[s], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&c->ev_done[s], hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+        spin_destroy(c);
+        return SPIN_EHIP;
     }
     *out = c;
     return SPIN_OK;
@@ -142,8 +143,11 @@ void spin_destroy(spin_ctx* ctx) {
     (void)hipDeviceSynchronize();
     free_workspace(ctx);
     free_profile(ctx);
-    for (int s = 0; s < kStages; ++s)
+    for (int s = 0; s < kStages; ++s) {
         if (ctx->ev[s]) (void)hipEventDestroy(ctx->ev[s]);
+        if (ctx->ev_done[s]) (void)hipEventDestroy(ctx->ev_done[s]);
+    }
+    if (ctx->copy_stream) (void)hipStreamDestroy(ctx->copy_stream);
     delete ctx;
 }
 
@@ -155,8 +159,9 @@ int spin_last_error(spin_ctx* ctx, char* buf, size_t n) {
 
 int spin_set_chunk(spin_ctx* ctx, int32_t keys_per_item) {
     if (!ctx) return SPIN_EINVAL;
+    if (keys_per_item == 0) keys_per_item = spin::kDefaultChunk;
     if (keys_per_item < 32 || keys_per_item > spin::kMaxChunk || keys_per_item % 32)
-        return fail(ctx, SPIN_EINVAL, "keys per item must be a multiple of 32 in 32..1024");
+        return fail(ctx, SPIN_EINVAL, "keys per item must be 0 (default) or a multiple of 32 in 32..2048");
     ctx->chunk = keys_per_item;
     return SPIN_OK;
 }
@@ -186,7 +191,7 @@ int spin_reserve(spin_ctx* ctx, int64_t max_req, int64_t max_rows, int64_t max_p
     e = hipDeviceSynchronize();
     if (e != hipSuccess) return fail_hip(ctx, e, "hipDeviceSynchronize");
     free_workspace(ctx);
-    for (int s = 0; s < kStages; ++s) ctx->ev_pending[s] = false;
+    for (int s = 0; s < kStages; ++s) ctx->ev_pending[s] = ctx->done_pending[s] = false;
     ctx->cap_req = ctx->cap_rows = ctx->cap_pages = ctx->cap_items = ctx->cap_slots = 0;
     const size_t blob = blob_size(max_req, max_rows, max_pages, max_items);
     const int64_t stat_rows = 2 * max_rows + max_req + 1;
@@ -198,14 +203,13 @@ int spin_reserve(spin_ctx* ctx, int64_t max_req, int64_t max_rows, int64_t max_p
             return fail_hip(ctx, e, #call);              \
         }                                                \
     } while (0)
-    SPIN_TRY(hipMalloc((void**)&ctx->d_blob, blob));
+    for (int s = 0; s < kStages; ++s) SPIN_TRY(hipMalloc((void**)&ctx->d_blob[s], blob));
     SPIN_TRY(hipMalloc((void**)&ctx->d_part_o, std::max<size_t>(16, (size_t)max_part_slots * spin::kPartRow * 4)));
     SPIN_TRY(hipMalloc((void**)&ctx->d_part_ml, std::max<size_t>(16, (size_t)max_part_slots * 2 * 4)));
     SPIN_TRY(hipMalloc((void**)&ctx->d_row_max, (size_t)stat_rows * 4));
     SPIN_TRY(hipMalloc((void**)&ctx->d_row_sum, (size_t)stat_rows * 8));
     SPIN_TRY(hipMalloc((void**)&ctx->d_row_arg, (size_t)stat_rows * 4));
-    SPIN_TRY(hipMalloc((void**)&ctx->d_row_off, (size_t)(max_req + 1) * 4));
-    for (int s = 0; s < kStages; ++s) SPIN_TRY(hipHostMalloc((void**)&ctx->h_stage[s], blob, hipHostMallocDefault));
+    for (int s = 0; s < kStages; ++s) SPIN_TRY(hipHostMalloc((void**)&ctx->h_stage[s], blob, hipHostMallocMapped | hipHostMallocPortable));
 #undef SPIN_TRY
     ctx->blob_bytes = blob;
     ctx->cap_req = max_req;
@@ -288,11 +292,22 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     memcpy(h + off, table->page_table, n_pages_used * 4);
     off = align16(off + n_pages_used * 4);
     if (off > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
-    e = hipMemcpyAsync(ctx->d_blob, h, off, hipMemcpyHostToDevice, stream);
+    // Upload on the context's own stream so that it runs beside the kernels of earlier calls; the
+    // caller's stream only waits for it.  d_blob[slot] is free once the kernels of the call that
+    // last used it are done.
+    const int slot = ctx->stage;
+    char* blob = ctx->d_blob[slot];
+    if (ctx->done_pending[slot]) {
+        e = hipStreamWaitEvent(ctx->copy_stream, ctx->ev_done[slot], 0);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
+    }
+    e = hipMemcpyAsync(blob, h, off, hipMemcpyHostToDevice, ctx->copy_stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync");
-    e = hipEventRecord(ctx->ev[ctx->stage], stream);
+    e = hipEventRecord(ctx->ev[slot], ctx->copy_stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    ctx->ev_pending[ctx->stage] = true;
+    ctx->ev_pending[slot] = true;
+    e = hipStreamWaitEvent(stream, ctx->ev[slot], 0);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
 
     // ---- launch
     int pshift = 0;
@@ -302,9 +317,9 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.k_pool = (const uint16_t*)kv->k_pool;
     ap.v_pool = (const uint16_t*)kv->v_pool;
     ap.q = (const uint16_t*)q_dev;
-    ap.items = (const spin::Item*)(ctx->d_blob + off_items);
+    ap.items = (const spin::Item*)(blob + off_items);
     ap.order = nullptr;
-    ap.page_table = (const int32_t*)(ctx->d_blob + off_pt);
+    ap.page_table = (const int32_t*)(blob + off_pt);
     ap.part_o = ctx->d_part_o;
     ap.part_ml = ctx->d_part_ml;
     ap.page_stride = kv->page_stride;
@@ -316,22 +331,25 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.page_shift = pshift;
     ap.scale_log2 = scale * 1.4426950408889634f;
     const int32_t* order_dev[3];
-    for (int c = 0; c < 3; ++c) order_dev[c] = (const int32_t*)(ctx->d_blob + off_order[c]);
+    for (int c = 0; c < 3; ++c) order_dev[c] = (const int32_t*)(blob + off_order[c]);
     spin::JoinParams jp;
     jp.items = ap.items;
-    jp.item_begin = (const int32_t*)(ctx->d_blob + off_begin);
-    jp.row_req = (const int32_t*)(ctx->d_blob + off_rowreq);
+    jp.item_begin = (const int32_t*)(blob + off_begin);
+    jp.row_req = (const int32_t*)(blob + off_rowreq);
     jp.part_o = ctx->d_part_o;
     jp.part_ml = ctx->d_part_ml;
     jp.o = (uint16_t*)o_dev;
     jp.n_q_heads = n_q_heads;
     jp.group = group;
-    jp.row_base = 0;
+    jp.n_rows = (int32_t)n_rows;
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     e = spin::launch_attn(kv->head_dim, ap, order_dev, n_in_class, jp, (int)n_rows, stream, pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
     if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    e = hipEventRecord(ctx->ev_done[slot], stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    ctx->done_pending[slot] = true;
     return SPIN_OK;
 }
 
@@ -342,6 +360,7 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     if (!ctx) return SPIN_EINVAL;
     if (mode != SPIN_ACCEPT_GREEDY && mode != SPIN_ACCEPT_REJECTION) return fail(ctx, SPIN_EINVAL, "unknown mode");
     if (n_req < 0 || vocab < 1) return fail(ctx, SPIN_EINVAL, "n_req < 0 or vocab < 1");
+    if (vocab > spin::kMaxVocab) return fail(ctx, SPIN_EUNSUPPORTED, "vocabulary larger than 1048576 ids");
     if (n_req == 0) return SPIN_OK;
     if (!draft_len_host) return fail(ctx, SPIN_EINVAL, "draft_len is null");
     ctx->row_off_host.resize(n_req + 1);
@@ -371,15 +390,17 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     char* h = nullptr;
     int rc = next_stage(ctx, &h);
     if (rc) return rc;
+    // The per-request row offsets (two ints per workgroup) are read by the kernel straight from this
+    // pinned, device-mapped buffer: no copy, no bubble on the stream.  The buffer is reused only after
+    // the event recorded behind the kernels has passed.
     memcpy(h, ctx->row_off_host.data(), (size_t)(n_req + 1) * 4);
-    e = hipMemcpyAsync(ctx->d_row_off, h, (size_t)(n_req + 1) * 4, hipMemcpyHostToDevice, stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync");
-    e = hipEventRecord(ctx->ev[ctx->stage], stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    ctx->ev_pending[ctx->stage] = true;
+    void* row_off_dev = nullptr;
+    e = hipHostGetDevicePointer(&row_off_dev, h, 0);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
+    const int slot = ctx->stage;
 
     spin::AcceptParams p;
-    p.row_off = ctx->d_row_off;
+    p.row_off = (const int32_t*)row_off_dev;
     p.draft_tokens = draft_tokens_dev;
     p.target_logits = target_logits_dev;
     p.draft_logits = draft_logits_dev;
@@ -399,6 +420,9 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     e = spin::launch_accept(p, stream, pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "acceptance launch");
     if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    e = hipEventRecord(ctx->ev[slot], stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    ctx->ev_pending[slot] = true;
     return SPIN_OK;
 }
 

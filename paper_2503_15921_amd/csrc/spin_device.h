@@ -35,7 +35,7 @@ struct JoinParams {
     const float* part_o;
     const float* part_ml;
     uint16_t* o;
-    int32_t n_q_heads, group, row_base;
+    int32_t n_q_heads, group, n_rows;
 };
 
 // ev_mid (may be null) is recorded between the attention kernels and the join kernel.
@@ -59,6 +59,9 @@ struct AcceptParams {
 };
 
 // ev_mid (may be null) is recorded between the two kernels.
+// Largest vocabulary the next-token search handles (its per-run sums live in LDS).
+constexpr int kMaxVocab = 1 << 20;
+
 hipError_t launch_accept(const AcceptParams& p, hipStream_t stream, hipEvent_t ev_mid);
 
 }  // namespace spin

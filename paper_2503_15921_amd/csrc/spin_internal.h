@@ -16,10 +16,10 @@ namespace spin {
 // column tiles of 16.
 constexpr int kMaxTileRows = 64;
 // Page ids one work item may touch (cached in LDS by the attention kernel).
-constexpr int kMaxItemPages = 72;
+constexpr int kMaxItemPages = 136;
 // Default / maximum number of keys per work item.
-constexpr int kDefaultChunk = 256;
-constexpr int kMaxChunk = 1024;
+constexpr int kDefaultChunk = 1024;
+constexpr int kMaxChunk = 2048;
 
 // One unit of attention work: draft rows [q_row0, q_row0+n_q) (packed row numbers) of `parent`
 // against its keys [k0, k1); row t of the item sees keys below min(k1, causal0 + t).

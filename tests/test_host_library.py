@@ -121,7 +121,7 @@ def test_check_tiling_accepts_exact_and_rejects_broken():
     assert spin.check_tiling([p], [g], subs) == 0
 
 
-@pytest.mark.parametrize("group,chunk,page", [(1, 64, 16), (1, 256, 16), (8, 256, 16), (4, 32, 4), (1, 1024, 1)])
+@pytest.mark.parametrize("group,chunk,page", [(1, 64, 16), (1, 256, 16), (8, 1024, 16), (4, 32, 4), (1, 2048, 1)])
 def test_scheduler_items_tile_every_request(group, chunk, page):
     rng = np.random.default_rng(group * 1000 + chunk)
     prefix = rng.integers(0, 700, size=7); draft = rng.integers(1, 17, size=7)
@@ -133,7 +133,7 @@ def test_scheduler_items_tile_every_request(group, chunk, page):
         for parent, qb, ql, kb, kl in items:
             assert ql * group <= 64
             assert 1 <= kl <= chunk
-            assert (kb + kl - 1) // page - kb // page + 1 <= 72
+            assert (kb + kl - 1) // page - kb // page + 1 <= 136
             assert kb // chunk == (kb + kl - 1) // chunk or kl <= chunk    # never longer than one chunk
         # parent-sorted: the join kernel walks a contiguous range per request
         assert list(items[:, 0]) == sorted(items[:, 0])
