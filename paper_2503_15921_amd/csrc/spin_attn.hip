@@ -43,6 +43,12 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
+// K/V bytes are used once: a non-temporal load keeps them from displacing anything in the caches
+// and streams measurably faster from HBM on this part.
+__device__ __forceinline__ u32x4 stream_load(const uint16_t* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
 template <int D, int NT>
 __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     constexpr int DCH = D / 8;      // 16-byte chunks per key row
@@ -96,14 +102,14 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 #pragma unroll
         for (int i = 0; i < KLOADS; ++i) {
             const int f = i * 64 + lane;
-            Kr[i] = *(const u32x4*)(row_ptr(P.k_pool, kb + f / DCH) + (f % DCH) * 8);
+            Kr[i] = stream_load(row_ptr(P.k_pool, kb + f / DCH) + (f % DCH) * 8);
         }
     };
     auto load_v = [&](int kb) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int kl = (j >> 2) * 16 + g * 4 + (j & 3);
-            Vr[j] = *(const u32x4*)(row_ptr(P.v_pool, kb + kl) + (m16 % DCH) * 8);
+            Vr[j] = stream_load(row_ptr(P.v_pool, kb + kl) + (m16 % DCH) * 8);
         }
     };
 
