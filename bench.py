@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="13b")
     ap.add_argument("--seed", type=int, default=3)
-    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--waves", type=int, default=0, help="wavefronts per attention launch (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="instead of the step, run a plain 1 GiB device copy per step (counter calibration)")
@@ -108,8 +108,8 @@ def main():
     t = batch.table
     ab = si.make_accept_batch(t.draft_len, cfg.vocab, cfg.logit_sigma, args.seed, device=dev)
     ctx = spin.SpinContext(0)
-    if args.chunk:
-        ctx.set_chunk(args.chunk)
+    if args.waves:
+        ctx.set_waves(args.waves)
     tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
     out = torch.empty_like(batch.q)
     n_acc = torch.empty(t.n_req, dtype=torch.int32, device=dev)

@@ -114,7 +114,7 @@ typedef struct spin_decomp_params {
 int spin_create(spin_ctx** out, int device_id);
 
 /* Allocate (or grow to) workspace for batches of up to max_req requests, max_rows draft rows in
- * total, max_pages page-table entries, max_items work items and max_part_slots partial result
+ * total, max_pages page-table entries, max_items work pieces and max_part_slots partial result
  * rows.  This is the only call that allocates device or pinned memory; it synchronises the
  * device.  spin_verify_attn / spin_accept return SPIN_ENOSPC when the reservation is too small
  * and spin_required() then reports what the refused call needed. */
@@ -134,10 +134,10 @@ const char* spin_strerror(int code);
 /* Copy the text of the context's last error into buf (NUL-terminated, truncated to n). */
 int spin_last_error(spin_ctx* ctx, char* buf, size_t n);
 
-/* KV chunk length of the scheduler (keys per work item: a multiple of 32 in 32..2048, or 0 for
- * the default of 1024).  Key ranges longer than this are cut so that the chip is filled evenly
- * (the same split-and-rejoin as Eq. (13), used as a scheduler). */
-int spin_set_chunk(spin_ctx* ctx, int32_t keys_per_item);
+/* Number of wavefronts the attention kernel runs per launch: 0 (default) = as many as the GPU
+ * holds at once, otherwise that many (for experiments and tests; results differ only in
+ * summation order). */
+int spin_set_waves(spin_ctx* ctx, int32_t n_waves);
 
 /* ---- decomposition (host only, no GPU needed) -------------------------------------------- */
 
@@ -156,13 +156,26 @@ int spin_kv_padding(const spin_req_table* table, int32_t kv_len, int64_t* n_rows
  * request covered by exactly one sub-request).  SPIN_OK or SPIN_ETABLE.  Host only. */
 int spin_check_tiling(const spin_req_table* table, const spin_subreq* subs, int32_t n_sub);
 
-/* The scheduler's view of a batch, for inspection and tests (host only).  Work item k covers
- * draft rows [q_begin, q_begin+q_len) x keys [kv_begin, kv_begin+kv_len) of `parent`, clipped
- * at the causal edge like a sub-request.  `group` = n_q_heads / n_kv_heads.  Same cap/n_out
- * protocol as spin_decompose.  subs == NULL means one sub-request per request. */
+/* The scheduler's view of a batch, for inspection and tests (host only).  The attention kernel
+ * runs a fixed number of wavefronts per launch; the key blocks (32 keys) of all (rectangle, KV
+ * head) pairs form one sequence that is cut into equal shares, one per wavefront.  A piece is one
+ * run of blocks of one (rectangle, KV head) inside one share.  `tile_class` 0/1/2 = launches for
+ * up to 16/32/64 (draft row x query head) rows; `wave` numbers the wavefronts of a class.
+ * Flags: CARRY_IN = continues the wavefront's previous piece, CARRY_OUT = continued by its next
+ * piece (nothing written), DIRECT = ends a rectangle that one wavefront held entirely and that
+ * holds every key its rows may see: final rows are written, no partial result.  `group` =
+ * n_q_heads / n_kv_heads, n_waves = wavefronts per class.  Same cap/n_out protocol as
+ * spin_decompose.  subs == NULL means one sub-request per request. */
+#define SPIN_PIECE_CARRY_IN 1
+#define SPIN_PIECE_CARRY_OUT 2
+#define SPIN_PIECE_DIRECT 4
+typedef struct spin_work_piece {
+    int32_t parent, q_begin, q_len, kv_begin, kv_len;
+    int32_t kv_head, tile_class, wave, flags;
+} spin_work_piece;
 int spin_schedule(const spin_req_table* table, const spin_subreq* subs, int32_t n_sub,
-                  int32_t page_size, int32_t group, int32_t keys_per_item,
-                  spin_subreq* items_out, int32_t cap, int32_t* n_out);
+                  int32_t page_size, int32_t group, int32_t n_kv_heads, int32_t n_waves,
+                  spin_work_piece* out, int32_t cap, int32_t* n_out);
 
 /* ---- the verification step ---------------------------------------------------------------- */
 

@@ -42,6 +42,14 @@ class SubReq(C.Structure):
                 ("kv_begin", C.c_int32), ("kv_len", C.c_int32)]
 
 
+class WorkPiece(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("parent", "q_begin", "q_len", "kv_begin", "kv_len", "kv_head",
+                                          "tile_class", "wave", "flags")]
+
+
+PIECE_CARRY_IN, PIECE_CARRY_OUT, PIECE_DIRECT = 1, 2, 4
+
+
 class DecompParams(C.Structure):
     _fields_ = [("policy", C.c_int32), ("q_width", C.c_int32), ("kv_len", C.c_int32),
                 ("max_subreq", C.c_int32), ("l_min", C.c_int32), ("l_max", C.c_int32),
@@ -55,7 +63,7 @@ class SpinError(RuntimeError):
 
 
 EXPORTS = ["spin_create", "spin_reserve", "spin_required", "spin_destroy", "spin_strerror",
-           "spin_last_error", "spin_set_chunk", "spin_decompose", "spin_kv_padding",
+           "spin_last_error", "spin_set_waves", "spin_decompose", "spin_kv_padding",
            "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_accept",
            "spin_profile_begin", "spin_profile_end"]
 
@@ -85,11 +93,12 @@ def load_library():
     lib.spin_strerror.argtypes = [C.c_int]
     lib.spin_strerror.restype = C.c_char_p
     lib.spin_last_error.argtypes = [C.c_void_p, C.c_char_p, C.c_size_t]
-    lib.spin_set_chunk.argtypes = [C.c_void_p, C.c_int32]
+    lib.spin_set_waves.argtypes = [C.c_void_p, C.c_int32]
     lib.spin_decompose.argtypes = [tp, C.POINTER(DecompParams), sp, C.c_int32, _i32p, _i32p]
     lib.spin_kv_padding.argtypes = [tp, C.c_int32, _i64p, _i64p]
     lib.spin_check_tiling.argtypes = [tp, sp, C.c_int32]
-    lib.spin_schedule.argtypes = [tp, sp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, sp, C.c_int32, _i32p]
+    lib.spin_schedule.argtypes = [tp, sp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                  C.POINTER(WorkPiece), C.c_int32, _i32p]
     lib.spin_verify_attn.argtypes = [C.c_void_p, C.POINTER(KvDesc), tp, sp, C.c_int32, C.c_void_p,
                                      C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
     lib.spin_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
@@ -185,18 +194,19 @@ def check_tiling(prefix_len, draft_len, subs) -> int:
     return lib.spin_check_tiling(C.byref(t.struct), p, n)
 
 
-def schedule(prefix_len, draft_len, subs, page_size: int, group: int, keys_per_item: int) -> np.ndarray:
-    """spin_schedule: the work items the attention kernel would run, as an int32 [n,5] array."""
+def schedule(prefix_len, draft_len, subs, page_size: int, group: int, n_kv_heads: int, n_waves: int) -> np.ndarray:
+    """spin_schedule: the pieces the attention kernel would stream, as an int32 [n,9] array of
+    (parent, q_begin, q_len, kv_begin, kv_len, kv_head, tile_class, wave, flags)."""
     lib = load_library()
     t = _Table(prefix_len, draft_len)
     p, n, keep = _subs_arg(subs)
     cnt = C.c_int32(0)
-    rc = lib.spin_schedule(C.byref(t.struct), p, n, page_size, group, keys_per_item, None, 0, C.byref(cnt))
+    rc = lib.spin_schedule(C.byref(t.struct), p, n, page_size, group, n_kv_heads, n_waves, None, 0, C.byref(cnt))
     if rc not in (OK, ENOSPC):
         _check(rc)
-    out = np.zeros((max(cnt.value, 1), 5), dtype=np.int32)
-    _check(lib.spin_schedule(C.byref(t.struct), p, n, page_size, group, keys_per_item,
-                             out.ctypes.data_as(C.POINTER(SubReq)), cnt.value, C.byref(cnt)))
+    out = np.zeros((max(cnt.value, 1), 9), dtype=np.int32)
+    _check(lib.spin_schedule(C.byref(t.struct), p, n, page_size, group, n_kv_heads, n_waves,
+                             out.ctypes.data_as(C.POINTER(WorkPiece)), cnt.value, C.byref(cnt)))
     return out[: cnt.value].copy()
 
 
@@ -231,8 +241,8 @@ class SpinContext:
         _check(self._lib.spin_required(self._h, *[C.byref(x) for x in v]), self._h)
         return tuple(x.value for x in v)
 
-    def set_chunk(self, keys_per_item: int):
-        _check(self._lib.spin_set_chunk(self._h, keys_per_item), self._h)
+    def set_waves(self, n_waves: int):
+        _check(self._lib.spin_set_waves(self._h, n_waves), self._h)
 
     def profile_begin(self, max_calls: int):
         _check(self._lib.spin_profile_begin(self._h, max_calls), self._h)

@@ -4,8 +4,10 @@
 // see, read through a page table; pieces of one request are rejoined with the single
 // denominator of Eq. (13), Sec. V-A.
 //
-// One wavefront works on one item = (draft rows x query heads of one KV group) x (a run of
-// keys) of one request and one KV head.  It streams the K and V rows of 32 keys at a time:
+// The launch holds as many wavefronts as the chip keeps resident (one per workgroup).  The host
+// has cut the sequence of all 32-key blocks of all (rectangle of draft rows x keys, KV head)
+// pairs into equal shares, one per wavefront; a share is a list of pieces, each a run of blocks
+// of one (rectangle, KV head).  A wavefront streams its pieces back to back:
 //   * K: every lane fetches 16 contiguous bytes so that one load instruction covers 1 KiB of
 //     contiguous cache, the tile is re-shaped through LDS (padded rows, conflict-free) into the
 //     MFMA operand layout [key][32 head dims], and S^T = K Q^T is formed with
@@ -19,11 +21,17 @@
 //     16-bit values in registers with byte permutes; V never touches LDS.  The key order of the
 //     contraction is chosen to be the order in which the score tile already holds P, so P goes
 //     from accumulator to operand without leaving its lane.
-// The next block's K and V are in flight (in registers) while the current one is consumed.
-// Un-normalised results (running max, sum, O) go to a partial buffer; a second kernel joins the
-// partials of each (row, head) and writes bf16.
+//   * The block after the current one -- the next of this piece or the first of the next piece --
+//     is always in flight (in registers) while the current one is consumed; descriptors and
+//     page ids of later pieces are fetched pieces ahead, so the stream never drains between
+//     pieces.  K/V loads are non-temporal.
+//   * A (rectangle, KV head) that one wavefront held completely, and that holds every key its
+//     rows may see, is normalised and written as bf16 at once.  Otherwise the un-normalised
+//     result (running max, sum, O) goes to a partial buffer and join_partials_kernel applies
+//     Eq. (13).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "spin_device.h"
 
@@ -55,235 +63,380 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     constexpr int KCALLS = D / 32;  // MFMA calls (32 head dims each) per 16-key score tile
     constexpr int KLOADS = DCH / 2; // 16-byte loads per lane for 32 keys of K
     constexpr int LROW = D + 8;     // LDS row pitch in elements: 16 bytes of padding per key
+    constexpr int PTR = (kMaxPiecePages + 63) / 64;   // page ids per lane
     __shared__ __attribute__((aligned(16))) uint16_t sK[32 * LROW];
-    __shared__ int32_t sPT[kMaxItemPages];
+    __shared__ int32_t sPT[3][PTR * 64];   // page ids of the current piece and the two after it
 
     const int lane = threadIdx.x;
     const int m16 = lane & 15, g = lane >> 4;
-    const int n_kv = P.n_kv_heads;
-    const int kvh = blockIdx.x % n_kv;
-    const Item it = P.items[P.order[blockIdx.x / n_kv]];
     const int G = P.group;
     const int pshift = P.page_shift;
     const int pmask = (1 << pshift) - 1;
-    const int k0 = it.k0, k1 = it.k1;
+    const int pc_begin = P.wave_begin[blockIdx.x], pc_end = P.wave_begin[blockIdx.x + 1];
+    if (pc_begin >= pc_end) return;
 
-    // page ids of this item
-    const int pg0 = k0 >> pshift;
-    const int npg = ((k1 - 1) >> pshift) - pg0 + 1;
-    for (int i = lane; i < npg; i += 64) sPT[i] = P.page_table[it.pt_base + pg0 + i];
-
-    // query operands and per-row visibility limits
-    bf16x8 qf[NT][KCALLS];
-    int lim[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int nn = nt * 16 + m16;
-        const int tl = nn / G, hg = nn - tl * G;
-        const bool valid = tl < it.n_q;
-        lim[nt] = valid ? min(k1, it.causal0 + tl) : k0;
-        const uint16_t* qp = P.q + ((int64_t)(it.q_row0 + (valid ? tl : 0)) * P.n_q_heads + kvh * G + hg) * D + g * 8;
-#pragma unroll
-        for (int c = 0; c < KCALLS; ++c) {
-            u32x4 v = valid ? *(const u32x4*)(qp + c * 32) : u32x4{0, 0, 0, 0};
-            qf[nt][c] = __builtin_bit_cast(bf16x8, v);
+    // Descriptor r of this wavefront's share (k0 == k1 when the share is exhausted).  Read through
+    // the constant address space: the descriptors are never written by this kernel, which lets the
+    // compiler fetch them with scalar loads.
+    auto fetch_piece = [&](int r, Piece& pc) {
+        if (pc_begin + r < pc_end) {
+            typedef const int32_t __attribute__((address_space(4)))* ConstWords;
+            const ConstWords w = (ConstWords)(uintptr_t)(P.pieces + pc_begin + r);
+            pc = Piece{w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]};
+        } else {
+            pc = Piece{0, 0, 0, 0, 0, 0, 0, 0};
         }
-    }
-    __syncthreads();
+    };
+    auto load_pages = [&](const Piece& pc, int32_t (&pr)[PTR]) {
+        const int pg0 = pc.k0 >> pshift;
+        const int npg = pc.k1 > pc.k0 ? ((pc.k1 - 1) >> pshift) - pg0 + 1 : 0;
+#pragma unroll
+        for (int i = 0; i < PTR; ++i) {
+            const int idx = lane + 64 * i;
+            pr[i] = idx < npg ? P.page_table[pc.pt_base + pg0 + idx] : 0;
+        }
+    };
+    auto store_pages = [&](int buf, const int32_t (&pr)[PTR]) {
+#pragma unroll
+        for (int i = 0; i < PTR; ++i) sPT[buf][lane + 64 * i] = pr[i];
+    };
 
-    const int64_t head_off = (int64_t)kvh * P.head_stride;
-    auto row_ptr = [&](const uint16_t* pool, int key) -> const uint16_t* {
-        key = min(key, k1 - 1);   // keys past the item's end are masked; fetch a valid row instead
-        const int pg = sPT[(key >> pshift) - pg0];
+    // query operands of a piece (zeros for rows beyond its draft rows)
+    bf16x8 qf[NT][KCALLS];
+    auto load_q = [&](const Piece& pc) {
+        const int kvh = pc.head_flags & kPieceHeadMask;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int nn = nt * 16 + m16;
+            const int tl = nn / G, hg = nn - tl * G;
+            const bool valid = tl < pc.n_q;
+            const uint16_t* qp = P.q + ((int64_t)(pc.q_row0 + (valid ? tl : 0)) * P.n_q_heads + kvh * G + hg) * D + g * 8;
+#pragma unroll
+            for (int c = 0; c < KCALLS; ++c) {
+                u32x4 v = valid ? *(const u32x4*)(qp + c * 32) : u32x4{0, 0, 0, 0};
+                qf[nt][c] = __builtin_bit_cast(bf16x8, v);
+            }
+        }
+    };
+
+    // K/V rows of 32 keys starting at kb of the piece described by (buf, pg0, k1, head_off)
+    u32x4 Kr[KLOADS], Vr[8];
+    auto row_ptr = [&](const uint16_t* pool, int buf, int pg0, int k1, int64_t head_off, int key) -> const uint16_t* {
+        key = min(key, k1 - 1);   // keys past the piece's end are masked; fetch a valid row instead
+        const int pg = sPT[buf][(key >> pshift) - pg0];
         return pool + (int64_t)pg * P.page_stride + head_off + (int64_t)(key & pmask) * P.token_stride;
     };
-    u32x4 Kr[KLOADS], Vr[8];
-    auto load_k = [&](int kb) {
+    auto load_k = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
 #pragma unroll
         for (int i = 0; i < KLOADS; ++i) {
             const int f = i * 64 + lane;
-            Kr[i] = stream_load(row_ptr(P.k_pool, kb + f / DCH) + (f % DCH) * 8);
+            Kr[i] = stream_load(row_ptr(P.k_pool, buf, pg0, k1, head_off, kb + f / DCH) + (f % DCH) * 8);
         }
     };
-    auto load_v = [&](int kb) {
+    auto load_v = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int kl = (j >> 2) * 16 + g * 4 + (j & 3);
-            Vr[j] = stream_load(row_ptr(P.v_pool, kb + kl) + (m16 % DCH) * 8);
+            Vr[j] = stream_load(row_ptr(P.v_pool, buf, pg0, k1, head_off, kb + kl) + (m16 % DCH) * 8);
         }
     };
 
+    // ---- start-up: the first four descriptors, page ids of the first three pieces in LDS
+    Piece cp, p1, p2, p3;
+    fetch_piece(0, cp);
+    fetch_piece(1, p1);
+    fetch_piece(2, p2);
+    fetch_piece(3, p3);
+    int next_piece = 4;
+    int32_t pr[PTR];
+    load_pages(cp, pr);
+    store_pages(0, pr);
+    load_pages(p1, pr);
+    store_pages(1, pr);
+    load_pages(p2, pr);
+    store_pages(2, pr);
+    bool pr_pending = false;   // pr holds page ids that still have to go to LDS
+    load_q(cp);
+    __syncthreads();
+
     f32x4 O[NT][8];
     float m_run[NT], l_run[NT];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        m_run[nt] = kNegBig;
-        l_run[nt] = 0.f;
-#pragma unroll
-        for (int jd = 0; jd < 8; ++jd) O[nt][jd] = f32x4{0, 0, 0, 0};
+    int lim[NT];
+    int cb = 0;   // LDS page-id buffer of the current piece; the next piece's is (cb + 1) % 3
+    {
+        const int64_t head = (int64_t)(cp.head_flags & kPieceHeadMask) * P.head_stride;
+        load_k(cb, cp.k0 >> pshift, cp.k1, head, cp.k0);
+        load_v(cb, cp.k0 >> pshift, cp.k1, head, cp.k0);
     }
 
-    const int full_end = min(k1, it.causal0);   // keys below this are visible to every row of the item
-    load_k(k0);
-    load_v(k0);
-    for (int kb = k0; kb < k1; kb += 32) {
-        // ---- K: registers -> LDS in operand shape
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < KLOADS; ++i) {
-            const int f = i * 64 + lane;
-            *(u32x4*)&sK[(f / DCH) * LROW + (f % DCH) * 8] = Kr[i];
-        }
-        __syncthreads();
-        load_k(kb + 32);   // past the item's end this re-reads its last key row (clamped): harmless
-
-        // ---- S^T = K Q^T
-        f32x4 S[2][NT];
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) S[t][nt] = f32x4{0, 0, 0, 0};
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int c = 0; c < KCALLS; ++c) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sK[(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    S[t][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[nt][c], S[t][nt], 0, 0, 0);
-            }
-
-        // ---- online softmax; lane (row, g) holds keys kb + t*16 + g*4 + r
-        const bool full = kb + 32 <= full_end;
-        bf16x8 Pb[NT];
+    while (true) {
+        // ---- per piece: visibility limits; fresh accumulators unless it continues the previous piece
+        const bool carry_in = cp.head_flags & kPieceCarryIn;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            float s[8];
+            const int tl = (nt * 16 + m16) / G;
+            lim[nt] = tl < cp.n_q ? min(cp.k1, cp.causal0 + tl) : cp.k0;
+            if (!carry_in) {
+                m_run[nt] = kNegBig;
+                l_run[nt] = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s[e] = S[e >> 2][nt][e & 3];
-            if (!full) {
+                for (int jd = 0; jd < 8; ++jd) O[nt][jd] = f32x4{0, 0, 0, 0};
+            }
+        }
+        const int full_end = min(cp.k1, cp.causal0);   // keys below this are visible to every row
+        const bool more = p1.k1 > p1.k0;               // another piece follows this one
+        const bool new_q = more && !(p1.head_flags & kPieceCarryIn);
+
+        for (int kb = cp.k0; kb < cp.k1; kb += 32) {
+            // The block after this one: the next 32 keys of this piece, or the first of the next
+            // piece.  With nothing left the current block is fetched once more (valid memory, unused).
+            const bool last = kb + 32 >= cp.k1;
+            const bool hop = last && more;
+            const int s_buf = hop ? (cb == 2 ? 0 : cb + 1) : cb;
+            const int s_pg0 = hop ? (p1.k0 >> pshift) : (cp.k0 >> pshift);
+            const int s_k1 = hop ? p1.k1 : cp.k1;
+            const int64_t s_head = (int64_t)((hop ? p1.head_flags : cp.head_flags) & kPieceHeadMask) * P.head_stride;
+            const int s_kb = hop ? p1.k0 : (last ? kb : kb + 32);
+
+            // ---- K: registers -> LDS in operand shape
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < KLOADS; ++i) {
+                const int f = i * 64 + lane;
+                *(u32x4*)&sK[(f / DCH) * LROW + (f % DCH) * 8] = Kr[i];
+            }
+            // Page ids asked for during the previous piece's last block are older than the K rows just
+            // consumed, so they have arrived: they belong to the piece two after this one and take the
+            // LDS buffer of the piece before this one.
+            if (pr_pending) {
+                store_pages(cb == 0 ? 2 : cb - 1, pr);
+                pr_pending = false;
+            }
+            __syncthreads();
+            // During the last block, ask for the page ids of the piece three after this one (its
+            // descriptor was fetched when this piece began).  Issued before the K/V rows below so that
+            // waiting for those rows also covers these.
+            if (last && (p3.k1 > p3.k0)) {
+                load_pages(p3, pr);
+                pr_pending = true;
+            }
+            load_k(s_buf, s_pg0, s_k1, s_head, s_kb);
+
+            // ---- S^T = K Q^T
+            f32x4 S[2][NT];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) S[t][nt] = f32x4{0, 0, 0, 0};
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int c = 0; c < KCALLS; ++c) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sK[(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        S[t][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[nt][c], S[t][nt], 0, 0, 0);
+                }
+            // the queries are no longer needed after the last block: fetch the next piece's if they differ
+            if (last && new_q) load_q(p1);
+
+            // ---- online softmax; lane (row, g) holds keys kb + t*16 + g*4 + r
+            const bool full = kb + 32 <= full_end;
+            bf16x8 Pb[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                float s[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[e] = S[e >> 2][nt][e & 3];
+                if (!full) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int key = kb + (e >> 2) * 16 + g * 4 + (e & 3);
+                        if (key >= lim[nt]) s[e] = -INFINITY;
+                    }
+                }
+                float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run[nt], mx * P.scale_log2);
+                const float alpha = fast_exp2(m_run[nt] - m_new);
+                m_run[nt] = m_new;
+                float p[8], sum = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const int key = kb + (e >> 2) * 16 + g * 4 + (e & 3);
-                    if (key >= lim[nt]) s[e] = -INFINITY;
+                    p[e] = fast_exp2(s[e] * P.scale_log2 - m_new);
+                    sum += p[e];
+                }
+                l_run[nt] = l_run[nt] * alpha + sum;
+#pragma unroll
+                for (int jd = 0; jd < 8; ++jd) O[nt][jd] *= alpha;
+                u32x4 pk = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+                Pb[nt] = __builtin_bit_cast(bf16x8, pk);
+            }
+
+            // ---- V: 8x8 transpose of 16-bit values inside each lane, then O^T += V^T P^T
+            // (in two halves of four head dims, to keep the transposed copy small)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                u32x4 Vt[4];
+#pragma unroll
+                for (int j4 = 0; j4 < 4; ++j4) {
+                    const int jd = hh * 4 + j4;
+                    const uint32_t sel = (jd & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+                    for (int kp = 0; kp < 4; ++kp)
+                        Vt[j4][kp] = __builtin_amdgcn_perm(Vr[2 * kp + 1][jd >> 1], Vr[2 * kp][jd >> 1], sel);
+                }
+                if (hh == 1) load_v(s_buf, s_pg0, s_k1, s_head, s_kb);
+#pragma unroll
+                for (int j4 = 0; j4 < 4; ++j4) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, Vt[j4]);
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        O[nt][hh * 4 + j4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Pb[nt], O[nt][hh * 4 + j4], 0, 0, 0);
                 }
             }
-            float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run[nt], mx * P.scale_log2);
-            const float alpha = fast_exp2(m_run[nt] - m_new);
-            m_run[nt] = m_new;
-            float p[8], sum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                p[e] = fast_exp2(s[e] * P.scale_log2 - m_new);
-                sum += p[e];
-            }
-            l_run[nt] = l_run[nt] * alpha + sum;
-#pragma unroll
-            for (int jd = 0; jd < 8; ++jd) O[nt][jd] *= alpha;
-            u32x4 pk = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-            Pb[nt] = __builtin_bit_cast(bf16x8, pk);
         }
 
-        // ---- V: 8x8 transpose of 16-bit values inside each lane, then O^T += V^T P^T
-        u32x4 Vt[8];
+        // ---- result of this piece, unless the next piece carries on with the same accumulators.
+        // Lane (row, g) holds, per jd, head dims (g*4 + r)*8 + jd, r = 0..3.
+        if (!(cp.head_flags & kPieceCarryOut) && !(P.exp_flags & 1)) {
+            const int kvh = cp.head_flags & kPieceHeadMask;
+            const bool direct = cp.head_flags & kPieceDirect;
 #pragma unroll
-        for (int jd = 0; jd < 8; ++jd) {
-            const uint32_t sel = (jd & 1) ? 0x07060302u : 0x05040100u;
+            for (int nt = 0; nt < NT; ++nt) {
+                float l = l_run[nt];
+                l += __shfl_xor(l, 16);
+                l += __shfl_xor(l, 32);
+                const int nn = nt * 16 + m16;
+                const int tl = nn / G, hg = nn - tl * G;
+                if (tl < cp.n_q) {
+                    if (direct) {
+                        // final rows: for fixed r the eight jd are eight consecutive head dims = 16 bytes
+                        const float inv = 1.0f / l;
+                        uint16_t* op = P.o + ((int64_t)(cp.q_row0 + tl) * P.n_q_heads + kvh * G + hg) * D + g * 32;
+                        if (g * 4 < DCH) {
 #pragma unroll
-            for (int kp = 0; kp < 4; ++kp)
-                Vt[jd][kp] = __builtin_amdgcn_perm(Vr[2 * kp + 1][jd >> 1], Vr[2 * kp][jd >> 1], sel);
+                            for (int r = 0; r < 4; ++r) {
+                                u32x4 w = {pack_bf16(O[nt][0][r] * inv, O[nt][1][r] * inv),
+                                           pack_bf16(O[nt][2][r] * inv, O[nt][3][r] * inv),
+                                           pack_bf16(O[nt][4][r] * inv, O[nt][5][r] * inv),
+                                           pack_bf16(O[nt][6][r] * inv, O[nt][7][r] * inv)};
+                                *(u32x4*)(op + r * 8) = w;
+                            }
+                        }
+                    } else {
+                        // partial rows, stored as [jd][16] so that each lane writes 16 contiguous bytes;
+                        // the join kernel undoes the permutation
+                        const int64_t slot = (int64_t)cp.out_base + nn;
+                        float* po = P.part_o + slot * kPartRow;
+                        if (g * 4 < DCH) {
+#pragma unroll
+                            for (int jd = 0; jd < 8; ++jd) *(f32x4*)(po + jd * 16 + g * 4) = O[nt][jd];
+                        }
+                        if (g == 0) {
+                            P.part_ml[slot * 2] = m_run[nt];
+                            P.part_ml[slot * 2 + 1] = l;
+                        }
+                    }
+                }
+            }
         }
-        load_v(kb + 32);
-#pragma unroll
-        for (int jd = 0; jd < 8; ++jd) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, Vt[jd]);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                O[nt][jd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Pb[nt], O[nt][jd], 0, 0, 0);
-        }
-    }
+        if (!more) break;
 
-    // ---- partial result: lane (row, g) holds, per jd, head dims (g*4 + r)*8 + jd, r = 0..3.
-    // Stored as [jd][16] so that each lane writes 16 contiguous bytes; the join kernel undoes it.
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        float l = l_run[nt];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        const int nn = nt * 16 + m16;
-        const int tl = nn / G;
-        if (tl < it.n_q) {
-            const int64_t slot = (int64_t)it.part_base + (int64_t)kvh * (it.n_q * G) + nn;
-            float* po = P.part_o + slot * kPartRow;
-            if (g * 4 < DCH) {
-#pragma unroll
-                for (int jd = 0; jd < 8; ++jd) *(f32x4*)(po + jd * 16 + g * 4) = O[nt][jd];
-            }
-            if (g == 0) {
-                P.part_ml[slot * 2] = m_run[nt];
-                P.part_ml[slot * 2 + 1] = l;
-            }
-        }
+        // ---- move on to the next piece; fetch one more descriptor
+        cb = cb == 2 ? 0 : cb + 1;
+        cp = p1;
+        p1 = p2;
+        p2 = p3;
+        fetch_piece(next_piece++, p3);
     }
 }
 
-// Join the pieces of one (packed row, query head): Eq. (13) -- one denominator over all tokens
+// Join the partial results of one (request, KV head): Eq. (13) -- one denominator over all tokens
 // of the original request.  With piece s holding (m_s, l_s, N_s) where l_s = sum of exp2(score -
 // m_s) and N_s the matching weighted value sum:  O = sum_s 2^(m_s-M) N_s / sum_s 2^(m_s-M) l_s.
-// One wavefront per (row, head); lane (chunk, jp) owns head dims chunk*8 + 2*jp and +1, which the
-// attention kernel left at partial elements (2*jp)*16 + chunk and (2*jp+1)*16 + chunk.
+// One workgroup per task; each wavefront takes (draft row, query head of the group) pairs in turn.
+// Lane (chunk, jp) owns head dims chunk*8 + 2*jp and +1, which the attention kernel left at
+// partial elements (2*jp)*16 + chunk and (2*jp+1)*16 + chunk.  Rows whose pieces were all
+// written directly have no partial result and are left alone.
 constexpr int kJoinWaves = 4;
 
 template <int D>
 __global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinParams P) {
-    const int lane = threadIdx.x & 63;
-    const int64_t w = (int64_t)blockIdx.x * kJoinWaves + (threadIdx.x >> 6);
-    if (w >= (int64_t)P.n_rows * P.n_q_heads) return;
-    const int r = (int)(w / P.n_q_heads), h = (int)(w - (int64_t)r * P.n_q_heads);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int req = P.tasks[2 * blockIdx.x], kvh = P.tasks[2 * blockIdx.x + 1];
     const int G = P.group;
-    const int kvh = h / G, hg = h - kvh * G;
-    const int req = P.row_req[r];
-    const int kb = P.item_begin[req], ke = P.item_begin[req + 1];
+    const int row0 = P.q_offset[req], n_rows = P.q_offset[req + 1] - row0;
+    const int sb = P.strip_begin[req], se = P.strip_begin[req + 1];
     const int chunk = lane & 15, jp = lane >> 4;
     const int e0 = (2 * jp) * 16 + chunk;
     const bool active = chunk * 8 < D;
 
-    float M = kNegBig, den = 0.f, n0 = 0.f, n1 = 0.f;
-#pragma unroll 4
-    for (int k = kb; k < ke; ++k) {
-        const Item it = P.items[k];
-        const int tl = r - it.q_row0;
-        if (tl < 0 || tl >= it.n_q) continue;
-        const int64_t slot = (int64_t)it.part_base + (int64_t)kvh * (it.n_q * G) + tl * G + hg;
-        const float m = P.part_ml[slot * 2], l = P.part_ml[slot * 2 + 1];
-        const float o0 = P.part_o[slot * kPartRow + e0], o1 = P.part_o[slot * kPartRow + e0 + 16];
-        const float Mn = fmaxf(M, m);
-        const float a = fast_exp2(M - Mn), b = fast_exp2(m - Mn);
-        den = den * a + l * b;
-        n0 = n0 * a + o0 * b;
-        n1 = n1 * a + o1 * b;
-        M = Mn;
-    }
-    if (active) {
-        const float inv = 1.0f / den;
-        uint32_t* op = reinterpret_cast<uint32_t*>(P.o + ((int64_t)r * P.n_q_heads + h) * D + chunk * 8 + 2 * jp);
-        *op = pack_bf16(n0 * inv, n1 * inv);
+    for (int pair = wave; pair < n_rows * G; pair += kJoinWaves) {
+        const int t = pair / G, hg = pair - t * G;
+        const int r = row0 + t;
+        float M = kNegBig, den = 0.f, n0 = 0.f, n1 = 0.f;
+        bool any = false;
+        for (int s = sb; s < se; ++s) {
+            const int first = P.ppos[(s * P.n_kv_heads + kvh) * 2], cnt = P.ppos[(s * P.n_kv_heads + kvh) * 2 + 1];
+            const int tl = r - P.pieces[first].q_row0;
+            if (tl < 0 || tl >= P.pieces[first].n_q) continue;
+#pragma unroll 2
+            for (int k = first; k < first + cnt; ++k) {
+                const Piece pc = P.pieces[k];
+                if (pc.head_flags & (kPieceCarryOut | kPieceDirect)) continue;
+                const int64_t slot = (int64_t)pc.out_base + tl * G + hg;
+                const float m = P.part_ml[slot * 2], l = P.part_ml[slot * 2 + 1];
+                const float o0 = P.part_o[slot * kPartRow + e0], o1 = P.part_o[slot * kPartRow + e0 + 16];
+                const float Mn = fmaxf(M, m);
+                const float a = fast_exp2(M - Mn), b = fast_exp2(m - Mn);
+                den = den * a + l * b;
+                n0 = n0 * a + o0 * b;
+                n1 = n1 * a + o1 * b;
+                M = Mn;
+                any = true;
+            }
+        }
+        if (any && active) {
+            const float inv = 1.0f / den;
+            const int h = kvh * G + hg;
+            uint32_t* op = reinterpret_cast<uint32_t*>(P.o + ((int64_t)r * P.n_q_heads + h) * D + chunk * 8 + 2 * jp);
+            *op = pack_bf16(n0 * inv, n1 * inv);
+        }
     }
 }
 
 template <int D>
-static hipError_t launch_attn_d(const AttnParams& base, const int32_t* const order_dev[3], const int32_t n_in_class[3],
-                                const JoinParams& jp, int n_rows, hipStream_t stream, hipEvent_t ev_mid) {
+static const void* attn_kernel_ptr(int cls) {
+    return cls == 0 ? (const void*)verify_attn_kernel<D, 1>
+         : cls == 1 ? (const void*)verify_attn_kernel<D, 2> : (const void*)verify_attn_kernel<D, 4>;
+}
+
+hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
+    const void* fn = head_dim == 128 ? attn_kernel_ptr<128>(cls) : attn_kernel_ptr<64>(cls);
+    int per_cu = 0, dev = 0;
+    hipDeviceProp_t prop;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64, 0);
+    if (e == hipSuccess) e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return e;
+    *n_waves = (per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
+    return hipSuccess;
+}
+
+template <int D>
+static hipError_t launch_attn_d(const AttnParams& base, const Piece* const pieces_dev[3],
+                                const int32_t* const wave_begin_dev[3], const int32_t n_waves[3],
+                                const JoinParams& jp, hipStream_t stream, hipEvent_t ev_mid) {
+    static const int expf = getenv("SPIN_EXP_FLAGS") ? atoi(getenv("SPIN_EXP_FLAGS")) : 0;
     for (int cls = 0; cls < 3; ++cls) {
-        if (n_in_class[cls] == 0) continue;
+        if (n_waves[cls] <= 0) continue;
         AttnParams p = base;
-        p.order = order_dev[cls];
-        const int64_t blocks = (int64_t)n_in_class[cls] * p.n_kv_heads;
-        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-        dim3 grid((unsigned)blocks), block(64);
+        p.pieces = pieces_dev[cls];
+        p.wave_begin = wave_begin_dev[cls];
+        p.exp_flags = expf;
+        dim3 grid((unsigned)n_waves[cls]), block(64);
         if (cls == 0) hipLaunchKernelGGL((verify_attn_kernel<D, 1>), grid, block, 0, stream, p);
         else if (cls == 1) hipLaunchKernelGGL((verify_attn_kernel<D, 2>), grid, block, 0, stream, p);
         else hipLaunchKernelGGL((verify_attn_kernel<D, 4>), grid, block, 0, stream, p);
@@ -294,21 +447,19 @@ static hipError_t launch_attn_d(const AttnParams& base, const int32_t* const ord
         hipError_t e = hipEventRecord(ev_mid, stream);
         if (e != hipSuccess) return e;
     }
-    if (n_rows > 0) {
-        const int64_t waves = (int64_t)n_rows * jp.n_q_heads;
-        dim3 grid((unsigned)((waves + kJoinWaves - 1) / kJoinWaves)), block(64 * kJoinWaves);
-        hipLaunchKernelGGL((join_partials_kernel<D>), grid, block, 0, stream, jp);
+    if (jp.n_tasks > 0) {
+        hipLaunchKernelGGL((join_partials_kernel<D>), dim3(jp.n_tasks), dim3(64 * kJoinWaves), 0, stream, jp);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-hipError_t launch_attn(int head_dim, const AttnParams& base, const int32_t* const order_dev[3],
-                       const int32_t n_in_class[3], const JoinParams& jp, int n_rows, hipStream_t stream,
-                       hipEvent_t ev_mid) {
-    if (head_dim == 128) return launch_attn_d<128>(base, order_dev, n_in_class, jp, n_rows, stream, ev_mid);
-    if (head_dim == 64) return launch_attn_d<64>(base, order_dev, n_in_class, jp, n_rows, stream, ev_mid);
+hipError_t launch_attn(int head_dim, const AttnParams& base, const Piece* const pieces_dev[3],
+                       const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const JoinParams& jp,
+                       hipStream_t stream, hipEvent_t ev_mid) {
+    if (head_dim == 128) return launch_attn_d<128>(base, pieces_dev, wave_begin_dev, n_waves, jp, stream, ev_mid);
+    if (head_dim == 64) return launch_attn_d<64>(base, pieces_dev, wave_begin_dev, n_waves, jp, stream, ev_mid);
     return hipErrorInvalidValue;
 }
 

@@ -20,7 +20,8 @@ inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 struct spin_ctx {
     int device = 0;
     std::string err;
-    int chunk = spin::kDefaultChunk;
+    int waves_override = 0;           // 0: as many wavefronts as the device holds
+    int resident[2][3] = {{0, 0, 0}, {0, 0, 0}};   // resident wavefronts per head dim (64, 128) and tile class
     // reserved capacities and what the last refused call needed
     int64_t cap_req = 0, cap_rows = 0, cap_pages = 0, cap_items = 0, cap_slots = 0;
     int64_t need_req = 0, need_rows = 0, need_pages = 0, need_items = 0, need_slots = 0;
@@ -93,9 +94,13 @@ void free_workspace(spin_ctx* c) {
     for (int s = 0; s < kStages; ++s) c->h_stage[s] = c->d_blob[s] = nullptr;
 }
 
+constexpr int kMaxWaves = 16384;   // wavefronts per launch the staging buffers are sized for
+
+// pieces | per-class wavefront ranges | (strip, head) piece ranges | strip ranges | row offsets | tasks | page table
 size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
-    return align16(items * sizeof(spin::Item)) + 3 * 16 + align16(items * 4) + align16((req + 1) * 4) +
-           align16(rows * 4) + align16(pages * 4) + 64;
+    (void)rows;
+    return align16(items * sizeof(spin::Piece)) + 3 * align16((kMaxWaves + 1) * 4) + 2 * align16(items * 8) +
+           2 * align16((req + 1) * 4) + align16(pages * 4) + 128;
 }
 
 // Next pinned staging buffer; waits until the copy that last used it has left the host.
@@ -157,12 +162,10 @@ int spin_last_error(spin_ctx* ctx, char* buf, size_t n) {
     return SPIN_OK;
 }
 
-int spin_set_chunk(spin_ctx* ctx, int32_t keys_per_item) {
+int spin_set_waves(spin_ctx* ctx, int32_t n_waves) {
     if (!ctx) return SPIN_EINVAL;
-    if (keys_per_item == 0) keys_per_item = spin::kDefaultChunk;
-    if (keys_per_item < 32 || keys_per_item > spin::kMaxChunk || keys_per_item % 32)
-        return fail(ctx, SPIN_EINVAL, "keys per item must be 0 (default) or a multiple of 32 in 32..2048");
-    ctx->chunk = keys_per_item;
+    if (n_waves < 0 || n_waves > kMaxWaves) return fail(ctx, SPIN_EINVAL, "n_waves must be 0 (automatic) or 1..16384");
+    ctx->waves_override = n_waves;
     return SPIN_OK;
 }
 
@@ -248,11 +251,25 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
         rc = spin::check_tiling(table, subs, n_sub, err);
         if (rc) return fail(ctx, rc, err);
     }
-    rc = spin::build_plan(table, subs, n_sub, kv->page_size, group, n_q_heads, ctx->chunk, ctx->plan, err);
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+    // wavefronts per launch: what the device keeps resident for each kernel variant, unless overridden
+    int32_t waves[3];
+    const int di = kv->head_dim == 128 ? 1 : 0;
+    for (int c = 0; c < 3; ++c) {
+        if (ctx->resident[di][c] == 0) {
+            int n = 0;
+            e = spin::attn_resident_waves(kv->head_dim, c, &n);
+            if (e != hipSuccess) return fail_hip(ctx, e, "occupancy query");
+            ctx->resident[di][c] = std::min(n, kMaxWaves);
+        }
+        waves[c] = ctx->waves_override > 0 ? ctx->waves_override : ctx->resident[di][c];
+    }
+    rc = spin::build_plan(table, subs, n_sub, kv->page_size, group, kv->n_kv_heads, waves, ctx->plan, err);
     if (rc) return fail(ctx, rc, err);
     const spin::Plan& plan = ctx->plan;
     const int64_t n_req = table->n_req, n_rows = table->q_offset[n_req], n_pages_used = table->pt_offset[n_req];
-    const int64_t n_items = (int64_t)plan.items.size();
+    const int64_t n_items = (int64_t)plan.pieces.size();
     if (n_req > ctx->cap_req || n_rows > ctx->cap_rows || n_pages_used > ctx->cap_pages || n_items > ctx->cap_items ||
         plan.part_slots > ctx->cap_slots) {
         ctx->need_req = n_req;
@@ -262,35 +279,31 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
         ctx->need_slots = plan.part_slots;
         return fail(ctx, SPIN_ENOSPC, "reserved workspace too small for this batch (see spin_required)");
     }
-    hipError_t e = hipSetDevice(ctx->device);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
     hipStream_t stream = (hipStream_t)hip_stream;
 
-    // ---- stage the tables: [items | order x3 | item_begin | row_req | page_table]
+    // ---- stage the tables
     char* h = nullptr;
     rc = next_stage(ctx, &h);
     if (rc) return rc;
     size_t off = 0;
-    const size_t off_items = off;
-    memcpy(h + off, plan.items.data(), n_items * sizeof(spin::Item));
-    off = align16(off + n_items * sizeof(spin::Item));
-    size_t off_order[3];
-    int32_t n_in_class[3];
+    auto put = [&](const void* src, size_t bytes) {
+        const size_t at = off;
+        if (bytes) memcpy(h + off, src, bytes);
+        off = align16(off + bytes);
+        return at;
+    };
+    const size_t off_pieces = put(plan.pieces.data(), n_items * sizeof(spin::Piece));
+    size_t off_waves[3];
+    int32_t n_waves_launch[3];
     for (int c = 0; c < 3; ++c) {
-        off_order[c] = off;
-        n_in_class[c] = (int32_t)plan.order[c].size();
-        memcpy(h + off, plan.order[c].data(), plan.order[c].size() * 4);
-        off = align16(off + plan.order[c].size() * 4);
+        n_waves_launch[c] = plan.wave_begin[c].empty() ? 0 : (int32_t)plan.wave_begin[c].size() - 1;
+        off_waves[c] = put(plan.wave_begin[c].data(), plan.wave_begin[c].size() * 4);
     }
-    const size_t off_begin = off;
-    memcpy(h + off, plan.item_begin.data(), (n_req + 1) * 4);
-    off = align16(off + (n_req + 1) * 4);
-    const size_t off_rowreq = off;
-    memcpy(h + off, plan.row_req.data(), n_rows * 4);
-    off = align16(off + n_rows * 4);
-    const size_t off_pt = off;
-    memcpy(h + off, table->page_table, n_pages_used * 4);
-    off = align16(off + n_pages_used * 4);
+    const size_t off_ppos = put(plan.ppos.data(), plan.ppos.size() * 4);
+    const size_t off_strips = put(plan.strip_begin.data(), (n_req + 1) * 4);
+    const size_t off_qoff = put(table->q_offset, (n_req + 1) * 4);
+    const size_t off_tasks = put(plan.tasks.data(), plan.tasks.size() * 4);
+    const size_t off_pt = put(table->page_table, n_pages_used * 4);
     if (off > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
     // Upload on the context's own stream so that it runs beside the kernels of earlier calls; the
     // caller's stream only waits for it.  d_blob[slot] is free once the kernels of the call that
@@ -317,11 +330,12 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.k_pool = (const uint16_t*)kv->k_pool;
     ap.v_pool = (const uint16_t*)kv->v_pool;
     ap.q = (const uint16_t*)q_dev;
-    ap.items = (const spin::Item*)(blob + off_items);
-    ap.order = nullptr;
+    ap.pieces = nullptr;
+    ap.wave_begin = nullptr;
     ap.page_table = (const int32_t*)(blob + off_pt);
     ap.part_o = ctx->d_part_o;
     ap.part_ml = ctx->d_part_ml;
+    ap.o = (uint16_t*)o_dev;
     ap.page_stride = kv->page_stride;
     ap.head_stride = kv->head_stride;
     ap.token_stride = kv->token_stride;
@@ -329,22 +343,30 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.n_kv_heads = kv->n_kv_heads;
     ap.group = group;
     ap.page_shift = pshift;
+    ap.exp_flags = 0;
     ap.scale_log2 = scale * 1.4426950408889634f;
-    const int32_t* order_dev[3];
-    for (int c = 0; c < 3; ++c) order_dev[c] = (const int32_t*)(blob + off_order[c]);
+    const spin::Piece* pieces_dev[3];
+    const int32_t* waves_dev[3];
+    for (int c = 0; c < 3; ++c) {
+        pieces_dev[c] = (const spin::Piece*)(blob + off_pieces) + plan.class_piece_begin[c];
+        waves_dev[c] = (const int32_t*)(blob + off_waves[c]);
+    }
     spin::JoinParams jp;
-    jp.items = ap.items;
-    jp.item_begin = (const int32_t*)(blob + off_begin);
-    jp.row_req = (const int32_t*)(blob + off_rowreq);
+    jp.pieces = (const spin::Piece*)(blob + off_pieces);
+    jp.ppos = (const int32_t*)(blob + off_ppos);
+    jp.strip_begin = (const int32_t*)(blob + off_strips);
+    jp.q_offset = (const int32_t*)(blob + off_qoff);
+    jp.tasks = (const int32_t*)(blob + off_tasks);
     jp.part_o = ctx->d_part_o;
     jp.part_ml = ctx->d_part_ml;
     jp.o = (uint16_t*)o_dev;
     jp.n_q_heads = n_q_heads;
+    jp.n_kv_heads = kv->n_kv_heads;
     jp.group = group;
-    jp.n_rows = (int32_t)n_rows;
+    jp.n_tasks = (int32_t)(plan.tasks.size() / 2);
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    e = spin::launch_attn(kv->head_dim, ap, order_dev, n_in_class, jp, (int)n_rows, stream, pe ? pe[1] : nullptr);
+    e = spin::launch_attn(kv->head_dim, ap, pieces_dev, waves_dev, n_waves_launch, jp, stream, pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
     if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     e = hipEventRecord(ctx->ev_done[slot], stream);

@@ -18,30 +18,38 @@ struct AttnParams {
     const uint16_t* k_pool;
     const uint16_t* v_pool;
     const uint16_t* q;
-    const Item* items;
-    const int32_t* order;
+    const Piece* pieces;         // pieces of one column-tile class, in streaming order
+    const int32_t* wave_begin;   // [gridDim.x + 1] pieces of each wavefront
     const int32_t* page_table;
-    float* part_o;     // [slots][kPartRow]
-    float* part_ml;    // [slots][2]: running max (log2 domain), sum
+    float* part_o;               // [slots][kPartRow]
+    float* part_ml;              // [slots][2]: running max (log2 domain), sum
+    uint16_t* o;                 // final rows of pieces flagged direct
     int64_t page_stride, head_stride, token_stride;   // elements
     int32_t n_q_heads, n_kv_heads, group, page_shift;
-    float scale_log2;  // softmax scale * log2(e)
+    int32_t exp_flags;
+    float scale_log2;            // softmax scale * log2(e)
 };
 
 struct JoinParams {
-    const Item* items;
-    const int32_t* item_begin;
-    const int32_t* row_req;
+    const Piece* pieces;         // all classes
+    const int32_t* ppos;         // [n_strips * n_kv_heads][2] first piece and count of each (strip, KV head)
+    const int32_t* strip_begin;  // [n_req + 1]
+    const int32_t* q_offset;     // [n_req + 1]
+    const int32_t* tasks;        // [n_tasks][2] (request, KV head)
     const float* part_o;
     const float* part_ml;
     uint16_t* o;
-    int32_t n_q_heads, group, n_rows;
+    int32_t n_q_heads, n_kv_heads, group, n_tasks;
 };
 
-// ev_mid (may be null) is recorded between the attention kernels and the join kernel.
-hipError_t launch_attn(int head_dim, const AttnParams& base, const int32_t* const order_dev[3],
-                       const int32_t n_in_class[3], const JoinParams& jp, int n_rows, hipStream_t stream,
-                       hipEvent_t ev_mid);
+// Wavefronts of the attention kernel of class `cls` (0, 1, 2) and head dim that fit on the device at once.
+hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves);
+
+// n_waves[c] wavefronts stream the pieces of class c; ev_mid (may be null) is recorded between the
+// attention kernels and the join kernel.
+hipError_t launch_attn(int head_dim, const AttnParams& base, const Piece* const pieces_dev[3],
+                       const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const JoinParams& jp,
+                       hipStream_t stream, hipEvent_t ev_mid);
 
 struct AcceptParams {
     const int32_t* row_off;        // [n_req+1] first draft row of each request (device)

@@ -175,13 +175,13 @@ static void join_along_rows(std::vector<spin_subreq>& r, const spin_req_table* t
 }
 
 int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, int page_size,
-               int group, int n_q_heads, int chunk, Plan& plan, std::string& err) {
+               int group, int n_kv_heads, const int32_t n_waves[3], Plan& plan, std::string& err) {
     if (group < 1 || group > kMaxTileRows) { err = "query heads per KV head must be 1..64"; return SPIN_EUNSUPPORTED; }
+    if (n_kv_heads < 1 || n_kv_heads > kPieceHeadMask) { err = "n_kv_heads out of range"; return SPIN_EUNSUPPORTED; }
     const int max_rows = kMaxTileRows / group;
-    // keys per item: bounded by the chunk and by the page ids one item may cache
-    int64_t page_cap = (int64_t)(kMaxItemPages - 2) * page_size;
-    int C = (int)std::min<int64_t>(std::min(chunk, kMaxChunk), page_cap);
-    C = std::max(C, 1);
+    // blocks one piece may span: bounded by the page ids a piece may cache
+    int64_t window_keys = std::min<int64_t>(2048, (int64_t)(kMaxPiecePages - 2) * page_size);
+    const int window_blocks = (int)std::max<int64_t>(1, window_keys / kBlockKeys);
 
     std::vector<spin_subreq>& rects = plan.rects;
     rects.clear();
@@ -209,60 +209,108 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
         return a.q_begin < b.q_begin;
     });
 
-    plan.items.clear();
-    for (int k = 0; k < 3; ++k) plan.order[k].clear();
-    plan.item_begin.assign(t->n_req + 1, 0);
-    int64_t slots = 0;
+    // ---- strips: rectangles cut into row bands one wavefront tile can hold
+    plan.strips.clear();
+    plan.strip_begin.assign(t->n_req + 1, 0);
+    for (int c = 0; c < 3; ++c) plan.class_blocks[c] = 0;
     for (const spin_subreq& s : rects) {
-        int32_t p = t->prefix_len[s.parent];
+        const int32_t p = t->prefix_len[s.parent];
         for (int32_t qb = s.q_begin; qb < s.q_begin + s.q_len; qb += max_rows) {
-            int32_t ql = std::min(max_rows, s.q_begin + s.q_len - qb);
-            int32_t ke = std::min(s.kv_begin + s.kv_len, p + qb + ql);
-            for (int32_t c = (s.kv_begin / C) * C; c < ke; c += C) {
-                int32_t k0 = std::max(c, s.kv_begin), k1 = std::min(c + C, ke);
-                if (k0 >= k1) continue;
-                Item it;
-                it.parent = s.parent;
-                it.q_row0 = t->q_offset[s.parent] + qb;
-                it.n_q = ql;
-                it.causal0 = p + qb + 1;
-                it.k0 = k0;
-                it.k1 = k1;
-                it.pt_base = t->pt_offset ? t->pt_offset[s.parent] : 0;
-                if (slots + (int64_t)ql * n_q_heads > INT32_MAX) { err = "too many partial results"; return SPIN_ENOSPC; }
-                it.part_base = (int32_t)slots;
-                slots += (int64_t)ql * n_q_heads;
-                plan.items.push_back(it);
-                plan.item_begin[s.parent + 1]++;
+            const int32_t ql = std::min(max_rows, s.q_begin + s.q_len - qb);
+            const int32_t ke = std::min(s.kv_begin + s.kv_len, p + qb + ql);
+            if (s.kv_begin >= ke) continue;
+            const int tiles = (ql * group + 15) / 16;
+            Strip st{s.parent, qb, ql, s.kv_begin, ke, tiles <= 1 ? 0 : (tiles == 2 ? 1 : 2),
+                     (s.kv_begin == 0 && ke == p + qb + ql) ? 1 : 0};
+            plan.strips.push_back(st);
+            plan.strip_begin[s.parent + 1]++;
+            plan.class_blocks[st.cls] += (int64_t)((ke - s.kv_begin + kBlockKeys - 1) / kBlockKeys) * n_kv_heads;
+        }
+    }
+    for (int32_t i = 0; i < t->n_req; ++i) plan.strip_begin[i + 1] += plan.strip_begin[i];
+    const size_t n_strips = plan.strips.size();
+    if ((int64_t)n_strips * n_kv_heads > INT32_MAX / 4) { err = "too many strips"; return SPIN_ENOSPC; }
+
+    // ---- pieces: per class the blocks of all (strip, KV head) pairs form one long sequence (strip,
+    // then head, then block); it is cut into equal shares, one per wavefront.  A wavefront keeps its
+    // accumulators while it stays inside one (strip, head), so only the cuts cost a partial result.
+    plan.pieces.clear();
+    plan.piece_strip.clear();
+    plan.piece_wave.clear();
+    plan.ppos.assign(n_strips * n_kv_heads * 2, 0);
+    plan.need_join.assign((size_t)t->n_req * n_kv_heads, 0);
+    int64_t slots = 0;
+    for (int c = 0; c < 3; ++c) {
+        plan.class_piece_begin[c] = (int32_t)plan.pieces.size();
+        std::vector<int32_t>& wb = plan.wave_begin[c];
+        wb.clear();
+        const int64_t T = plan.class_blocks[c];
+        if (T == 0) continue;
+        const int64_t W = std::max<int64_t>(1, std::min<int64_t>(n_waves[c], T / kMinBlocksPerWave));
+        int64_t wave = 0, pos = 0;
+        wb.push_back(0);
+        for (size_t si = 0; si < n_strips; ++si) {
+            const Strip& st = plan.strips[si];
+            if (st.cls != c) continue;
+            const int32_t nb = (st.k1 - st.k0 + kBlockKeys - 1) / kBlockKeys;
+            const int32_t p = t->prefix_len[st.parent];
+            for (int kvh = 0; kvh < n_kv_heads; ++kvh) {
+                const size_t first = plan.pieces.size();
+                int32_t b = 0;
+                while (b < nb) {
+                    while (wave < W - 1 && pos >= (wave + 1) * T / W) {
+                        ++wave;
+                        wb.push_back((int32_t)(plan.pieces.size() - plan.class_piece_begin[c]));
+                    }
+                    const int64_t seg_end = wave == W - 1 ? T : (wave + 1) * T / W;
+                    const int32_t take = (int32_t)std::min<int64_t>(std::min<int64_t>(nb - b, seg_end - pos), window_blocks);
+                    Piece pc;
+                    pc.head_flags = kvh;
+                    pc.q_row0 = t->q_offset[st.parent] + st.q_begin;
+                    pc.n_q = st.q_len;
+                    pc.causal0 = p + st.q_begin + 1;
+                    pc.k0 = st.k0 + b * kBlockKeys;
+                    pc.k1 = std::min(st.k1, st.k0 + (b + take) * kBlockKeys);
+                    pc.pt_base = t->pt_offset ? t->pt_offset[st.parent] : 0;
+                    pc.out_base = 0;
+                    plan.pieces.push_back(pc);
+                    plan.piece_strip.push_back((int32_t)si);
+                    plan.piece_wave.push_back((int32_t)wave);
+                    b += take;
+                    pos += take;
+                }
+                // flags: runs of pieces held by the same wavefront carry their accumulators along
+                const size_t last = plan.pieces.size();
+                const bool one_wave = plan.piece_wave[first] == plan.piece_wave[last - 1];
+                for (size_t k = first; k < last; ++k) {
+                    Piece& pc = plan.pieces[k];
+                    if (k > first && plan.piece_wave[k - 1] == plan.piece_wave[k]) pc.head_flags |= kPieceCarryIn;
+                    if (k + 1 < last && plan.piece_wave[k + 1] == plan.piece_wave[k]) {
+                        pc.head_flags |= kPieceCarryOut;
+                    } else if (one_wave && st.row_complete) {
+                        pc.head_flags |= kPieceDirect;
+                    } else {
+                        if (slots + (int64_t)st.q_len * group > INT32_MAX) { err = "too many partial results"; return SPIN_ENOSPC; }
+                        pc.out_base = (int32_t)slots;
+                        slots += (int64_t)st.q_len * group;
+                        plan.need_join[(size_t)st.parent * n_kv_heads + kvh] = 1;
+                    }
+                }
+                plan.ppos[(si * n_kv_heads + kvh) * 2] = (int32_t)first;
+                plan.ppos[(si * n_kv_heads + kvh) * 2 + 1] = (int32_t)(last - first);
             }
         }
+        while ((int64_t)wb.size() < W + 1) wb.push_back((int32_t)(plan.pieces.size() - plan.class_piece_begin[c]));
     }
-    for (int32_t i = 0; i < t->n_req; ++i) plan.item_begin[i + 1] += plan.item_begin[i];
+    plan.class_piece_begin[3] = (int32_t)plan.pieces.size();
     plan.part_slots = slots;
-
-    // launch order: per column-tile class, longest items first (counting sort on length)
-    std::vector<int32_t>& tmp = plan.row_req;   // borrowed as scratch before it is filled below
-    for (int cls = 0; cls < 3; ++cls) {
-        tmp.assign(C + 2, 0);
-        for (size_t k = 0; k < plan.items.size(); ++k) {
-            const Item& it = plan.items[k];
-            int tiles = (it.n_q * group + 15) / 16;
-            int c = tiles <= 1 ? 0 : (tiles == 2 ? 1 : 2);
-            if (c == cls) tmp[C - (it.k1 - it.k0) + 1]++;
-        }
-        for (int k = 0; k <= C; ++k) tmp[k + 1] += tmp[k];
-        plan.order[cls].resize(tmp[C + 1]);
-        for (size_t k = 0; k < plan.items.size(); ++k) {
-            const Item& it = plan.items[k];
-            int tiles = (it.n_q * group + 15) / 16;
-            int c = tiles <= 1 ? 0 : (tiles == 2 ? 1 : 2);
-            if (c == cls) plan.order[cls][tmp[C - (it.k1 - it.k0)]++] = (int32_t)k;
-        }
-    }
-    int32_t R = t->n_req ? t->q_offset[t->n_req] : 0;
-    plan.row_req.resize(R);
+    plan.tasks.clear();
     for (int32_t i = 0; i < t->n_req; ++i)
-        for (int32_t r = t->q_offset[i]; r < t->q_offset[i + 1]; ++r) plan.row_req[r] = i;
+        for (int kvh = 0; kvh < n_kv_heads; ++kvh)
+            if (plan.need_join[(size_t)i * n_kv_heads + kvh]) {
+                plan.tasks.push_back(i);
+                plan.tasks.push_back(kvh);
+            }
     return SPIN_OK;
 }
 
@@ -369,28 +417,33 @@ int spin_check_tiling(const spin_req_table* table, const spin_subreq* subs, int3
 }
 
 int spin_schedule(const spin_req_table* table, const spin_subreq* subs, int32_t n_sub, int32_t page_size,
-                  int32_t group, int32_t keys_per_item, spin_subreq* items_out, int32_t cap,
+                  int32_t group, int32_t n_kv_heads, int32_t n_waves, spin_work_piece* out, int32_t cap,
                   int32_t* n_out) {
     std::string err;
-    if (!n_out || cap < 0 || (cap > 0 && !items_out) || page_size < 1 || keys_per_item < 1) return SPIN_EINVAL;
+    if (!n_out || cap < 0 || (cap > 0 && !out) || page_size < 1 || n_waves < 1) return SPIN_EINVAL;
     int rc = spin::validate_table(table, 1, -1, false, err);
     if (rc) return rc;
     if (!table->q_offset && table->n_req > 0) return SPIN_EINVAL;
-    if (subs) {
+    if (subs || n_sub != 0) {
         rc = spin::check_tiling(table, subs, n_sub, err);
         if (rc) return rc;
     }
     spin::Plan plan;
     spin_req_table t = *table;
     t.pt_offset = nullptr;
-    rc = spin::build_plan(&t, subs, n_sub, page_size, group, group, keys_per_item, plan, err);
+    const int32_t waves[3] = {n_waves, n_waves, n_waves};
+    rc = spin::build_plan(&t, subs, n_sub, page_size, group, n_kv_heads, waves, plan, err);
     if (rc) return rc;
-    *n_out = (int32_t)plan.items.size();
-    if ((int64_t)plan.items.size() > cap) return SPIN_ENOSPC;
-    for (size_t k = 0; k < plan.items.size(); ++k) {
-        const spin::Item& it = plan.items[k];
-        int32_t qb = it.q_row0 - table->q_offset[it.parent];
-        items_out[k] = {it.parent, qb, it.n_q, it.k0, it.k1 - it.k0};
+    *n_out = (int32_t)plan.pieces.size();
+    if ((int64_t)plan.pieces.size() > cap) return SPIN_ENOSPC;
+    for (size_t k = 0; k < plan.pieces.size(); ++k) {
+        const spin::Piece& pc = plan.pieces[k];
+        const spin::Strip& st = plan.strips[plan.piece_strip[k]];
+        out[k] = {st.parent, st.q_begin, st.q_len, pc.k0, pc.k1 - pc.k0, pc.head_flags & spin::kPieceHeadMask,
+                  st.cls, plan.piece_wave[k],
+                  ((pc.head_flags & spin::kPieceCarryIn) ? SPIN_PIECE_CARRY_IN : 0) |
+                      ((pc.head_flags & spin::kPieceCarryOut) ? SPIN_PIECE_CARRY_OUT : 0) |
+                      ((pc.head_flags & spin::kPieceDirect) ? SPIN_PIECE_DIRECT : 0)};
     }
     return SPIN_OK;
 }

@@ -25,19 +25,19 @@ def ctx():
     c.close()
 
 
-def hip_attention(ctx, batch, subs=None, scale=0.0, chunk=None):
+def hip_attention(ctx, batch, subs=None, scale=0.0, waves=None):
     t = batch.table
     tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
     out = torch.full_like(batch.q, float("nan"))
-    if chunk is not None:
-        ctx.set_chunk(chunk)
+    if waves is not None:
+        ctx.set_waves(waves)
     try:
         ctx.verify_attn(tab, batch.k_pool, batch.v_pool, batch.q, out, batch.cfg.n_q_heads, subs=subs,
                         softmax_scale=scale)
         torch.cuda.synchronize()
     finally:
-        if chunk is not None:
-            ctx.set_chunk(0)
+        if waves is not None:
+            ctx.set_waves(0)
     return out
 
 
@@ -103,12 +103,13 @@ def test_wide_group_many_rows(ctx):
     assert_close(hip_attention(ctx, b), oracle_attention(b, 0.0), "gqa8 row bands")
 
 
-@pytest.mark.parametrize("chunk", [32, 64, 256, 512, 2048])
-def test_chunk_lengths(ctx, chunk):
-    cfg = make_cfg("chunks", 6, 4, 4, 128)
-    prefix = np.array([5, 100, 640, 1025, 2047, 3000]); draft = np.array([3, 1, 8, 2, 5, 4])
+@pytest.mark.parametrize("waves", [1, 2, 5, 64, 1000, 16384])
+def test_wavefront_counts(ctx, waves):
+    # the same batch cut into 1 ... many shares: everything direct, long carried runs, many partial joins
+    cfg = make_cfg("shares", 6, 4, 4, 128)
+    prefix = np.array([5, 100, 640, 1025, 2047, 5000]); draft = np.array([3, 1, 8, 2, 5, 4])
     b = si.make_verify_batch(cfg, 13, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
-    assert_close(hip_attention(ctx, b, chunk=chunk), oracle_attention(b, 0.0), f"chunk {chunk}")
+    assert_close(hip_attention(ctx, b, waves=waves), oracle_attention(b, 0.0), f"waves {waves}")
 
 
 def test_unit_scale_peaked_softmax(ctx):

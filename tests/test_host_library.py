@@ -121,40 +121,80 @@ def test_check_tiling_accepts_exact_and_rejects_broken():
     assert spin.check_tiling([p], [g], subs) == 0
 
 
-@pytest.mark.parametrize("group,chunk,page", [(1, 64, 16), (1, 256, 16), (8, 1024, 16), (4, 32, 4), (1, 2048, 1)])
-def test_scheduler_items_tile_every_request(group, chunk, page):
-    rng = np.random.default_rng(group * 1000 + chunk)
-    prefix = rng.integers(0, 700, size=7); draft = rng.integers(1, 17, size=7)
+def blocks_of(piece):
+    return -(-int(piece[4]) // 32)
+
+
+@pytest.mark.parametrize("group,n_kv,n_waves,page", [(1, 4, 64, 16), (1, 2, 7, 16), (8, 2, 100, 16), (4, 1, 3, 4),
+                                                     (1, 3, 1000, 1), (3, 2, 16, 16)])
+def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page):
+    rng = np.random.default_rng(group * 1000 + n_waves)
+    prefix = rng.integers(0, 3000, size=7); draft = rng.integers(1, 17, size=7)
     decomps = [None, orc.decompose_q_split(prefix, draft, 4), orc.decompose_kv_split(prefix, draft, 100),
                np.array([(i,) + r for i in range(7) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))])]
     for subs in decomps:
-        items = spin.schedule(prefix, draft, subs, page, group, chunk)
-        assert_exact_tiling(prefix, draft, items)
-        for parent, qb, ql, kb, kl in items:
-            assert ql * group <= 64
-            assert 1 <= kl <= chunk
-            assert (kb + kl - 1) // page - kb // page + 1 <= 136
-            assert kb // chunk == (kb + kl - 1) // chunk or kl <= chunk    # never longer than one chunk
-        # parent-sorted: the join kernel walks a contiguous range per request
-        assert list(items[:, 0]) == sorted(items[:, 0])
+        pcs = spin.schedule(prefix, draft, subs, page, group, n_kv, n_waves)
+        for h in range(n_kv):
+            assert_exact_tiling(prefix, draft, pcs[pcs[:, 5] == h][:, :5])
+        for pc in pcs:
+            parent, qb, ql, kb, kl, kvh, cls, wave, flags = (int(x) for x in pc)
+            assert ql * group <= 64 and cls == (0 if ql * group <= 16 else 1 if ql * group <= 32 else 2)
+            assert kl >= 1 and (kb + kl - 1) // page - kb // page + 1 <= 136
+            assert 0 <= wave < n_waves
+        for cls in range(3):
+            c = pcs[pcs[:, 6] == cls]
+            if len(c) == 0:
+                continue
+            # equal shares: the wavefronts of a class differ by at most one block
+            per_wave = np.zeros(n_waves, dtype=np.int64)
+            for pc in c:
+                per_wave[pc[7]] += blocks_of(pc)
+            used = per_wave[per_wave > 0]
+            assert used.max() - used.min() <= 1
+            # a wavefront's pieces are consecutive in the class's streaming order
+            assert list(c[:, 7]) == sorted(c[:, 7])
+        # flags: CARRY_IN / CARRY_OUT link neighbours of one (rectangle, head) inside one wavefront;
+        # DIRECT only where one wavefront holds a whole rectangle that reaches from key 0 to its causal edge
+        for k, pc in enumerate(pcs):
+            parent, qb, ql, kb, kl, kvh, cls, wave, flags = (int(x) for x in pc)
+            same_prev = k > 0 and tuple(pcs[k - 1][[0, 1, 2, 5, 6, 7]]) == (parent, qb, ql, kvh, cls, wave) \
+                and pcs[k - 1][3] + pcs[k - 1][4] == kb
+            assert bool(flags & spin.PIECE_CARRY_IN) == bool(same_prev)
+            if flags & spin.PIECE_CARRY_IN:
+                assert pcs[k - 1][8] & spin.PIECE_CARRY_OUT
+            if flags & spin.PIECE_DIRECT:
+                chain_start = k
+                while pcs[chain_start][8] & spin.PIECE_CARRY_IN:
+                    chain_start -= 1
+                assert pcs[chain_start][3] == 0 and kb + kl == prefix[parent] + qb + ql
+                assert not (flags & spin.PIECE_CARRY_OUT)
 
 
 def test_scheduler_rejoins_row_bands_sharing_a_prefix():
     # width-4 pieces of a 16-row draft block all start at key 0: they are streamed as one band, so
-    # the item count equals that of the undivided request
+    # the schedule equals that of the undivided request; so does a cut along the keys
     prefix = np.array([1000, 300]); draft = np.array([16, 2])
-    whole = spin.schedule(prefix, draft, None, 16, 1, 256)
-    split = spin.schedule(prefix, draft, orc.decompose_q_split(prefix, draft, 4), 16, 1, 256)
+    whole = spin.schedule(prefix, draft, None, 16, 1, 2, 8)
+    split = spin.schedule(prefix, draft, orc.decompose_q_split(prefix, draft, 4), 16, 1, 2, 8)
     np.testing.assert_array_equal(whole, split)
-    kv = spin.schedule(prefix, draft, orc.decompose_kv_split(prefix, draft, 100), 16, 1, 256)
+    kv = spin.schedule(prefix, draft, orc.decompose_kv_split(prefix, draft, 100), 16, 1, 2, 8)
     np.testing.assert_array_equal(whole, kv)
+
+
+def test_scheduler_single_wave_writes_everything_directly():
+    prefix = np.array([100, 5000, 0]); draft = np.array([3, 8, 1])
+    pcs = spin.schedule(prefix, draft, None, 16, 1, 2, 1)
+    ends = pcs[(pcs[:, 8] & spin.PIECE_CARRY_OUT) == 0]
+    assert len(ends) == 3 * 2 and (ends[:, 8] & spin.PIECE_DIRECT).all()
+    # the long request is cut into page-id windows that carry their accumulators along
+    assert (pcs[pcs[:, 0] == 1][:, 4] <= 2048).all() and (pcs[:, 8] & spin.PIECE_CARRY_IN).any()
 
 
 def test_scheduler_rejects_inexact_tiling():
     prefix = np.array([40]); draft = np.array([4])
     subs = orc.decompose_kv_split(prefix, draft, 16)[:-1]
     with pytest.raises(spin.SpinError) as e:
-        spin.schedule(prefix, draft, subs, 16, 1, 256)
+        spin.schedule(prefix, draft, subs, 16, 1, 1, 8)
     assert e.value.code == spin.ETABLE
 
 
