@@ -356,7 +356,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 // Join the partial results of one (request, KV head): Eq. (13) -- one denominator over all tokens
 // of the original request.  With piece s holding (m_s, l_s, N_s) where l_s = sum of exp2(score -
 // m_s) and N_s the matching weighted value sum:  O = sum_s 2^(m_s-M) N_s / sum_s 2^(m_s-M) l_s.
-// One workgroup per task; each wavefront takes (draft row, query head of the group) pairs in turn.
+// One wavefront per (task, draft row, query head of the group).
 // Lane (chunk, jp) owns head dims chunk*8 + 2*jp and +1, which the attention kernel left at
 // partial elements (2*jp)*16 + chunk and (2*jp+1)*16 + chunk.  Rows whose pieces were all
 // written directly have no partial result and are left alone.
@@ -373,7 +373,9 @@ __global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinPara
     const int e0 = (2 * jp) * 16 + chunk;
     const bool active = chunk * 8 < D;
 
-    for (int pair = wave; pair < n_rows * G; pair += kJoinWaves) {
+    {
+        const int pair = blockIdx.y * kJoinWaves + wave;
+        if (pair >= n_rows * G) return;
         const int t = pair / G, hg = pair - t * G;
         const int r = row0 + t;
         float M = kNegBig, den = 0.f, n0 = 0.f, n1 = 0.f;
@@ -448,7 +450,8 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         if (e != hipSuccess) return e;
     }
     if (jp.n_tasks > 0) {
-        hipLaunchKernelGGL((join_partials_kernel<D>), dim3(jp.n_tasks), dim3(64 * kJoinWaves), 0, stream, jp);
+        const int pair_groups = (jp.max_pairs + kJoinWaves - 1) / kJoinWaves;
+        hipLaunchKernelGGL((join_partials_kernel<D>), dim3(jp.n_tasks, pair_groups), dim3(64 * kJoinWaves), 0, stream, jp);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

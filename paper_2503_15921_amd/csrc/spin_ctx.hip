@@ -364,6 +364,9 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     jp.n_kv_heads = kv->n_kv_heads;
     jp.group = group;
     jp.n_tasks = (int32_t)(plan.tasks.size() / 2);
+    int32_t max_draft = 1;
+    for (int64_t i = 0; i < n_req; ++i) max_draft = std::max(max_draft, table->draft_len[i]);
+    jp.max_pairs = max_draft * group;
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     e = spin::launch_attn(kv->head_dim, ap, pieces_dev, waves_dev, n_waves_launch, jp, stream, pe ? pe[1] : nullptr);

@@ -40,6 +40,7 @@ struct JoinParams {
     const float* part_ml;
     uint16_t* o;
     int32_t n_q_heads, n_kv_heads, group, n_tasks;
+    int32_t max_pairs;           // largest (draft rows x group) of any request
 };
 
 // Wavefronts of the attention kernel of class `cls` (0, 1, 2) and head dim that fit on the device at once.
