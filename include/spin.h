@@ -159,8 +159,10 @@ int spin_check_tiling(const spin_req_table* table, const spin_subreq* subs, int3
 /* The scheduler's view of a batch, for inspection and tests (host only).  The attention kernel
  * runs a fixed number of wavefronts per launch; the key blocks (32 keys) of all (rectangle, KV
  * head) pairs form one sequence that is cut into equal shares, one per wavefront.  A piece is one
- * run of blocks of one (rectangle, KV head) inside one share.  `tile_class` 0/1/2 = launches for
- * up to 16/32/64 (draft row x query head) rows; `wave` numbers the wavefronts of a class.
+ * run of blocks of one (rectangle, KV head) inside one share.  The last part of the sequence is
+ * cut into small chunks instead, which wavefronts take from a queue as they finish their share
+ * (QUEUED).  `tile_class` 0/1/2 = launches for up to 16/32/64 (draft row x query head) rows;
+ * `wave` numbers the shares of a class: first the per-wavefront ones, then the queued chunks.
  * Flags: CARRY_IN = continues the wavefront's previous piece, CARRY_OUT = continued by its next
  * piece (nothing written), DIRECT = ends a rectangle that one wavefront held entirely and that
  * holds every key its rows may see: final rows are written, no partial result.  `group` =
@@ -169,6 +171,7 @@ int spin_check_tiling(const spin_req_table* table, const spin_subreq* subs, int3
 #define SPIN_PIECE_CARRY_IN 1
 #define SPIN_PIECE_CARRY_OUT 2
 #define SPIN_PIECE_DIRECT 4
+#define SPIN_PIECE_QUEUED 8
 typedef struct spin_work_piece {
     int32_t parent, q_begin, q_len, kv_begin, kv_len;
     int32_t kv_head, tile_class, wave, flags;

@@ -47,7 +47,7 @@ class WorkPiece(C.Structure):
                                           "tile_class", "wave", "flags")]
 
 
-PIECE_CARRY_IN, PIECE_CARRY_OUT, PIECE_DIRECT = 1, 2, 4
+PIECE_CARRY_IN, PIECE_CARRY_OUT, PIECE_DIRECT, PIECE_QUEUED = 1, 2, 4, 8
 
 
 class DecompParams(C.Structure):

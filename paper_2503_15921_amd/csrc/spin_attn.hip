@@ -72,8 +72,10 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     const int G = P.group;
     const int pshift = P.page_shift;
     const int pmask = (1 << pshift) - 1;
-    const int pc_begin = P.wave_begin[blockIdx.x], pc_end = P.wave_begin[blockIdx.x + 1];
-    if (pc_begin >= pc_end) return;
+    // A wavefront first streams its own share, then takes queued chunks until none are left.
+    for (int share = blockIdx.x;;) {
+    const int pc_begin = P.wave_begin[share], pc_end = P.wave_begin[share + 1];
+    if (pc_begin < pc_end) {   // (shares are never empty; an empty one would have no valid row to fetch)
 
     // Descriptor r of this wavefront's share (k0 == k1 when the share is exhausted).  Read through
     // the constant address space: the descriptors are never written by this kernel, which lets the
@@ -351,6 +353,15 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
         p2 = p3;
         fetch_piece(next_piece++, p3);
     }
+    }
+    if (P.n_queued == 0) break;
+    int next = 0;
+    if (lane == 0) next = atomicAdd(P.queue, 1);
+    next = __builtin_amdgcn_readfirstlane(next);
+    if (next >= P.n_queued) break;
+    share = gridDim.x + next;
+    __syncthreads();
+    }
 }
 
 // Join the partial results of one (request, KV head): Eq. (13) -- one denominator over all tokens
@@ -430,13 +441,16 @@ hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
 template <int D>
 static hipError_t launch_attn_d(const AttnParams& base, const Piece* const pieces_dev[3],
                                 const int32_t* const wave_begin_dev[3], const int32_t n_waves[3],
-                                const JoinParams& jp, hipStream_t stream, hipEvent_t ev_mid) {
+                                const int32_t n_queued[3], int32_t* queues_dev, const JoinParams& jp,
+                                hipStream_t stream, hipEvent_t ev_mid) {
     static const int expf = getenv("SPIN_EXP_FLAGS") ? atoi(getenv("SPIN_EXP_FLAGS")) : 0;
     for (int cls = 0; cls < 3; ++cls) {
         if (n_waves[cls] <= 0) continue;
         AttnParams p = base;
         p.pieces = pieces_dev[cls];
         p.wave_begin = wave_begin_dev[cls];
+        p.queue = queues_dev + cls;
+        p.n_queued = n_queued[cls];
         p.exp_flags = expf;
         dim3 grid((unsigned)n_waves[cls]), block(64);
         if (cls == 0) hipLaunchKernelGGL((verify_attn_kernel<D, 1>), grid, block, 0, stream, p);
@@ -459,10 +473,12 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
 }
 
 hipError_t launch_attn(int head_dim, const AttnParams& base, const Piece* const pieces_dev[3],
-                       const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const JoinParams& jp,
-                       hipStream_t stream, hipEvent_t ev_mid) {
-    if (head_dim == 128) return launch_attn_d<128>(base, pieces_dev, wave_begin_dev, n_waves, jp, stream, ev_mid);
-    if (head_dim == 64) return launch_attn_d<64>(base, pieces_dev, wave_begin_dev, n_waves, jp, stream, ev_mid);
+                       const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
+                       int32_t* queues_dev, const JoinParams& jp, hipStream_t stream, hipEvent_t ev_mid) {
+    if (head_dim == 128)
+        return launch_attn_d<128>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid);
+    if (head_dim == 64)
+        return launch_attn_d<64>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid);
     return hipErrorInvalidValue;
 }
 

@@ -99,7 +99,8 @@ constexpr int kMaxWaves = 16384;   // wavefronts per launch the staging buffers 
 // pieces | per-class wavefront ranges | (strip, head) piece ranges | strip ranges | row offsets | tasks | page table
 size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
     (void)rows;
-    return align16(items * sizeof(spin::Piece)) + 3 * align16((kMaxWaves + 1) * 4) + 2 * align16(items * 8) +
+    // every share holds at least one piece, so there are at most `items` share boundaries in all
+    return align16(items * sizeof(spin::Piece)) + align16(items * 4) + 3 * 32 + 2 * align16(items * 8) +
            2 * align16((req + 1) * 4) + align16(pages * 4) + 128;
 }
 
@@ -294,11 +295,15 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     };
     const size_t off_pieces = put(plan.pieces.data(), n_items * sizeof(spin::Piece));
     size_t off_waves[3];
-    int32_t n_waves_launch[3];
+    int32_t n_waves_launch[3], n_queued[3];
     for (int c = 0; c < 3; ++c) {
-        n_waves_launch[c] = plan.wave_begin[c].empty() ? 0 : (int32_t)plan.wave_begin[c].size() - 1;
+        const int32_t n_shares = plan.wave_begin[c].empty() ? 0 : (int32_t)plan.wave_begin[c].size() - 1;
+        n_waves_launch[c] = plan.n_static[c];
+        n_queued[c] = n_shares - plan.n_static[c];
         off_waves[c] = put(plan.wave_begin[c].data(), plan.wave_begin[c].size() * 4);
     }
+    const int32_t zero_queues[4] = {0, 0, 0, 0};   // the chunk queues start at zero with every upload
+    const size_t off_queues = put(zero_queues, sizeof zero_queues);
     const size_t off_ppos = put(plan.ppos.data(), plan.ppos.size() * 4);
     const size_t off_strips = put(plan.strip_begin.data(), (n_req + 1) * 4);
     const size_t off_qoff = put(table->q_offset, (n_req + 1) * 4);
@@ -332,6 +337,8 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.q = (const uint16_t*)q_dev;
     ap.pieces = nullptr;
     ap.wave_begin = nullptr;
+    ap.queue = nullptr;
+    ap.n_queued = 0;
     ap.page_table = (const int32_t*)(blob + off_pt);
     ap.part_o = ctx->d_part_o;
     ap.part_ml = ctx->d_part_ml;
@@ -369,7 +376,8 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     jp.max_pairs = max_draft * group;
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    e = spin::launch_attn(kv->head_dim, ap, pieces_dev, waves_dev, n_waves_launch, jp, stream, pe ? pe[1] : nullptr);
+    e = spin::launch_attn(kv->head_dim, ap, pieces_dev, waves_dev, n_waves_launch, n_queued, (int32_t*)(blob + off_queues),
+                          jp, stream, pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
     if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     e = hipEventRecord(ctx->ev_done[slot], stream);

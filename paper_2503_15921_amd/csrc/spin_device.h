@@ -19,7 +19,9 @@ struct AttnParams {
     const uint16_t* v_pool;
     const uint16_t* q;
     const Piece* pieces;         // pieces of one column-tile class, in streaming order
-    const int32_t* wave_begin;   // [gridDim.x + 1] pieces of each wavefront
+    const int32_t* wave_begin;   // [n_shares + 1] pieces of each share: gridDim.x per-wavefront shares, then queued chunks
+    int32_t* queue;              // next queued chunk to hand out (zero at launch)
+    int32_t n_queued;
     const int32_t* page_table;
     float* part_o;               // [slots][kPartRow]
     float* part_ml;              // [slots][2]: running max (log2 domain), sum
@@ -49,8 +51,8 @@ hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves);
 // n_waves[c] wavefronts stream the pieces of class c; ev_mid (may be null) is recorded between the
 // attention kernels and the join kernel.
 hipError_t launch_attn(int head_dim, const AttnParams& base, const Piece* const pieces_dev[3],
-                       const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const JoinParams& jp,
-                       hipStream_t stream, hipEvent_t ev_mid);
+                       const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
+                       int32_t* queues_dev, const JoinParams& jp, hipStream_t stream, hipEvent_t ev_mid);
 
 struct AcceptParams {
     const int32_t* row_off;        // [n_req+1] first draft row of each request (device)

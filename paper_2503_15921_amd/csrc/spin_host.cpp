@@ -212,7 +212,7 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
     // ---- strips: rectangles cut into row bands one wavefront tile can hold
     plan.strips.clear();
     plan.strip_begin.assign(t->n_req + 1, 0);
-    for (int c = 0; c < 3; ++c) plan.class_blocks[c] = 0;
+    for (int c = 0; c < 3; ++c) plan.class_blocks[c] = 0, plan.n_static[c] = 0;
     for (const spin_subreq& s : rects) {
         const int32_t p = t->prefix_len[s.parent];
         for (int32_t qb = s.q_begin; qb < s.q_begin + s.q_len; qb += max_rows) {
@@ -247,6 +247,23 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
         const int64_t T = plan.class_blocks[c];
         if (T == 0) continue;
         const int64_t W = std::max<int64_t>(1, std::min<int64_t>(n_waves[c], T / kMinBlocksPerWave));
+        // Share boundaries.  The first part of the sequence is cut into W equal shares, one per
+        // wavefront.  Wavefronts do not all stream at the same speed, so the last part is cut into
+        // small chunks that wavefronts take from a queue as they finish (sizes shrink towards the end).
+        std::vector<int64_t>& bounds = plan.bounds;
+        bounds.clear();
+        const int64_t T_dyn = (W >= kMinDynamicWaves && T / W >= kMinBlocksForQueue) ? T * kDynamicPercent / 100 : 0;
+        const int64_t T_static = T - T_dyn;
+        for (int64_t w = 1; w <= W; ++w) bounds.push_back(w * T_static / W);
+        plan.n_static[c] = (int32_t)W;
+        for (int64_t at = T_static; at < T;) {
+            const int64_t left = T - at;
+            const int64_t chunk = std::min<int64_t>(left, std::max<int64_t>(kMinChunkBlocks, std::min<int64_t>(kMaxChunkBlocks, left / W)));
+            at += chunk;
+            bounds.push_back(at);
+        }
+        const int64_t n_shares = (int64_t)bounds.size();
+        if (n_shares > INT32_MAX / 2) { err = "too many shares"; return SPIN_ENOSPC; }
         int64_t wave = 0, pos = 0;
         wb.push_back(0);
         for (size_t si = 0; si < n_strips; ++si) {
@@ -258,11 +275,11 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
                 const size_t first = plan.pieces.size();
                 int32_t b = 0;
                 while (b < nb) {
-                    while (wave < W - 1 && pos >= (wave + 1) * T / W) {
+                    while (wave < n_shares - 1 && pos >= bounds[wave]) {
                         ++wave;
                         wb.push_back((int32_t)(plan.pieces.size() - plan.class_piece_begin[c]));
                     }
-                    const int64_t seg_end = wave == W - 1 ? T : (wave + 1) * T / W;
+                    const int64_t seg_end = bounds[wave];
                     const int32_t take = (int32_t)std::min<int64_t>(std::min<int64_t>(nb - b, seg_end - pos), window_blocks);
                     Piece pc;
                     pc.head_flags = kvh;
@@ -300,7 +317,7 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
                 plan.ppos[(si * n_kv_heads + kvh) * 2 + 1] = (int32_t)(last - first);
             }
         }
-        while ((int64_t)wb.size() < W + 1) wb.push_back((int32_t)(plan.pieces.size() - plan.class_piece_begin[c]));
+        while ((int64_t)wb.size() < n_shares + 1) wb.push_back((int32_t)(plan.pieces.size() - plan.class_piece_begin[c]));
     }
     plan.class_piece_begin[3] = (int32_t)plan.pieces.size();
     plan.part_slots = slots;
@@ -443,7 +460,8 @@ int spin_schedule(const spin_req_table* table, const spin_subreq* subs, int32_t 
                   st.cls, plan.piece_wave[k],
                   ((pc.head_flags & spin::kPieceCarryIn) ? SPIN_PIECE_CARRY_IN : 0) |
                       ((pc.head_flags & spin::kPieceCarryOut) ? SPIN_PIECE_CARRY_OUT : 0) |
-                      ((pc.head_flags & spin::kPieceDirect) ? SPIN_PIECE_DIRECT : 0)};
+                      ((pc.head_flags & spin::kPieceDirect) ? SPIN_PIECE_DIRECT : 0) |
+                      (plan.piece_wave[k] >= plan.n_static[st.cls] ? SPIN_PIECE_QUEUED : 0)};
     }
     return SPIN_OK;
 }

@@ -21,6 +21,13 @@ constexpr int kBlockKeys = 32;
 constexpr int kMaxPiecePages = 136;
 // A wavefront is given at least this many blocks before another wavefront is used.
 constexpr int kMinBlocksPerWave = 4;
+// Share of the blocks (percent) that is handed out from a queue at the end instead of up front, the
+// size range of the queued chunks in blocks, and the launch and share sizes from which queueing is used.
+constexpr int kDynamicPercent = 10;
+constexpr int kMinChunkBlocks = 16;
+constexpr int kMaxChunkBlocks = 32;
+constexpr int kMinDynamicWaves = 64;
+constexpr int kMinBlocksForQueue = 192;   // blocks per wavefront below which queueing does not pay
 
 constexpr int32_t kPieceHeadMask = 0xffff;
 constexpr int32_t kPieceCarryIn = 1 << 16;   // accumulators continue from the wavefront's previous piece
@@ -55,7 +62,10 @@ struct Plan {
     std::vector<int32_t> piece_strip;     // strip of each piece
     std::vector<int32_t> piece_wave;      // wavefront (within its class) of each piece
     int32_t class_piece_begin[4] = {0, 0, 0, 0};
-    std::vector<int32_t> wave_begin[3];   // [n_waves+1] pieces (index within the class) of each wavefront
+    std::vector<int32_t> wave_begin[3];   // [n_shares+1] pieces (index within the class) of each share:
+                                          // first the n_static per-wavefront shares, then the queued chunks
+    int32_t n_static[3] = {0, 0, 0};
+    std::vector<int64_t> bounds;
     std::vector<int32_t> ppos;            // [n_strips * n_kv_heads][2]: first piece (global index) and count
     std::vector<int32_t> tasks;           // [n_tasks][2]: (request, KV head) pairs that have partial results to join
     int64_t part_slots = 0;

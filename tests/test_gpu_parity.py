@@ -112,6 +112,17 @@ def test_wavefront_counts(ctx, waves):
     assert_close(hip_attention(ctx, b, waves=waves), oracle_attention(b, 0.0), f"waves {waves}")
 
 
+def test_queued_tail_of_long_batch(ctx):
+    # long enough that the scheduler hands the last tenth of the blocks out from its queue
+    import paper_2503_15921_amd as spin
+    cfg = make_cfg("queued", 6, 8, 8, 128)
+    prefix = np.array([8100, 9000, 7000, 8500, 9500, 8000]); draft = np.array([4, 8, 1, 6, 2, 5])
+    pcs = spin.schedule(prefix, draft, None, 16, 1, 8, 64)
+    assert (pcs[:, 8] & spin.PIECE_QUEUED).any()
+    b = si.make_verify_batch(cfg, 21, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
+    assert_close(hip_attention(ctx, b, waves=64), oracle_attention(b, 0.0), "queued tail")
+
+
 def test_unit_scale_peaked_softmax(ctx):
     # the literal Eq. (2) (no 1/sqrt(d)): scores ~ N(0, d), softmax dominated by a few keys, |O| ~ 1
     cfg = make_cfg("peaked", 5, 4, 4, 128)

@@ -125,11 +125,12 @@ def blocks_of(piece):
     return -(-int(piece[4]) // 32)
 
 
-@pytest.mark.parametrize("group,n_kv,n_waves,page", [(1, 4, 64, 16), (1, 2, 7, 16), (8, 2, 100, 16), (4, 1, 3, 4),
-                                                     (1, 3, 1000, 1), (3, 2, 16, 16)])
-def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page):
+@pytest.mark.parametrize("group,n_kv,n_waves,page,top", [(1, 4, 64, 16, 3000), (1, 2, 7, 16, 3000), (8, 2, 100, 16, 3000),
+                                                         (4, 1, 3, 4, 3000), (1, 3, 1000, 1, 3000), (3, 2, 16, 16, 3000),
+                                                         (1, 8, 64, 16, 30000)])
+def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page, top):
     rng = np.random.default_rng(group * 1000 + n_waves)
-    prefix = rng.integers(0, 3000, size=7); draft = rng.integers(1, 17, size=7)
+    prefix = rng.integers(0, top, size=7); draft = rng.integers(1, 17, size=7)
     decomps = [None, orc.decompose_q_split(prefix, draft, 4), orc.decompose_kv_split(prefix, draft, 100),
                np.array([(i,) + r for i in range(7) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))])]
     for subs in decomps:
@@ -140,18 +141,25 @@ def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page
             parent, qb, ql, kb, kl, kvh, cls, wave, flags = (int(x) for x in pc)
             assert ql * group <= 64 and cls == (0 if ql * group <= 16 else 1 if ql * group <= 32 else 2)
             assert kl >= 1 and (kb + kl - 1) // page - kb // page + 1 <= 136
-            assert 0 <= wave < n_waves
+            assert wave >= 0
         for cls in range(3):
             c = pcs[pcs[:, 6] == cls]
             if len(c) == 0:
                 continue
-            # equal shares: the wavefronts of a class differ by at most one block
-            per_wave = np.zeros(n_waves, dtype=np.int64)
+            # equal shares: the wavefronts of a class differ by at most one block; queued chunks
+            # (handed out at run time) come after them and hold 1..64 blocks
+            per_share = np.zeros(int(c[:, 7].max()) + 1, dtype=np.int64)
             for pc in c:
-                per_wave[pc[7]] += blocks_of(pc)
-            used = per_wave[per_wave > 0]
-            assert used.max() - used.min() <= 1
-            # a wavefront's pieces are consecutive in the class's streaming order
+                per_share[pc[7]] += blocks_of(pc)
+            queued = np.zeros(len(per_share), dtype=bool)
+            queued[c[(c[:, 8] & spin.PIECE_QUEUED) != 0][:, 7]] = True
+            static = per_share[~queued]
+            assert len(static) <= n_waves and static.min() >= 1 and static.max() - static.min() <= 1
+            if queued.any():
+                assert queued[len(static):].all() and n_waves >= 64
+                assert per_share[queued].min() >= 1 and per_share[queued].max() <= 32
+                assert static.min() >= 150 and 0.05 < per_share[queued].sum() / per_share.sum() < 0.15
+            # a share's pieces are consecutive in the class's streaming order
             assert list(c[:, 7]) == sorted(c[:, 7])
         # flags: CARRY_IN / CARRY_OUT link neighbours of one (rectangle, head) inside one wavefront;
         # DIRECT only where one wavefront holds a whole rectangle that reaches from key 0 to its causal edge
