@@ -38,30 +38,30 @@ def cpu_baseline(cfg, batch, ab, budget_s=20.0):
     total_cells = float((n_tok * cfg.n_q_heads).sum())
     kb, vb, qb = si.bf16_bits(batch.k_pool), si.bf16_bits(batch.v_pool), si.bf16_bits(batch.q)
     scale = 1.0 / math.sqrt(cfg.head_dim)
-    order = rng.permutation(t.n_req)
     done_cells, t_attn, n_pairs = 0.0, 0.0, 0
-    for i in order:
+    while t_attn < budget_s * 0.6 and n_pairs < t.n_req * cfg.n_q_heads:
+        i = int(rng.integers(t.n_req))
         h = int(rng.integers(cfg.n_q_heads))
         t0 = time.perf_counter()
         orc.verify_attention(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, cfg.page_size,
-                             qb, kb, vb, cfg.n_q_heads, cfg.n_kv_heads, scale, requests=[int(i)], heads=[h])
+                             qb, kb, vb, cfg.n_q_heads, cfg.n_kv_heads, scale, requests=[i], heads=[h])
         t_attn += time.perf_counter() - t0
         done_cells += float(n_tok[i])
         n_pairs += 1
-        if t_attn > budget_s * 0.6:
-            break
     attn_full = t_attn * total_cells / done_cells
-    # acceptance on the first requests until the budget is used
-    nreq = 0
-    rows = 0
-    while nreq < t.n_req and rows < 48:
-        rows += int(t.draft_len[nreq]); nreq += 1
-    tl = ab.target_logits[: rows + nreq].cpu().numpy()
-    dl = ab.draft_logits[:rows].cpu().numpy()
-    t0 = time.perf_counter()
-    orc.accept_rejection(t.draft_len[:nreq], ab.draft_tokens[:rows].cpu().numpy(), tl, dl,
-                         ab.u_accept[:rows].cpu().numpy(), ab.u_sample[:nreq].cpu().numpy())
-    t_acc = time.perf_counter() - t0
+    # acceptance: requests in order until the rest of the budget is used
+    nreq, t_acc = 0, 0.0
+    tl_all, dl_all = ab.target_logits, ab.draft_logits
+    while nreq < t.n_req and t_acc < budget_s * 0.3:
+        r0, r1 = int(t.q_offset[nreq]), int(t.q_offset[nreq + 1])
+        tl = tl_all[r0 + nreq: r1 + nreq + 1].cpu().numpy()
+        dl = dl_all[r0:r1].cpu().numpy()
+        toks = ab.draft_tokens[r0:r1].cpu().numpy()
+        ua = ab.u_accept[r0:r1].cpu().numpy(); us = ab.u_sample[nreq:nreq + 1].cpu().numpy()
+        t0 = time.perf_counter()
+        orc.accept_rejection(t.draft_len[nreq:nreq + 1], toks, tl, dl, ua, us)
+        t_acc += time.perf_counter() - t0
+        nreq += 1
     acc_full = t_acc * t.n_req / nreq
     value = t.n_rows / (attn_full + acc_full)
     return {"value": value, "unit": "verified draft tokens/s", "cores": int(cores), "kind": "oracle",
