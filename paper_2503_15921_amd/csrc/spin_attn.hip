@@ -43,6 +43,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr float kNegBig = -1.0e30f;   // running-max start: finite, so (m_old - m_new) is never NaN
+constexpr float kSlack = 6.0f;        // log2 of how far a score may exceed the exponent reference (grouped kernel)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -55,6 +56,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // and streams measurably faster from HBM on this part.
 __device__ __forceinline__ u32x4 stream_load(const uint16_t* p) {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+// the same from a wavefront-uniform base plus a 32-bit per-lane byte offset (scalar base + vector offset addressing)
+__device__ __forceinline__ u32x4 stream_load(const char* base, uint32_t byte_off) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + byte_off));
 }
 
 template <int D, int NT>
@@ -128,18 +133,48 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
         const int pg = sPT[buf][(key >> pshift) - pg0];
         return pool + (int64_t)pg * P.page_stride + head_off + (int64_t)(key & pmask) * P.token_stride;
     };
+    // With 16-token pages whose rows are contiguous (token_stride == D), a full 32-key block that starts
+    // on a page boundary is exactly two page-head tiles: two wavefront-uniform base addresses plus
+    // constant per-lane offsets, no per-lane address arithmetic.  Anything else takes the general path.
+    const bool tile_layout = pshift == 4 && P.token_stride == D;
+    auto page_bases = [&](const uint16_t* pool, int buf, int pg0, int64_t head_off, int kb, const char*& a, const char*& b) {
+        const int pi = (kb >> 4) - pg0;
+        const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][pi]);
+        const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][pi + 1]);
+        a = (const char*)(pool + (int64_t)pga * P.page_stride + head_off);
+        b = (const char*)(pool + (int64_t)pgb * P.page_stride + head_off);
+    };
     auto load_k = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
+        if (tile_layout && !(kb & 31) && kb + 32 <= k1) {
+            const char *a, *b;
+            page_bases(P.k_pool, buf, pg0, head_off, kb, a, b);
+            constexpr int KPI = 64 / DCH;            // keys per load instruction
 #pragma unroll
-        for (int i = 0; i < KLOADS; ++i) {
-            const int f = i * 64 + lane;
-            Kr[i] = stream_load(row_ptr(P.k_pool, buf, pg0, k1, head_off, kb + f / DCH) + (f % DCH) * 8);
+            for (int i = 0; i < KLOADS; ++i) {
+                const int key = i * KPI;             // first key of this instruction within the block
+                Kr[i] = stream_load(key < 16 ? a : b, (uint32_t)((key & 15) * D * 2 + lane * 16));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < KLOADS; ++i) {
+                const int f = i * 64 + lane;
+                Kr[i] = stream_load(row_ptr(P.k_pool, buf, pg0, k1, head_off, kb + f / DCH) + (f % DCH) * 8);
+            }
         }
     };
     auto load_v = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
+        if (tile_layout && !(kb & 31) && kb + 32 <= k1) {
+            const char *a, *b;
+            page_bases(P.v_pool, buf, pg0, head_off, kb, a, b);
+            const uint32_t lo = (uint32_t)(g * 4 * D * 2 + (m16 % DCH) * 16);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int kl = (j >> 2) * 16 + g * 4 + (j & 3);
-            Vr[j] = stream_load(row_ptr(P.v_pool, buf, pg0, k1, head_off, kb + kl) + (m16 % DCH) * 8);
+            for (int j = 0; j < 8; ++j) Vr[j] = stream_load(j < 4 ? a : b, lo + (uint32_t)((j & 3) * D * 2));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int kl = (j >> 2) * 16 + g * 4 + (j & 3);
+                Vr[j] = stream_load(row_ptr(P.v_pool, buf, pg0, k1, head_off, kb + kl) + (m16 % DCH) * 8);
+            }
         }
     };
 
@@ -231,9 +266,9 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) S[t][nt] = f32x4{0, 0, 0, 0};
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int c = 0; c < KCALLS; ++c)      // the two tiles alternate, so consecutive MFMAs are independent
 #pragma unroll
-                for (int c = 0; c < KCALLS; ++c) {
+                for (int t = 0; t < 2; ++t) {
                     const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sK[(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
@@ -364,6 +399,288 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     }
 }
 
+// Grouped-query variant: a workgroup of NW wavefronts shares one K/V stream.  With G query heads
+// per KV head a strip has up to 64 (draft row x query head) rows; wavefront w owns row tile w (16
+// rows), so the per-block work of all rows runs on NW SIMDs at once while every K/V byte is
+// fetched from HBM once.  A block is 32*NW keys: each wavefront fetches its own 32 keys of it
+// (K and V both as 1 KiB-contiguous loads), parks them in LDS, and after a barrier every
+// wavefront reads all NW sub-blocks: K in MFMA operand shape, V as eight keys of one 16-byte column
+// chunk per lane, transposed in registers as in the single-wavefront kernel.  Shares, pieces,
+// the look-ahead across pieces and the queue are the same, with the workgroup in the wavefront's place.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P) {
+    constexpr int DCH = D / 8;
+    constexpr int KCALLS = D / 32;
+    constexpr int KLOADS = DCH / 2;
+    constexpr int LROW = D + 8;
+    constexpr int BK = 32 * NW;     // keys per block
+    constexpr int PTR = (kMaxPiecePages + 63) / 64;
+    __shared__ __attribute__((aligned(16))) uint16_t sK[NW][32 * LROW];
+    __shared__ u32x4 sVt[NW][8][64];   // V of each sub-block as MFMA operands: [head dim within chunk][lane]
+    __shared__ int32_t sPT[3][PTR * 64];
+    __shared__ int32_t s_next;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m16 = lane & 15, g = lane >> 4;
+    const int G = P.group;
+    const int pshift = P.page_shift;
+    const int pmask = (1 << pshift) - 1;
+    const int nn = wave * 16 + m16;          // this lane's row of the strip's (draft row x head) rows
+    const int tl = nn / G, hg = nn - tl * G;
+
+    for (int share = blockIdx.x;;) {
+    const int pc_begin = P.wave_begin[share], pc_end = P.wave_begin[share + 1];
+    if (pc_begin < pc_end) {
+    auto fetch_piece = [&](int r, Piece& pc) {
+        if (pc_begin + r < pc_end) {
+            typedef const int32_t __attribute__((address_space(4)))* ConstWords;
+            const ConstWords w = (ConstWords)(uintptr_t)(P.pieces + pc_begin + r);
+            pc = Piece{w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]};
+        } else {
+            pc = Piece{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    };
+    // page ids are handled by wavefront 0 for the whole workgroup
+    auto load_pages = [&](const Piece& pc, int32_t (&pr)[PTR]) {
+        const int pg0 = pc.k0 >> pshift;
+        const int npg = pc.k1 > pc.k0 ? ((pc.k1 - 1) >> pshift) - pg0 + 1 : 0;
+#pragma unroll
+        for (int i = 0; i < PTR; ++i) {
+            const int idx = lane + 64 * i;
+            pr[i] = (wave == 0 && idx < npg) ? P.page_table[pc.pt_base + pg0 + idx] : 0;
+        }
+    };
+    auto store_pages = [&](int buf, const int32_t (&pr)[PTR]) {
+        if (wave == 0) {
+#pragma unroll
+            for (int i = 0; i < PTR; ++i) sPT[buf][lane + 64 * i] = pr[i];
+        }
+    };
+    bf16x8 qf[KCALLS];
+    auto load_q = [&](const Piece& pc) {
+        const int kvh = pc.head_flags & kPieceHeadMask;
+        const bool valid = tl < pc.n_q;
+        const uint16_t* qp = P.q + ((int64_t)(pc.q_row0 + (valid ? tl : 0)) * P.n_q_heads + kvh * G + hg) * D + g * 8;
+#pragma unroll
+        for (int c = 0; c < KCALLS; ++c) {
+            u32x4 v = valid ? *(const u32x4*)(qp + c * 32) : u32x4{0, 0, 0, 0};
+            qf[c] = __builtin_bit_cast(bf16x8, v);
+        }
+    };
+    // this wavefront's 32 keys (kb + 32*wave ...) of the block starting at kb: K as 1 KiB-contiguous
+    // loads, V as the same 16-byte column chunk of eight keys per lane (see the kernel above)
+    u32x4 Kr[KLOADS], Vr[8];
+    auto row_ptr = [&](const uint16_t* pool, int buf, int pg0, int k1, int64_t head_off, int key) -> const uint16_t* {
+        key = min(key, k1 - 1);   // past the end: a valid row, masked later
+        const int pg = sPT[buf][(key >> pshift) - pg0];
+        return pool + (int64_t)pg * P.page_stride + head_off + (int64_t)(key & pmask) * P.token_stride;
+    };
+    const bool tile_layout = pshift == 4 && P.token_stride == D;   // see the single-wavefront kernel
+    auto load_kv = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
+        const int kw = kb + 32 * wave;
+        if (tile_layout && !(kb & 31) && kb + BK <= k1) {
+            const int pi = (kw >> 4) - pg0;
+            const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][pi]);
+            const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][pi + 1]);
+            const int64_t oa = (int64_t)pga * P.page_stride + head_off, ob = (int64_t)pgb * P.page_stride + head_off;
+            const char *ka = (const char*)(P.k_pool + oa), *kb_ = (const char*)(P.k_pool + ob);
+            const char *va = (const char*)(P.v_pool + oa), *vb = (const char*)(P.v_pool + ob);
+            constexpr int KPI = 64 / DCH;
+#pragma unroll
+            for (int i = 0; i < KLOADS; ++i) {
+                const int key = i * KPI;
+                Kr[i] = stream_load(key < 16 ? ka : kb_, (uint32_t)((key & 15) * D * 2 + lane * 16));
+            }
+            const uint32_t lo = (uint32_t)(g * 4 * D * 2 + (m16 % DCH) * 16);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) Vr[j] = stream_load(j < 4 ? va : vb, lo + (uint32_t)((j & 3) * D * 2));
+        } else {
+#pragma unroll
+            for (int i = 0; i < KLOADS; ++i) {
+                const int f = i * 64 + lane;
+                Kr[i] = stream_load(row_ptr(P.k_pool, buf, pg0, k1, head_off, kw + f / DCH) + (f % DCH) * 8);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int kl = (j >> 2) * 16 + g * 4 + (j & 3);
+                Vr[j] = stream_load(row_ptr(P.v_pool, buf, pg0, k1, head_off, kw + kl) + (m16 % DCH) * 8);
+            }
+        }
+    };
+
+    Piece cp, p1, p2, p3;
+    fetch_piece(0, cp);
+    fetch_piece(1, p1);
+    fetch_piece(2, p2);
+    fetch_piece(3, p3);
+    int next_piece = 4;
+    int32_t pr[PTR];
+    load_pages(cp, pr);
+    store_pages(0, pr);
+    load_pages(p1, pr);
+    store_pages(1, pr);
+    load_pages(p2, pr);
+    store_pages(2, pr);
+    bool pr_pending = false;
+    load_q(cp);
+    __syncthreads();
+
+    f32x4 O[8];
+    float m_run = kNegBig, l_run = 0.f;
+    int cb = 0;
+    load_kv(cb, cp.k0 >> pshift, cp.k1, (int64_t)(cp.head_flags & kPieceHeadMask) * P.head_stride, cp.k0);
+
+    while (true) {
+        const int lim = tl < cp.n_q ? min(cp.k1, cp.causal0 + tl) : cp.k0;
+        if (!(cp.head_flags & kPieceCarryIn)) {
+            m_run = kNegBig;
+            l_run = 0.f;
+#pragma unroll
+            for (int jd = 0; jd < 8; ++jd) O[jd] = f32x4{0, 0, 0, 0};
+        }
+        const int full_end = min(cp.k1, cp.causal0);
+        const bool more = p1.k1 > p1.k0;
+        const bool new_q = more && !(p1.head_flags & kPieceCarryIn);
+
+        for (int kb = cp.k0; kb < cp.k1; kb += BK) {
+            const bool last = kb + BK >= cp.k1;
+            const bool hop = last && more;
+            const int s_buf = hop ? (cb == 2 ? 0 : cb + 1) : cb;
+            const int s_pg0 = hop ? (p1.k0 >> pshift) : (cp.k0 >> pshift);
+            const int s_k1 = hop ? p1.k1 : cp.k1;
+            const int64_t s_head = (int64_t)((hop ? p1.head_flags : cp.head_flags) & kPieceHeadMask) * P.head_stride;
+            const int s_kb = hop ? p1.k0 : (last ? kb : kb + BK);
+
+            // ---- everybody has finished with the previous block's tiles: park this block's rows in LDS
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < KLOADS; ++i) {
+                const int f = i * 64 + lane;
+                *(u32x4*)&sK[wave][(f / DCH) * LROW + (f % DCH) * 8] = Kr[i];
+            }
+            // V: 8x8 transpose of 16-bit values inside each lane, done once here for all wavefronts
+#pragma unroll
+            for (int jd = 0; jd < 8; ++jd) {
+                const uint32_t sel = (jd & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 vt;
+#pragma unroll
+                for (int kp = 0; kp < 4; ++kp) vt[kp] = __builtin_amdgcn_perm(Vr[2 * kp + 1][jd >> 1], Vr[2 * kp][jd >> 1], sel);
+                sVt[wave][jd][lane] = vt;
+            }
+            if (pr_pending) {
+                store_pages(cb == 0 ? 2 : cb - 1, pr);
+                pr_pending = false;
+            }
+            __syncthreads();
+            if (last && (p3.k1 > p3.k0)) {
+                load_pages(p3, pr);
+                pr_pending = true;
+            }
+            load_kv(s_buf, s_pg0, s_k1, s_head, s_kb);
+
+            // ---- every wavefront works through all NW sub-blocks for its own 16 rows
+#pragma unroll 1
+            for (int sb = 0; sb < NW; ++sb) {
+                const int kb2 = kb + 32 * sb;
+                if (kb2 >= cp.k1) break;              // the block's tail beyond the piece holds nothing
+                f32x4 S[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
+#pragma unroll
+                for (int c = 0; c < KCALLS; ++c)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sK[sb][(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
+                        S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[c], S[t], 0, 0, 0);
+                    }
+                float s[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[e] = S[e >> 2][e & 3];
+                if (kb2 + 32 > full_end) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int key = kb2 + (e >> 2) * 16 + g * 4 + (e & 3);
+                        if (key >= lim) s[e] = -INFINITY;
+                    }
+                }
+                float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                // The exponent reference m_run follows the running maximum lazily: it moves (and the
+                // accumulators are rescaled) only when some row's maximum has grown past it by more than
+                // kSlack, so exp2(score - m_run) stays below 2^kSlack and most blocks skip the rescale.
+                if (__any(mx * P.scale_log2 > m_run + kSlack)) {
+                    const float m_new = fmaxf(m_run, mx * P.scale_log2);
+                    const float alpha = fast_exp2(m_run - m_new);
+                    m_run = m_new;
+                    l_run *= alpha;
+#pragma unroll
+                    for (int jd = 0; jd < 8; ++jd) O[jd] *= alpha;
+                }
+                float p[8], sum = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    p[e] = fast_exp2(s[e] * P.scale_log2 - m_run);
+                    sum += p[e];
+                }
+                l_run += sum;
+                const u32x4 pk = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+                const bf16x8 Pb = __builtin_bit_cast(bf16x8, pk);
+#pragma unroll
+                for (int jd = 0; jd < 8; ++jd)
+                    O[jd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, sVt[sb][jd][lane]), Pb, O[jd], 0, 0, 0);
+            }
+            // the queries are no longer needed after the last block: fetch the next piece's if they differ
+            if (last && new_q) load_q(p1);
+        }
+
+        if (!(cp.head_flags & kPieceCarryOut)) {
+            const int kvh = cp.head_flags & kPieceHeadMask;
+            float l = l_run;
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            if (tl < cp.n_q) {
+                if (cp.head_flags & kPieceDirect) {
+                    const float inv = 1.0f / l;
+                    uint16_t* op = P.o + ((int64_t)(cp.q_row0 + tl) * P.n_q_heads + kvh * G + hg) * D + g * 32;
+                    if (g * 4 < DCH) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            u32x4 w = {pack_bf16(O[0][r] * inv, O[1][r] * inv), pack_bf16(O[2][r] * inv, O[3][r] * inv),
+                                       pack_bf16(O[4][r] * inv, O[5][r] * inv), pack_bf16(O[6][r] * inv, O[7][r] * inv)};
+                            *(u32x4*)(op + r * 8) = w;
+                        }
+                    }
+                } else {
+                    const int64_t slot = (int64_t)cp.out_base + nn;
+                    float* po = P.part_o + slot * kPartRow;
+                    if (g * 4 < DCH) {
+#pragma unroll
+                        for (int jd = 0; jd < 8; ++jd) *(f32x4*)(po + jd * 16 + g * 4) = O[jd];
+                    }
+                    if (g == 0) {
+                        P.part_ml[slot * 2] = m_run;
+                        P.part_ml[slot * 2 + 1] = l;
+                    }
+                }
+            }
+        }
+        if (!more) break;
+        cb = cb == 2 ? 0 : cb + 1;
+        cp = p1;
+        p1 = p2;
+        p2 = p3;
+        fetch_piece(next_piece++, p3);
+    }
+    }
+    if (P.n_queued == 0) break;
+    __syncthreads();
+    if (threadIdx.x == 0) s_next = atomicAdd(P.queue, 1);
+    __syncthreads();
+    const int next = s_next;
+    if (next >= P.n_queued) break;
+    share = gridDim.x + next;
+    }
+}
+
 // Join the partial results of one (request, KV head): Eq. (13) -- one denominator over all tokens
 // of the original request.  With piece s holding (m_s, l_s, N_s) where l_s = sum of exp2(score -
 // m_s) and N_s the matching weighted value sum:  O = sum_s 2^(m_s-M) N_s / sum_s 2^(m_s-M) l_s.
@@ -423,18 +740,22 @@ __global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinPara
 template <int D>
 static const void* attn_kernel_ptr(int cls) {
     return cls == 0 ? (const void*)verify_attn_kernel<D, 1>
-         : cls == 1 ? (const void*)verify_attn_kernel<D, 2> : (const void*)verify_attn_kernel<D, 4>;
+         : cls == 1 ? (const void*)verify_attn_group_kernel<D, 2> : (const void*)verify_attn_group_kernel<D, 4>;
 }
 
 hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
     const void* fn = head_dim == 128 ? attn_kernel_ptr<128>(cls) : attn_kernel_ptr<64>(cls);
     int per_cu = 0, dev = 0;
     hipDeviceProp_t prop;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64, 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, cls == 0 ? 64 : (cls == 1 ? 128 : 256), 0);
     if (e == hipSuccess) e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e != hipSuccess) return e;
-    *n_waves = (per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
+    if (per_cu < 1) per_cu = 1;
+    // the single-wavefront kernel streams best with one wavefront per SIMD: more wavefronts mean more,
+    // shorter shares (more cuts and partial results) and the stream is not latency-bound
+    if (cls == 0 && per_cu > 4) per_cu = 4;
+    *n_waves = per_cu * prop.multiProcessorCount;
     return hipSuccess;
 }
 
@@ -452,10 +773,10 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         p.queue = queues_dev + cls;
         p.n_queued = n_queued[cls];
         p.exp_flags = expf;
-        dim3 grid((unsigned)n_waves[cls]), block(64);
-        if (cls == 0) hipLaunchKernelGGL((verify_attn_kernel<D, 1>), grid, block, 0, stream, p);
-        else if (cls == 1) hipLaunchKernelGGL((verify_attn_kernel<D, 2>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((verify_attn_kernel<D, 4>), grid, block, 0, stream, p);
+        dim3 grid((unsigned)n_waves[cls]);
+        if (cls == 0) hipLaunchKernelGGL((verify_attn_kernel<D, 1>), grid, dim3(64), 0, stream, p);
+        else if (cls == 1) hipLaunchKernelGGL((verify_attn_group_kernel<D, 2>), grid, dim3(128), 0, stream, p);
+        else hipLaunchKernelGGL((verify_attn_group_kernel<D, 4>), grid, dim3(256), 0, stream, p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -181,7 +181,6 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
     const int max_rows = kMaxTileRows / group;
     // blocks one piece may span: bounded by the page ids a piece may cache
     int64_t window_keys = std::min<int64_t>(2048, (int64_t)(kMaxPiecePages - 2) * page_size);
-    const int window_blocks = (int)std::max<int64_t>(1, window_keys / kBlockKeys);
 
     std::vector<spin_subreq>& rects = plan.rects;
     rects.clear();
@@ -224,8 +223,17 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
                      (s.kv_begin == 0 && ke == p + qb + ql) ? 1 : 0};
             plan.strips.push_back(st);
             plan.strip_begin[s.parent + 1]++;
-            plan.class_blocks[st.cls] += (int64_t)((ke - s.kv_begin + kBlockKeys - 1) / kBlockKeys) * n_kv_heads;
         }
+    }
+    // One launch per call: every strip runs in the kernel instance of the widest strip (1, 2 or 4
+    // wavefronts per workgroup, 32 keys per wavefront and block).
+    int call_cls = 0;
+    for (const Strip& st : plan.strips) call_cls = std::max(call_cls, st.cls);
+    const int bk = kBlockKeys << call_cls;
+    const int window_blocks = (int)std::max<int64_t>(1, window_keys / bk);
+    for (Strip& st : plan.strips) {
+        st.cls = call_cls;
+        plan.class_blocks[call_cls] += (int64_t)((st.k1 - st.k0 + bk - 1) / bk) * n_kv_heads;
     }
     for (int32_t i = 0; i < t->n_req; ++i) plan.strip_begin[i + 1] += plan.strip_begin[i];
     const size_t n_strips = plan.strips.size();
@@ -252,13 +260,13 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
         // small chunks that wavefronts take from a queue as they finish (sizes shrink towards the end).
         std::vector<int64_t>& bounds = plan.bounds;
         bounds.clear();
-        const int64_t T_dyn = (W >= kMinDynamicWaves && T / W >= kMinBlocksForQueue) ? T * kDynamicPercent / 100 : 0;
+        const int64_t T_dyn = (W >= kMinDynamicWaves && T / W * bk >= kMinKeysForQueue) ? T * kDynamicPercent / 100 : 0;
         const int64_t T_static = T - T_dyn;
         for (int64_t w = 1; w <= W; ++w) bounds.push_back(w * T_static / W);
         plan.n_static[c] = (int32_t)W;
         for (int64_t at = T_static; at < T;) {
             const int64_t left = T - at;
-            const int64_t chunk = std::min<int64_t>(left, std::max<int64_t>(kMinChunkBlocks, std::min<int64_t>(kMaxChunkBlocks, left / W)));
+            const int64_t chunk = std::min<int64_t>(left, std::max<int64_t>(kMinChunkKeys / bk, std::min<int64_t>(kMaxChunkKeys / bk, left / W)));
             at += chunk;
             bounds.push_back(at);
         }
@@ -269,7 +277,7 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
         for (size_t si = 0; si < n_strips; ++si) {
             const Strip& st = plan.strips[si];
             if (st.cls != c) continue;
-            const int32_t nb = (st.k1 - st.k0 + kBlockKeys - 1) / kBlockKeys;
+            const int32_t nb = (st.k1 - st.k0 + bk - 1) / bk;
             const int32_t p = t->prefix_len[st.parent];
             for (int kvh = 0; kvh < n_kv_heads; ++kvh) {
                 const size_t first = plan.pieces.size();
@@ -286,8 +294,8 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
                     pc.q_row0 = t->q_offset[st.parent] + st.q_begin;
                     pc.n_q = st.q_len;
                     pc.causal0 = p + st.q_begin + 1;
-                    pc.k0 = st.k0 + b * kBlockKeys;
-                    pc.k1 = std::min(st.k1, st.k0 + (b + take) * kBlockKeys);
+                    pc.k0 = st.k0 + b * bk;
+                    pc.k1 = std::min(st.k1, st.k0 + (b + take) * bk);
                     pc.pt_base = t->pt_offset ? t->pt_offset[st.parent] : 0;
                     pc.out_base = 0;
                     plan.pieces.push_back(pc);

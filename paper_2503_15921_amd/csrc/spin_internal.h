@@ -15,19 +15,20 @@ namespace spin {
 // Rows of the (draft row x query head of one KV group) tile one wavefront works on: up to 4 MFMA
 // column tiles of 16.
 constexpr int kMaxTileRows = 64;
-// Keys per streaming block of the attention kernel.
+// Keys per wavefront and streaming block of the attention kernels (a block of the grouped-query
+// kernel holds 32 keys per wavefront of its workgroup).
 constexpr int kBlockKeys = 32;
 // Page ids one piece may touch (cached in LDS by the attention kernel).
 constexpr int kMaxPiecePages = 136;
 // A wavefront is given at least this many blocks before another wavefront is used.
 constexpr int kMinBlocksPerWave = 4;
 // Share of the blocks (percent) that is handed out from a queue at the end instead of up front, the
-// size range of the queued chunks in blocks, and the launch and share sizes from which queueing is used.
+// size range of the queued chunks in keys, and the launch and share sizes from which queueing is used.
 constexpr int kDynamicPercent = 10;
-constexpr int kMinChunkBlocks = 16;
-constexpr int kMaxChunkBlocks = 32;
+constexpr int kMinChunkKeys = 512;
+constexpr int kMaxChunkKeys = 1024;
 constexpr int kMinDynamicWaves = 64;
-constexpr int kMinBlocksForQueue = 192;   // blocks per wavefront below which queueing does not pay
+constexpr int kMinKeysForQueue = 6144;   // keys per share below which queueing does not pay
 
 constexpr int32_t kPieceHeadMask = 0xffff;
 constexpr int32_t kPieceCarryIn = 1 << 16;   // accumulators continue from the wavefront's previous piece

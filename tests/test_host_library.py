@@ -121,8 +121,8 @@ def test_check_tiling_accepts_exact_and_rejects_broken():
     assert spin.check_tiling([p], [g], subs) == 0
 
 
-def blocks_of(piece):
-    return -(-int(piece[4]) // 32)
+def blocks_of(piece, bk=32):
+    return -(-int(piece[4]) // bk)
 
 
 @pytest.mark.parametrize("group,n_kv,n_waves,page,top", [(1, 4, 64, 16, 3000), (1, 2, 7, 16, 3000), (8, 2, 100, 16, 3000),
@@ -137,9 +137,12 @@ def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page
         pcs = spin.schedule(prefix, draft, subs, page, group, n_kv, n_waves)
         for h in range(n_kv):
             assert_exact_tiling(prefix, draft, pcs[pcs[:, 5] == h][:, :5])
+        widest = int((pcs[:, 2] * group).max())        # one launch per call, sized for the widest strip
+        call_cls = 0 if widest <= 16 else 1 if widest <= 32 else 2
+        bk = 32 << call_cls
         for pc in pcs:
             parent, qb, ql, kb, kl, kvh, cls, wave, flags = (int(x) for x in pc)
-            assert ql * group <= 64 and cls == (0 if ql * group <= 16 else 1 if ql * group <= 32 else 2)
+            assert ql * group <= 64 and cls == call_cls
             assert kl >= 1 and (kb + kl - 1) // page - kb // page + 1 <= 136
             assert wave >= 0
         for cls in range(3):
@@ -150,15 +153,15 @@ def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page
             # (handed out at run time) come after them and hold 1..64 blocks
             per_share = np.zeros(int(c[:, 7].max()) + 1, dtype=np.int64)
             for pc in c:
-                per_share[pc[7]] += blocks_of(pc)
+                per_share[pc[7]] += blocks_of(pc, bk)
             queued = np.zeros(len(per_share), dtype=bool)
             queued[c[(c[:, 8] & spin.PIECE_QUEUED) != 0][:, 7]] = True
             static = per_share[~queued]
             assert len(static) <= n_waves and static.min() >= 1 and static.max() - static.min() <= 1
             if queued.any():
                 assert queued[len(static):].all() and n_waves >= 64
-                assert per_share[queued].min() >= 1 and per_share[queued].max() <= 32
-                assert static.min() >= 150 and 0.05 < per_share[queued].sum() / per_share.sum() < 0.15
+                assert per_share[queued].min() >= 1 and per_share[queued].max() * bk <= 1024
+                assert static.min() * bk >= 5000 and 0.05 < per_share[queued].sum() / per_share.sum() < 0.15
             # a share's pieces are consecutive in the class's streaming order
             assert list(c[:, 7]) == sorted(c[:, 7])
         # flags: CARRY_IN / CARRY_OUT link neighbours of one (rectangle, head) inside one wavefront;
