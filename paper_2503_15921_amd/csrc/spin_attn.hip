@@ -425,8 +425,14 @@ __global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P
     const int G = P.group;
     const int pshift = P.page_shift;
     const int pmask = (1 << pshift) - 1;
-    const int nn = wave * 16 + m16;          // this lane's row of the strip's (draft row x head) rows
-    const int tl = nn / G, hg = nn - tl * G;
+    // How the wavefronts divide a piece: a strip with T row tiles (16 rows each) is given T_eff = 1, 2 or
+    // 4 tiles; wavefront w owns tile w % T_eff and, when there are more wavefronts than tiles, every
+    // (NW / T_eff)-th 32-key sub-block of each block -- so narrow strips split the keys instead of
+    // leaving wavefronts idle, and the wavefronts sharing a tile merge their accumulators at the end.
+    auto tiles_eff = [&](const Piece& pc) {
+        const int t = (pc.n_q * G + 15) >> 4;
+        return t <= 1 ? 1 : (t == 2 || NW == 2 ? 2 : 4);
+    };
 
     for (int share = blockIdx.x;;) {
     const int pc_begin = P.wave_begin[share], pc_end = P.wave_begin[share + 1];
@@ -459,6 +465,8 @@ __global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P
     bf16x8 qf[KCALLS];
     auto load_q = [&](const Piece& pc) {
         const int kvh = pc.head_flags & kPieceHeadMask;
+        const int nn = (wave % tiles_eff(pc)) * 16 + m16;
+        const int tl = nn / G, hg = nn - tl * G;
         const bool valid = tl < pc.n_q;
         const uint16_t* qp = P.q + ((int64_t)(pc.q_row0 + (valid ? tl : 0)) * P.n_q_heads + kvh * G + hg) * D + g * 8;
 #pragma unroll
@@ -531,6 +539,10 @@ __global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P
     load_kv(cb, cp.k0 >> pshift, cp.k1, (int64_t)(cp.head_flags & kPieceHeadMask) * P.head_stride, cp.k0);
 
     while (true) {
+        const int t_eff = tiles_eff(cp);
+        const int ksplit = NW / t_eff, kgroup = wave / t_eff;   // this wavefront takes sub-blocks kgroup, kgroup + ksplit, ...
+        const int nn = (wave % t_eff) * 16 + m16;                // this lane's row of the strip's (draft row x head) rows
+        const int tl = nn / G, hg = nn - tl * G;
         const int lim = tl < cp.n_q ? min(cp.k1, cp.causal0 + tl) : cp.k0;
         if (!(cp.head_flags & kPieceCarryIn)) {
             m_run = kNegBig;
@@ -578,9 +590,9 @@ __global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P
             }
             load_kv(s_buf, s_pg0, s_k1, s_head, s_kb);
 
-            // ---- every wavefront works through all NW sub-blocks for its own 16 rows
+            // ---- every wavefront works through its sub-blocks for its own 16 rows
 #pragma unroll 1
-            for (int sb = 0; sb < NW; ++sb) {
+            for (int sb = kgroup; sb < NW; sb += ksplit) {
                 const int kb2 = kb + 32 * sb;
                 if (kb2 >= cp.k1) break;              // the block's tail beyond the piece holds nothing
                 f32x4 S[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
@@ -632,7 +644,35 @@ __global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P
             if (last && new_q) load_q(p1);
         }
 
-        if (!(cp.head_flags & kPieceCarryOut)) {
+        // ---- wavefronts that shared a row tile (each on its own keys) merge into the first of them
+        if (!(cp.head_flags & kPieceCarryOut) && ksplit > 1) {
+            f32x4* const sMergeO = reinterpret_cast<f32x4*>(&sVt[0][0][0]);     // [wave][8][64] overlays the V tiles exactly
+            float* const sMergeML = reinterpret_cast<float*>(&sK[0][0]);        // [wave][2][64] overlays the K tiles
+            __syncthreads();                       // everybody has finished reading the tiles
+            if (kgroup > 0) {
+#pragma unroll
+                for (int jd = 0; jd < 8; ++jd) sMergeO[(wave * 8 + jd) * 64 + lane] = O[jd];
+                sMergeML[(wave * 2 + 0) * 64 + lane] = m_run;
+                sMergeML[(wave * 2 + 1) * 64 + lane] = l_run;
+            }
+            __syncthreads();
+            if (kgroup == 0) {
+                for (int k = 1; k < ksplit; ++k) {
+                    const int pw = wave + k * t_eff;
+                    const float m2 = sMergeML[(pw * 2 + 0) * 64 + lane], l2 = sMergeML[(pw * 2 + 1) * 64 + lane];
+                    const float M = fmaxf(m_run, m2);
+                    const float a = fast_exp2(m_run - M), b = fast_exp2(m2 - M);
+#pragma unroll
+                    for (int jd = 0; jd < 8; ++jd) {
+                        const f32x4 o2 = sMergeO[(pw * 8 + jd) * 64 + lane];
+                        O[jd] = O[jd] * a + o2 * b;
+                    }
+                    l_run = l_run * a + l2 * b;
+                    m_run = M;
+                }
+            }
+        }
+        if (!(cp.head_flags & kPieceCarryOut) && kgroup == 0) {
             const int kvh = cp.head_flags & kPieceHeadMask;
             float l = l_run;
             l += __shfl_xor(l, 16);

@@ -331,7 +331,7 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     int pshift = 0;
     while ((1 << pshift) < kv->page_size) ++pshift;
     const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)kv->head_dim);
-    spin::AttnParams ap;
+    spin::AttnParams ap = {};
     ap.k_pool = (const uint16_t*)kv->k_pool;
     ap.v_pool = (const uint16_t*)kv->v_pool;
     ap.q = (const uint16_t*)q_dev;
@@ -358,7 +358,7 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
         pieces_dev[c] = (const spin::Piece*)(blob + off_pieces) + plan.class_piece_begin[c];
         waves_dev[c] = (const int32_t*)(blob + off_waves[c]);
     }
-    spin::JoinParams jp;
+    spin::JoinParams jp = {};
     jp.pieces = (const spin::Piece*)(blob + off_pieces);
     jp.ppos = (const int32_t*)(blob + off_ppos);
     jp.strip_begin = (const int32_t*)(blob + off_strips);
@@ -432,7 +432,7 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
     const int slot = ctx->stage;
 
-    spin::AcceptParams p;
+    spin::AcceptParams p = {};
     p.row_off = (const int32_t*)row_off_dev;
     p.draft_tokens = draft_tokens_dev;
     p.target_logits = target_logits_dev;
