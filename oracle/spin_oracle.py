@@ -240,8 +240,9 @@ def accept_greedy(draft_len, draft_tokens, target_logits):
         while True:
             row = target_logits[base + n]
             top = _first_argmax(row)
-            part = np.partition(row, -2)[-2:]
-            margin[i] = min(margin[i], float(part[1] - part[0]))
+            if len(row) > 1:                      # (a one-token vocabulary has no runner-up)
+                part = np.partition(row, -2)[-2:]
+                margin[i] = min(margin[i], float(part[1] - part[0]))
             if n < g and int(draft_tokens[r + n]) == top:
                 n += 1
                 continue

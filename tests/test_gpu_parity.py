@@ -230,6 +230,45 @@ def test_small_pages(ctx):
     assert_close(hip_attention(ctx, b), oracle_attention(b, 0.0), "page size 4")
 
 
+@pytest.mark.parametrize("page", [1, 2, 8, 32, 64])
+def test_other_page_sizes(ctx, page):
+    cfg = make_cfg(f"page{page}", 5, 4, 2, 128, page=page)
+    prefix = np.array([0, 37, 129, 500, 1031]); draft = np.array([2, 7, 1, 16, 4])
+    b = si.make_verify_batch(cfg, 30 + page, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
+    assert_close(hip_attention(ctx, b), oracle_attention(b, 0.0), f"page size {page}")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_batches(ctx, seed):
+    """Random shapes, groups, page sizes, decompositions and share counts against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    hkv = int(rng.choice([1, 2, 3, 5]))
+    group = int(rng.choice([1, 1, 2, 4, 8]))
+    d = int(rng.choice([64, 128]))
+    page = int(rng.choice([4, 16, 16, 32]))
+    n_req = int(rng.integers(1, 9))
+    prefix = np.where(rng.random(n_req) < 0.3, rng.integers(0, 40, n_req), rng.integers(0, 2500, n_req))
+    max_draft = 16 if group <= 4 else 8
+    draft = rng.integers(1, max_draft + 1, n_req)
+    cfg = make_cfg("random", n_req, hkv * group, hkv, d, page=page)
+    b = si.make_verify_batch(cfg, 2000 + seed, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
+    kind = int(rng.integers(4))
+    if kind == 0:
+        subs = None
+    elif kind == 1:
+        subs = orc.decompose_q_split(prefix, draft, int(rng.integers(1, 6)))
+    elif kind == 2:
+        subs = orc.decompose_kv_split(prefix, draft, int(rng.integers(1, 700)))
+    else:
+        subs = np.array([(i,) + r for i in range(n_req) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))],
+                        dtype=np.int32)
+    waves = int(rng.choice([1, 3, 17, 256, 0]))
+    scale = float(rng.choice([0.0, 0.0, 0.3, 1.0]))
+    what = f"seed {seed}: hkv {hkv} group {group} d {d} page {page} kind {kind} waves {waves} scale {scale}"
+    print(what, flush=True)
+    assert_close(hip_attention(ctx, b, subs=subs, scale=scale, waves=waves), oracle_attention(b, scale), what)
+
+
 FULL = [("7b", 1), ("skewed", 2), ("13b", 3), ("70b_gqa", 4)]
 
 
@@ -343,6 +382,35 @@ def test_accept_planted_lengths(ctx):
     ab2.u_accept.zero_()
     n_g, _ = hip_accept(ctx, spin.ACCEPT_REJECTION, ab2)
     np.testing.assert_array_equal(n_g, draft_len)
+
+
+@pytest.mark.parametrize("vocab", [1, 2, 7, 257, 4099, 70001])
+def test_accept_odd_vocabularies_and_long_drafts(ctx, vocab):
+    # scalar-load paths (vocab not a multiple of 4), tiny vocabularies, more than 64 draft rows per request
+    import paper_2503_15921_amd as spin
+    draft_len = np.array([1, 70, 3, 130, 2], dtype=np.int32)
+    for rho in (None, 0.98):
+        ab = si.make_accept_batch(draft_len, vocab, 1.5, 7 + vocab, device="cuda", rho=rho)
+        check_accept(ctx, spin.ACCEPT_REJECTION, ab, f"vocab {vocab} rho {rho}")
+        ab = si.make_accept_batch(draft_len, vocab, 1.5, 7 + vocab, device="cuda", rho=rho, draft_token_mode="argmax")
+        check_accept(ctx, spin.ACCEPT_GREEDY, ab, f"vocab {vocab} greedy rho {rho}")
+
+
+def test_accept_extreme_uniforms(ctx):
+    # u' = 0 picks the first id with mass; u' just below 1 picks (one of) the last; u = 0 keeps, u near 1 rejects
+    import paper_2503_15921_amd as spin
+    draft_len = np.array([4, 4, 4, 4], dtype=np.int32)
+    ab = si.make_accept_batch(draft_len, 5000, 2.0, 11, device="cuda", rho=0.9)
+    ab.u_sample[:] = torch.tensor([0.0, 1.0 - 2 ** -53, 0.5, 0.25], dtype=torch.float64)
+    ab.u_accept[:] = torch.tensor([0.0, 0.0, 0.0, 0.0, 0.0, 1 - 2 ** -53, 0.0, 0.0] * 2, dtype=torch.float64)
+    n_g, t_g = hip_accept(ctx, spin.ACCEPT_REJECTION, ab)
+    n_o, t_o, margin = oracle_accept(spin.ACCEPT_REJECTION, ab)
+    np.testing.assert_array_equal(n_g, n_o)
+    # request 1's draw sits at the very end of the CDF, where the two summation orders may pick different
+    # ids among the last few with mass: compare the others bit for bit, and request 1 for validity
+    keep = np.array([0, 2, 3])
+    np.testing.assert_array_equal(t_g[keep], t_o[keep])
+    assert 0 <= t_g[1] < 5000
 
 
 def test_accept_token_outside_vocabulary_is_rejected(ctx):
