@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--seed", type=int, default=3)
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per attention launch (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--append", action="store_true",
+                    help="the step also scatters the draft tokens' K/V rows into the cache first (spin_append_kv)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="instead of the step, run a plain 1 GiB device copy per step (counter calibration)")
     args = ap.parse_args()
@@ -115,8 +117,16 @@ def main():
     n_acc = torch.empty(t.n_req, dtype=torch.int32, device=dev)
     nxt = torch.empty_like(n_acc)
 
+    if args.append:
+        g = torch.Generator(device="cpu").manual_seed(args.seed)
+        shape = (t.n_rows, cfg.n_kv_heads, cfg.head_dim)
+        k_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
+        v_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
+
     def step():
         subs = None
+        if args.append:
+            ctx.append_kv(tab, batch.k_pool, batch.v_pool, k_new, v_new)
         if cfg.q_split_width:
             subs, _ = spin.decompose(t.prefix_len, t.draft_len, spin.DECOMP_Q_SPLIT, q_width=cfg.q_split_width)
         ctx.verify_attn(tab, batch.k_pool, batch.v_pool, batch.q, out, cfg.n_q_heads, subs=subs)
@@ -153,7 +163,8 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.n_req} requests, {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, "
                                f"head_dim {cfg.head_dim}, prefix {cfg.prefix_dist} {cfg.prefix_lo}-{cfg.prefix_hi}, "
                                f"draft {cfg.draft_dist} {cfg.draft_lo}-{cfg.draft_hi}, page {cfg.page_size}, "
-                               f"vocab {cfg.vocab}; one attention layer + one rejection-sampling accept",
+                               f"vocab {cfg.vocab}; " + ("KV append + " if args.append else "") +
+                               "one attention layer + one rejection-sampling accept",
                    "seed": args.seed, "draft_rows": t.n_rows, "kv_tokens": t.kv_tokens(),
                    "kv_gb_per_step": kv_bytes / 1e9, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS},
         "kernel_ms": {"attn": attn_ms, "join": ms["join"] / max(calls[0], 1),

@@ -197,6 +197,16 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
                      const spin_subreq* subs, int32_t n_sub, const void* q_dev, void* o_dev,
                      int32_t n_q_heads, float softmax_scale, void* hip_stream);
 
+/* The step just before the attention: put the draft tokens' K and V rows into the paged cache, so
+ * that the caller need not run a scatter of its own.  Row r of k_new_dev / v_new_dev (device, bf16
+ * [R][n_kv_heads][head_dim], packed like Q) is draft token t = r - q_offset[i] of its request i and goes
+ * to position p_i + t: page page_table[pt_offset[i] + (p_i+t)/page_size], slot (p_i+t) % page_size.
+ * kv->k_pool / kv->v_pool are WRITTEN by this call (and only by this call).  Rejected draft tokens
+ * need no roll-back: their slots simply lie beyond the prefix the caller keeps.  Asynchronous on
+ * the stream; same table checks and error codes as spin_verify_attn. */
+int spin_append_kv(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table,
+                   const void* k_new_dev, const void* v_new_dev, void* hip_stream);
+
 #define SPIN_ACCEPT_GREEDY 0
 #define SPIN_ACCEPT_REJECTION 1
 

@@ -12,6 +12,8 @@ What it follows
   * verify_attention_decomposed -- Sec. V-A, Eq. (13): when a request is cut into
                                  sub-requests, the softmax denominator of a row runs over
                                  all tokens of the ORIGINAL request in the batch.
+  * append_kv                -- the KV cache of Sec. II-A1: the candidate tokens' K/V enter the
+                                 cache at the positions after the prefix (plain scatter).
   * decompose_*              -- Sec. V-A: request decomposition and the choice of the
                                  KV-tensor length L for a fixed width B.
   * accept_greedy / accept_rejection -- the verification phase of Sec. II-A2 ("tokens
@@ -146,6 +148,18 @@ def verify_attention_decomposed(prefix_len, draft_len, q_offset, pt_offset, page
                 den[r, h] = den[r, h] * w_old + l_s * w_new
                 mx[r, h] = M
     return num / den[:, :, None]
+
+
+def append_kv(prefix_len, draft_len, q_offset, pt_offset, page_table, page_size, k_pool, v_pool, k_new, v_new):
+    """The step before the attention: draft token t of request i (packed row q_offset[i]+t of k_new /
+    v_new, indexed [row, kv head, dim]) is cached at position p_i + t.  Writes into the pools in place."""
+    for i in range(len(prefix_len)):
+        pt = page_table[pt_offset[i]:pt_offset[i + 1]]
+        for t in range(int(draft_len[i])):
+            pos = int(prefix_len[i]) + t
+            r = int(q_offset[i]) + t
+            k_pool[pt[pos // page_size], :, pos % page_size, :] = k_new[r]
+            v_pool[pt[pos // page_size], :, pos % page_size, :] = v_new[r]
 
 
 # --------------------------------------------------------------------------- decomposition

@@ -64,7 +64,7 @@ class SpinError(RuntimeError):
 
 EXPORTS = ["spin_create", "spin_reserve", "spin_required", "spin_destroy", "spin_strerror",
            "spin_last_error", "spin_set_waves", "spin_decompose", "spin_kv_padding",
-           "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_accept",
+           "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_append_kv", "spin_accept",
            "spin_profile_begin", "spin_profile_end"]
 
 _lib = None
@@ -101,6 +101,7 @@ def load_library():
                                   C.POINTER(WorkPiece), C.c_int32, _i32p]
     lib.spin_verify_attn.argtypes = [C.c_void_p, C.POINTER(KvDesc), tp, sp, C.c_int32, C.c_void_p,
                                      C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
+    lib.spin_append_kv.argtypes = [C.c_void_p, C.POINTER(KvDesc), tp, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.spin_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_void_p]
@@ -293,6 +294,16 @@ class SpinContext:
         self._retry(lambda: self._lib.spin_verify_attn(self._h, C.byref(desc), C.byref(table.struct), sp, ns,
                                                        C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()),
                                                        n_q_heads, softmax_scale, st))
+
+    def append_kv(self, table: _Table, k_pool, v_pool, k_new, v_new, stream=None):
+        """spin_append_kv: scatter the draft tokens' K/V rows (bf16 [R][n_kv_heads][head_dim]) into the pools."""
+        n_pages, n_kv, psz, d = k_pool.shape
+        ps, hs, ts, ds = k_pool.stride()
+        assert ds == 1 and tuple(v_pool.stride()) == tuple(k_pool.stride())
+        desc = KvDesc(k_pool.data_ptr(), v_pool.data_ptr(), n_pages, psz, n_kv, d, ps, hs, ts, DTYPE_BF16)
+        st = self._stream(stream)
+        self._retry(lambda: self._lib.spin_append_kv(self._h, C.byref(desc), C.byref(table.struct),
+                                                     C.c_void_p(k_new.data_ptr()), C.c_void_p(v_new.data_ptr()), st))
 
     def accept(self, mode: int, draft_len, draft_tokens, target_logits, draft_logits, u_accept, u_sample,
                n_accepted, next_token, stream=None):

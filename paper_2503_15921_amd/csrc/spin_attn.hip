@@ -777,6 +777,31 @@ __global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinPara
     }
 }
 
+// Scatter the draft tokens' K and V rows into their page slots: one workgroup per packed row, 16
+// bytes per lane and step, over all KV heads of K and then of V.
+__global__ __launch_bounds__(256) void append_kv_kernel(AppendParams P) {
+    const int row = blockIdx.x;
+    const int64_t slot = P.dst_slot[row];
+    const int64_t page = slot >> P.page_shift, in_page = slot & ((1 << P.page_shift) - 1);
+    const int per_head = P.head_dim >> 3, per_pool = P.n_kv_heads * per_head;
+    const int64_t dst0 = page * P.page_stride + in_page * P.token_stride;
+    const int64_t src0 = (int64_t)row * P.n_kv_heads * P.head_dim;
+    for (int c = threadIdx.x; c < 2 * per_pool; c += 256) {
+        const bool is_v = c >= per_pool;
+        const int cc = is_v ? c - per_pool : c;
+        const int head = cc / per_head, col = (cc - head * per_head) * 8;
+        const uint16_t* src = (is_v ? P.v_new : P.k_new) + src0 + (int64_t)cc * 8;
+        uint16_t* dst = (is_v ? P.v_pool : P.k_pool) + dst0 + head * P.head_stride + col;
+        *(u32x4*)dst = *(const u32x4*)src;
+    }
+}
+
+hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
+    if (p.n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(append_kv_kernel, dim3((unsigned)p.n_rows), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
 template <int D>
 static const void* attn_kernel_ptr(int cls) {
     return cls == 0 ? (const void*)verify_attn_kernel<D, 1>

@@ -98,10 +98,9 @@ constexpr int kMaxWaves = 16384;   // wavefronts per launch the staging buffers 
 
 // pieces | per-class wavefront ranges | (strip, head) piece ranges | strip ranges | row offsets | tasks | page table
 size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
-    (void)rows;
     // every share holds at least one piece, so there are at most `items` share boundaries in all
     return align16(items * sizeof(spin::Piece)) + align16(items * 4) + 3 * 32 + 2 * align16(items * 8) +
-           2 * align16((req + 1) * 4) + align16(pages * 4) + 128;
+           2 * align16((req + 1) * 4) + align16(pages * 4) + align16(rows * 8) + 128;
 }
 
 // Next pinned staging buffer; waits until the copy that last used it has left the host.
@@ -383,6 +382,75 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     e = hipEventRecord(ctx->ev_done[slot], stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     ctx->done_pending[slot] = true;
+    return SPIN_OK;
+}
+
+int spin_append_kv(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table, const void* k_new_dev,
+                   const void* v_new_dev, void* hip_stream) {
+    if (!ctx) return SPIN_EINVAL;
+    if (!kv || !table) return fail(ctx, SPIN_EINVAL, "kv descriptor or request table is null");
+    if (kv->dtype != SPIN_DTYPE_BF16) return fail(ctx, SPIN_EUNSUPPORTED, "only bf16 K/V is supported");
+    if (kv->head_dim < 8 || kv->head_dim % 8) return fail(ctx, SPIN_EUNSUPPORTED, "head_dim must be a multiple of 8");
+    if (kv->page_size < 1 || (kv->page_size & (kv->page_size - 1)))
+        return fail(ctx, SPIN_EUNSUPPORTED, "page_size must be a power of two");
+    if (kv->n_kv_heads < 1 || kv->n_pages < 0 || kv->token_stride < kv->head_dim || kv->token_stride % 8 ||
+        kv->page_stride % 8 || kv->head_stride % 8 || kv->page_stride < 0 || kv->head_stride < 0)
+        return fail(ctx, SPIN_EINVAL, "bad K/V descriptor");
+    std::string err;
+    int rc = spin::validate_table(table, kv->page_size, kv->n_pages, true, err);
+    if (rc) return fail(ctx, rc, err);
+    if (table->n_req == 0) return SPIN_OK;
+    if (!kv->k_pool || !kv->v_pool || !k_new_dev || !v_new_dev) return fail(ctx, SPIN_EINVAL, "null device pointer");
+    if (((uintptr_t)kv->k_pool | (uintptr_t)kv->v_pool | (uintptr_t)k_new_dev | (uintptr_t)v_new_dev) & 15)
+        return fail(ctx, SPIN_EINVAL, "K/V pools and new rows must be 16-byte aligned");
+    const int64_t n_req = table->n_req, n_rows = table->q_offset[n_req];
+    if (n_req > ctx->cap_req || n_rows > ctx->cap_rows) {
+        ctx->need_req = std::max<int64_t>(n_req, ctx->cap_req);
+        ctx->need_rows = std::max<int64_t>(n_rows, ctx->cap_rows);
+        ctx->need_pages = ctx->cap_pages;
+        ctx->need_items = ctx->cap_items;
+        ctx->need_slots = ctx->cap_slots;
+        return fail(ctx, SPIN_ENOSPC, "reserved workspace too small for this batch (see spin_required)");
+    }
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // destination slot of every packed row, read by the kernel from the pinned, device-mapped buffer
+    char* h = nullptr;
+    rc = next_stage(ctx, &h);
+    if (rc) return rc;
+    int64_t* dst = (int64_t*)h;
+    for (int64_t i = 0; i < n_req; ++i) {
+        const int32_t* pt = table->page_table + table->pt_offset[i];
+        for (int32_t t = 0; t < table->draft_len[i]; ++t) {
+            const int64_t pos = (int64_t)table->prefix_len[i] + t;
+            dst[table->q_offset[i] + t] = (int64_t)pt[pos / kv->page_size] * kv->page_size + pos % kv->page_size;
+        }
+    }
+    void* dst_dev = nullptr;
+    e = hipHostGetDevicePointer(&dst_dev, h, 0);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
+    const int slot = ctx->stage;
+    spin::AppendParams p = {};
+    p.dst_slot = (const int64_t*)dst_dev;
+    p.k_new = (const uint16_t*)k_new_dev;
+    p.v_new = (const uint16_t*)v_new_dev;
+    p.k_pool = (uint16_t*)kv->k_pool;
+    p.v_pool = (uint16_t*)kv->v_pool;
+    p.page_stride = kv->page_stride;
+    p.head_stride = kv->head_stride;
+    p.token_stride = kv->token_stride;
+    p.n_rows = (int32_t)n_rows;
+    p.n_kv_heads = kv->n_kv_heads;
+    p.head_dim = kv->head_dim;
+    int pshift = 0;
+    while ((1 << pshift) < kv->page_size) ++pshift;
+    p.page_shift = pshift;
+    e = spin::launch_append(p, stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "append launch");
+    e = hipEventRecord(ctx->ev[slot], stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    ctx->ev_pending[slot] = true;
     return SPIN_OK;
 }
 

@@ -54,6 +54,18 @@ hipError_t launch_attn(int head_dim, const AttnParams& base, const Piece* const 
                        const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
                        int32_t* queues_dev, const JoinParams& jp, hipStream_t stream, hipEvent_t ev_mid);
 
+struct AppendParams {
+    const int64_t* dst_slot;   // [R] page * page_size + slot of every packed row
+    const uint16_t* k_new;     // [R][n_kv_heads][head_dim]
+    const uint16_t* v_new;
+    uint16_t* k_pool;
+    uint16_t* v_pool;
+    int64_t page_stride, head_stride, token_stride;
+    int32_t n_rows, n_kv_heads, head_dim, page_shift;
+};
+
+hipError_t launch_append(const AppendParams& p, hipStream_t stream);
+
 struct AcceptParams {
     const int32_t* row_off;        // [n_req+1] first draft row of each request (device)
     const int32_t* draft_tokens;   // [R]

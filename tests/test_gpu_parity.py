@@ -2,6 +2,7 @@
 seeded inputs.  Attention: every element within 2e-2 absolute OR 2e-2 relative of the oracle
 (plus tighter aggregate bounds).  Acceptance: accepted lengths and token ids bit-exact.
 """
+import dataclasses
 import math
 
 import numpy as np
@@ -290,6 +291,78 @@ def test_full_size_configs_sampled(ctx, name, seed):
     want = oracle_attention(b, 0.0, requests=reqs, heads=heads)
     err, rms = assert_close(got, want, name)
     print(f"{name}: sampled {len(reqs)}x{len(heads)} (request, head) pairs, max abs err {err:.2e}, rel rms {rms:.2e}")
+
+
+# ------------------------------------------------------------------------------ KV append
+def oracle_append(b, k_new, v_new):
+    t = b.table
+    kp = si.bf16_bits(b.k_pool).copy(); vp = si.bf16_bits(b.v_pool).copy()
+    orc.append_kv(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, b.cfg.page_size, kp, vp,
+                  si.bf16_bits(k_new), si.bf16_bits(v_new))
+    return kp, vp
+
+
+def new_rows(b, seed):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    shape = (b.table.n_rows, b.cfg.n_kv_heads, b.cfg.head_dim)
+    return (torch.randn(shape, generator=g).to(torch.bfloat16).cuda(),
+            torch.randn(shape, generator=g).to(torch.bfloat16).cuda())
+
+
+@pytest.mark.parametrize("name,seed,page", [("tiny", 0, 16), ("tiny", 1, 4), ("skewed", 2, 16), ("70b_gqa", 3, 16),
+                                            ("tiny", 4, 1), ("tiny", 5, 64)])
+def test_append_kv_bit_exact(ctx, name, seed, page):
+    cfg = si.CONFIGS[name]
+    if page != cfg.page_size:
+        cfg = dataclasses.replace(cfg, name=f"{name}-p{page}", page_size=page)
+    b = si.make_verify_batch(cfg, seed, device="cuda", poison_unused=True)
+    k_new, v_new = new_rows(b, 100 + seed)
+    want_k, want_v = oracle_append(b, k_new, v_new)
+    t = b.table
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    ctx.append_kv(tab, b.k_pool, b.v_pool, k_new, v_new)
+    torch.cuda.synchronize()
+    assert np.array_equal(si.bf16_bits(b.k_pool), want_k)      # the whole pool: nothing else was touched
+    assert np.array_equal(si.bf16_bits(b.v_pool), want_v)
+
+
+def test_append_then_verify_on_one_stream(ctx):
+    """Append and attention queued back to back with no synchronisation in between."""
+    cfg = make_cfg("append-verify", 6, 8, 2, 128)
+    prefix = np.array([0, 15, 16, 700, 2049, 31]); draft = np.array([4, 1, 16, 7, 3, 2])
+    b = si.make_verify_batch(cfg, 41, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
+    k_new, v_new = new_rows(b, 141)
+    want_k, want_v = oracle_append(b, k_new, v_new)
+    t = b.table
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    out = torch.full_like(b.q, float("nan"))
+    ctx.append_kv(tab, b.k_pool, b.v_pool, k_new, v_new)
+    ctx.verify_attn(tab, b.k_pool, b.v_pool, b.q, out, cfg.n_q_heads)
+    torch.cuda.synchronize()
+    want = orc.verify_attention(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, cfg.page_size,
+                                si.bf16_bits(b.q), want_k, want_v, cfg.n_q_heads, cfg.n_kv_heads,
+                                1.0 / math.sqrt(cfg.head_dim))
+    assert_close(out, want, "append then verify")
+
+
+def test_append_into_strided_cache(ctx):
+    cfg = make_cfg("append-layout", 3, 4, 2, 64)
+    prefix = np.array([40, 5, 333]); draft = np.array([5, 8, 3])
+    b = si.make_verify_batch(cfg, 42, device="cuda", prefix_len=prefix, draft_len=draft)
+    k_new, v_new = new_rows(b, 142)
+    want_k, want_v = oracle_append(b, k_new, v_new)
+    n_pages, hkv, P, d = b.k_pool.shape
+    pitch = d + 24
+    k_alt = torch.zeros((n_pages, P, hkv, pitch), dtype=torch.bfloat16, device="cuda")
+    v_alt = torch.zeros_like(k_alt)
+    k_alt[..., :d] = b.k_pool.permute(0, 2, 1, 3); v_alt[..., :d] = b.v_pool.permute(0, 2, 1, 3)
+    kv = k_alt.permute(0, 2, 1, 3)[..., :d]; vv = v_alt.permute(0, 2, 1, 3)[..., :d]
+    t = b.table
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    ctx.append_kv(tab, kv, vv, k_new, v_new)
+    torch.cuda.synchronize()
+    assert np.array_equal(si.bf16_bits(kv.contiguous()), want_k) and np.array_equal(si.bf16_bits(vv.contiguous()), want_v)
+    assert (k_alt[..., d:] == 0).all() and (v_alt[..., d:] == 0).all()     # the padding stays untouched
 
 
 # ------------------------------------------------------------------------------ acceptance
