@@ -81,6 +81,13 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--append", action="store_true",
                     help="the step also scatters the draft tokens' K/V rows into the cache first (spin_append_kv)")
+    ap.add_argument("--decomp", default="config",
+                    help="decomposition of the batch: config (the configuration's own), none, q:<width>, kv:<length>, "
+                         "search:<max sub-requests> (the padding-minimising length search of Sec. V-A)")
+    ap.add_argument("--microbatches", type=int, default=1,
+                    help="split the batch into this many micro-batches of about equal K/V volume, issued round-robin "
+                         "on --streams streams (acceptance of one overlaps attention of the next)")
+    ap.add_argument("--streams", type=int, default=2)
     ap.add_argument("--calib-copy", action="store_true",
                     help="instead of the step, run a plain 1 GiB device copy per step (counter calibration)")
     args = ap.parse_args()
@@ -109,40 +116,102 @@ def main():
     batch = si.make_verify_batch(cfg, args.seed, device=dev)
     t = batch.table
     ab = si.make_accept_batch(t.draft_len, cfg.vocab, cfg.logit_sigma, args.seed, device=dev)
-    ctx = spin.SpinContext(0)
+    M = max(1, args.microbatches)
+    S = 1 if M == 1 else max(1, min(args.streams, M))
+    ctxs = [spin.SpinContext(0) for _ in range(S)]
     if args.waves:
-        ctx.set_waves(args.waves)
-    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+        for c in ctxs:
+            c.set_waves(args.waves)
+    streams = [torch.cuda.current_stream()] if S == 1 else [torch.cuda.Stream() for _ in range(S)]
     out = torch.empty_like(batch.q)
     n_acc = torch.empty(t.n_req, dtype=torch.int32, device=dev)
     nxt = torch.empty_like(n_acc)
-
     if args.append:
         g = torch.Generator(device="cpu").manual_seed(args.seed)
         shape = (t.n_rows, cfg.n_kv_heads, cfg.head_dim)
         k_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
         v_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
 
+    # micro-batches: contiguous request ranges of about equal K/V volume
+    tok = np.cumsum(t.prefix_len.astype(np.int64) + t.draft_len)
+    cuts = [0] + [int(np.searchsorted(tok, tok[-1] * (m + 1) / M, side="left")) + 1 for m in range(M - 1)] + [t.n_req]
+    cuts = sorted(set(min(c, t.n_req) for c in cuts))
+    mbs = []
+    for i0, i1 in zip(cuts[:-1], cuts[1:]):
+        r0, r1 = int(t.q_offset[i0]), int(t.q_offset[i1])
+        p0, p1 = int(t.pt_offset[i0]), int(t.pt_offset[i1])
+        c = ctxs[len(mbs) % S]
+        mbs.append(dict(
+            ctx=c, stream=streams[len(mbs) % S], prefix=t.prefix_len[i0:i1], draft=t.draft_len[i0:i1],
+            tab=c.make_table(t.prefix_len[i0:i1], t.draft_len[i0:i1], t.q_offset[i0:i1 + 1] - r0,
+                             t.pt_offset[i0:i1 + 1] - p0, t.page_table[p0:p1]),
+            q=batch.q[r0:r1], out=out[r0:r1], tokens=ab.draft_tokens[r0:r1], target=ab.target_logits[r0 + i0:r1 + i1],
+            dlogits=ab.draft_logits[r0:r1], u_acc=ab.u_accept[r0:r1], u_smp=ab.u_sample[i0:i1],
+            n_acc=n_acc[i0:i1], nxt=nxt[i0:i1],
+            k_new=k_new[r0:r1] if args.append else None, v_new=v_new[r0:r1] if args.append else None))
+
+    def decomposition(prefix, draft):
+        d = args.decomp
+        if d == "config":
+            d = f"q:{cfg.q_split_width}" if cfg.q_split_width else "none"
+        if d == "none":
+            return None
+        kind, _, val = d.partition(":")
+        if kind == "q":
+            return spin.decompose(prefix, draft, spin.DECOMP_Q_SPLIT, q_width=int(val))[0]
+        if kind == "kv":
+            return spin.decompose(prefix, draft, spin.DECOMP_KV_SPLIT, kv_len=int(val))[0]
+        if kind == "search":
+            return spin.decompose(prefix, draft, spin.DECOMP_KV_SEARCH, max_subreq=int(val), l_min=64,
+                                  l_max=int(prefix.max() + draft.max()), l_step=16)[0]
+        raise SystemExit(f"unknown --decomp {args.decomp}")
+
+    attn_done = [torch.cuda.Event() for _ in mbs]
+
     def step():
-        subs = None
-        if args.append:
-            ctx.append_kv(tab, batch.k_pool, batch.v_pool, k_new, v_new)
-        if cfg.q_split_width:
-            subs, _ = spin.decompose(t.prefix_len, t.draft_len, spin.DECOMP_Q_SPLIT, q_width=cfg.q_split_width)
-        ctx.verify_attn(tab, batch.k_pool, batch.v_pool, batch.q, out, cfg.n_q_heads, subs=subs)
-        ctx.accept(spin.ACCEPT_REJECTION, t.draft_len, ab.draft_tokens, ab.target_logits, ab.draft_logits,
-                   ab.u_accept, ab.u_sample, n_acc, nxt)
+        for k, mb in enumerate(mbs):
+            subs = decomposition(mb["prefix"], mb["draft"])
+            with torch.cuda.stream(mb["stream"]):
+                if S > 1:
+                    # attention kernels fill the chip: chain them, so that only the acceptance of one
+                    # micro-batch runs beside the attention of the next
+                    mb["stream"].wait_event(attn_done[k - 1])
+                if args.append:
+                    mb["ctx"].append_kv(mb["tab"], batch.k_pool, batch.v_pool, mb["k_new"], mb["v_new"])
+                mb["ctx"].verify_attn(mb["tab"], batch.k_pool, batch.v_pool, mb["q"], mb["out"], cfg.n_q_heads, subs=subs)
+                if S > 1:
+                    attn_done[k].record(mb["stream"])
+                mb["ctx"].accept(spin.ACCEPT_REJECTION, mb["draft"], mb["tokens"], mb["target"], mb["dlogits"],
+                                 mb["u_acc"], mb["u_smp"], mb["n_acc"], mb["nxt"])
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.profile_begin(args.steps)
+    for c in ctxs:
+        c.profile_begin(args.steps * len(mbs))
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms, calls = ctx.profile_end()
+    ms = {"attn": 0.0, "join": 0.0, "row_stats": 0.0, "finish": 0.0}
+    calls = [0, 0]
+    for c in ctxs:
+        m1, c1 = c.profile_end()
+        for k in ms:
+            ms[k] += m1[k]
+        calls = [calls[0] + c1[0], calls[1] + c1[1]]
+    # the host's share of a step (decomposition, scheduling, staging, launches), measured apart from the timed
+    # region with an idle GPU in front of every step so that no call waits for a staging buffer
+    host = 0.0
+    for _ in range(10):
+        torch.cuda.synchronize()
+        h0 = time.perf_counter()
+        step()
+        host += time.perf_counter() - h0
+    torch.cuda.synchronize()
+    # kernel times below are per step: the sum over the step's micro-batches
+    calls = [calls[0] / len(mbs), calls[1] / len(mbs)]
 
     ms_per_step = wall * 1e3 / args.steps
     kv_bytes = si.algorithmic_kv_bytes(t, cfg.n_kv_heads, cfg.head_dim)
@@ -158,6 +227,7 @@ def main():
         "value": t.n_rows / (ms_per_step * 1e-3),
         "unit": "verified draft tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "host_ms_per_step": host * 1e3 / 10,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.n_req} requests, {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, "
@@ -165,6 +235,7 @@ def main():
                                f"draft {cfg.draft_dist} {cfg.draft_lo}-{cfg.draft_hi}, page {cfg.page_size}, "
                                f"vocab {cfg.vocab}; " + ("KV append + " if args.append else "") +
                                "one attention layer + one rejection-sampling accept",
+                   "decomposition": args.decomp, "microbatches": len(mbs), "streams": S,
                    "seed": args.seed, "draft_rows": t.n_rows, "kv_tokens": t.kv_tokens(),
                    "kv_gb_per_step": kv_bytes / 1e9, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS},
         "kernel_ms": {"attn": attn_ms, "join": ms["join"] / max(calls[0], 1),
@@ -175,7 +246,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, batch, ab)
-    ctx.close()
+    for c in ctxs:
+        c.close()
     print(json.dumps(res))
 
 
