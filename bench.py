@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--append", action="store_true",
                     help="the step also scatters the draft tokens' K/V rows into the cache first (spin_append_kv)")
+    ap.add_argument("--tree", default="", help="drafts are token trees of this shape (random, star, wide, chain): "
+                                               "spin_verify_attn_tree instead of spin_verify_attn")
     ap.add_argument("--decomp", default="config",
                     help="decomposition of the batch: config (the configuration's own), none, q:<width>, kv:<length>, "
                          "search:<max sub-requests> (the padding-minimising length search of Sec. V-A)")
@@ -132,6 +134,7 @@ def main():
         k_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
         v_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
 
+    masks = si.random_trees(t.draft_len, np.random.default_rng(args.seed), args.tree)[1] if args.tree else None
     # micro-batches: contiguous request ranges of about equal K/V volume
     tok = np.cumsum(t.prefix_len.astype(np.int64) + t.draft_len)
     cuts = [0] + [int(np.searchsorted(tok, tok[-1] * (m + 1) / M, side="left")) + 1 for m in range(M - 1)] + [t.n_req]
@@ -147,7 +150,7 @@ def main():
                              t.pt_offset[i0:i1 + 1] - p0, t.page_table[p0:p1]),
             q=batch.q[r0:r1], out=out[r0:r1], tokens=ab.draft_tokens[r0:r1], target=ab.target_logits[r0 + i0:r1 + i1],
             dlogits=ab.draft_logits[r0:r1], u_acc=ab.u_accept[r0:r1], u_smp=ab.u_sample[i0:i1],
-            n_acc=n_acc[i0:i1], nxt=nxt[i0:i1],
+            n_acc=n_acc[i0:i1], nxt=nxt[i0:i1], masks=masks[r0:r1] if args.tree else None,
             k_new=k_new[r0:r1] if args.append else None, v_new=v_new[r0:r1] if args.append else None))
 
     def decomposition(prefix, draft):
@@ -178,7 +181,8 @@ def main():
                     mb["stream"].wait_event(attn_done[k - 1])
                 if args.append:
                     mb["ctx"].append_kv(mb["tab"], batch.k_pool, batch.v_pool, mb["k_new"], mb["v_new"])
-                mb["ctx"].verify_attn(mb["tab"], batch.k_pool, batch.v_pool, mb["q"], mb["out"], cfg.n_q_heads, subs=subs)
+                mb["ctx"].verify_attn(mb["tab"], batch.k_pool, batch.v_pool, mb["q"], mb["out"], cfg.n_q_heads, subs=subs,
+                                      tree_mask=mb["masks"])
                 if S > 1:
                     attn_done[k].record(mb["stream"])
                 mb["ctx"].accept(spin.ACCEPT_REJECTION, mb["draft"], mb["tokens"], mb["target"], mb["dlogits"],
@@ -233,7 +237,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.n_req} requests, {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, "
                                f"head_dim {cfg.head_dim}, prefix {cfg.prefix_dist} {cfg.prefix_lo}-{cfg.prefix_hi}, "
                                f"draft {cfg.draft_dist} {cfg.draft_lo}-{cfg.draft_hi}, page {cfg.page_size}, "
-                               f"vocab {cfg.vocab}; " + ("KV append + " if args.append else "") +
+                               f"vocab {cfg.vocab}; " + ("KV append + " if args.append else "") + (f"{args.tree} draft trees, " if args.tree else "") +
                                "one attention layer + one rejection-sampling accept",
                    "decomposition": args.decomp, "microbatches": len(mbs), "streams": S,
                    "seed": args.seed, "draft_rows": t.n_rows, "kv_tokens": t.kv_tokens(),

@@ -197,6 +197,20 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
                      const spin_subreq* subs, int32_t n_sub, const void* q_dev, void* o_dev,
                      int32_t n_q_heads, float softmax_scale, void* hip_stream);
 
+/* spin_verify_attn for tree-shaped drafts (the token trees of the speculative-inference systems the
+ * paper's related work names): the draft tokens of a request are the nodes of a tree whose root hangs
+ * below the last prefix token, numbered so that every node comes after its parent, and draft row t sees
+ * the whole prefix plus its ancestors and itself instead of all earlier draft tokens.
+ * tree_mask (host, [R], packed like Q): bit u of tree_mask[q_offset[i] + t] is set iff row t of request
+ * i sees draft key p_i + u.  Bit t must be set and no bit above t; draft_len <= 64; violations give
+ * SPIN_ETABLE.  A mask with bits 0..t set in every row is the linear draft of spin_verify_attn.
+ * Sub-requests tile the same causal region as in spin_verify_attn; the mask only removes cells.
+ * Everything else (arguments, layouts, asynchrony, errors) is as in spin_verify_attn. */
+int spin_verify_attn_tree(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table,
+                          const spin_subreq* subs, int32_t n_sub, const uint64_t* tree_mask,
+                          const void* q_dev, void* o_dev, int32_t n_q_heads, float softmax_scale,
+                          void* hip_stream);
+
 /* The step just before the attention: put the draft tokens' K and V rows into the paged cache, so
  * that the caller need not run a scatter of its own.  Row r of k_new_dev / v_new_dev (device, bf16
  * [R][n_kv_heads][head_dim], packed like Q) is draft token t = r - q_offset[i] of its request i and goes

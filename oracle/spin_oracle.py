@@ -70,13 +70,29 @@ def gather_request_kv(pool: np.ndarray, page_table: np.ndarray, page_size: int,
 
 
 # --------------------------------------------------------------------------- attention
+def _tree_visible(masks, p, k0, k1) -> np.ndarray:
+    """[rows, k1-k0] booleans: key j is a prefix key (j < p) or draft key p+u with bit u of the row's mask set."""
+    keys = np.arange(k0, k1)
+    out = np.ones((len(masks), k1 - k0), dtype=bool)
+    for t, m in enumerate(masks):
+        m = int(m)
+        for c, j in enumerate(keys):
+            if j >= p:
+                out[t, c] = bool((m >> int(j - p)) & 1)
+    return out
+
+
 def verify_attention(prefix_len, draft_len, q_offset, pt_offset, page_table, page_size,
                      q, k_pool, v_pool, n_q_heads, n_kv_heads, scale,
-                     requests=None, heads=None) -> np.ndarray:
+                     requests=None, heads=None, tree_mask=None) -> np.ndarray:
     """Eq. (2) per request, per query head, per draft row, over the visible keys.
 
     Returns float64 [R, n_q_heads, d].  `requests` / `heads` restrict the work to a sample
     (other entries stay NaN) so that large batches can be spot-checked.
+
+    tree_mask (uint64 [R], optional): the drafts are token trees (the related work the paper names
+    next to speculative decoding); row t then sees the prefix and those draft keys p+u whose bit
+    u is set in tree_mask[row] -- its ancestors and itself -- instead of every earlier draft key.
     """
     R = int(q_offset[-1])
     d = q.shape[-1]
@@ -96,6 +112,8 @@ def verify_attention(prefix_len, draft_len, q_offset, pt_offset, page_table, pag
             Q = _as_f64(q[r0:r0 + g, h, :])                               # [g, d]
             S = scale * (Q @ K.T)                                         # [g, n]
             visible = np.arange(n)[None, :] <= (p + np.arange(g))[:, None]
+            if tree_mask is not None:
+                visible = visible & _tree_visible(tree_mask[r0:r0 + g], p, 0, n)
             S = np.where(visible, S, NEG_INF)
             m = S.max(axis=1, keepdims=True)
             F = np.where(visible, np.exp(S - m), 0.0)                     # F(Q_i,K_j) up to e^-m
@@ -105,7 +123,7 @@ def verify_attention(prefix_len, draft_len, q_offset, pt_offset, page_table, pag
 
 
 def verify_attention_decomposed(prefix_len, draft_len, q_offset, pt_offset, page_table, page_size,
-                                q, k_pool, v_pool, n_q_heads, n_kv_heads, scale, subs) -> np.ndarray:
+                                q, k_pool, v_pool, n_q_heads, n_kv_heads, scale, subs, tree_mask=None) -> np.ndarray:
     """Attention evaluated sub-request by sub-request, then joined as Eq. (13) demands.
 
     `subs` is an int array [n_sub, 5] of (parent, q_begin, q_len, kv_begin, kv_len): a rectangle
@@ -131,6 +149,8 @@ def verify_attention_decomposed(prefix_len, draft_len, q_offset, pt_offset, page
             Q = _as_f64(q[r0:r0 + ql, h, :])
             S = scale * (Q @ K.T)
             visible = (kb + np.arange(kl))[None, :] <= (p + qb + np.arange(ql))[:, None]
+            if tree_mask is not None:
+                visible = visible & _tree_visible(tree_mask[r0:r0 + ql], p, kb, kb + kl)
             for t in range(ql):
                 vis = visible[t]
                 if not vis.any():

@@ -64,7 +64,7 @@ class SpinError(RuntimeError):
 
 EXPORTS = ["spin_create", "spin_reserve", "spin_required", "spin_destroy", "spin_strerror",
            "spin_last_error", "spin_set_waves", "spin_decompose", "spin_kv_padding",
-           "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_append_kv", "spin_accept",
+           "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_verify_attn_tree", "spin_append_kv", "spin_accept",
            "spin_profile_begin", "spin_profile_end"]
 
 _lib = None
@@ -101,6 +101,8 @@ def load_library():
                                   C.POINTER(WorkPiece), C.c_int32, _i32p]
     lib.spin_verify_attn.argtypes = [C.c_void_p, C.POINTER(KvDesc), tp, sp, C.c_int32, C.c_void_p,
                                      C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
+    lib.spin_verify_attn_tree.argtypes = [C.c_void_p, C.POINTER(KvDesc), tp, sp, C.c_int32, C.POINTER(C.c_uint64),
+                                          C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
     lib.spin_append_kv.argtypes = [C.c_void_p, C.POINTER(KvDesc), tp, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.spin_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -275,8 +277,8 @@ class SpinContext:
 
     def verify_attn(self, table: _Table, k_pool, v_pool, q, out, n_q_heads: int, subs=None,
                     softmax_scale: float = 0.0, page_size: Optional[int] = None, stream=None,
-                    strides=None):
-        """spin_verify_attn.  k_pool/v_pool: torch bf16 [n_pages][n_kv_heads][page_size][head_dim]
+                    strides=None, tree_mask=None):
+        """spin_verify_attn, or spin_verify_attn_tree when tree_mask (host uint64 [R]) is given.  k_pool/v_pool: torch bf16 [n_pages][n_kv_heads][page_size][head_dim]
         (or any layout with `strides` = (page, head, token) in elements and page_size given);
         q/out: torch bf16 [R][n_q_heads][head_dim]."""
         if strides is None:
@@ -291,6 +293,13 @@ class SpinContext:
         desc = KvDesc(k_pool.data_ptr(), v_pool.data_ptr(), n_pages, psz, n_kv, d, ps, hs, ts, DTYPE_BF16)
         sp, ns, keep = _subs_arg(subs)
         st = self._stream(stream)
+        if tree_mask is not None:
+            tm = np.ascontiguousarray(tree_mask, dtype=np.uint64)
+            assert tm.shape == (q.shape[0],)
+            self._retry(lambda: self._lib.spin_verify_attn_tree(
+                self._h, C.byref(desc), C.byref(table.struct), sp, ns, tm.ctypes.data_as(C.POINTER(C.c_uint64)),
+                C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()), n_q_heads, softmax_scale, st))
+            return
         self._retry(lambda: self._lib.spin_verify_attn(self._h, C.byref(desc), C.byref(table.struct), sp, ns,
                                                        C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()),
                                                        n_q_heads, softmax_scale, st))

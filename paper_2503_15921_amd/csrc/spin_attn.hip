@@ -62,7 +62,7 @@ __device__ __forceinline__ u32x4 stream_load(const char* base, uint32_t byte_off
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + byte_off));
 }
 
-template <int D, int NT>
+template <int D, int NT, bool TREE>
 __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     constexpr int DCH = D / 8;      // 16-byte chunks per key row
     constexpr int KCALLS = D / 32;  // MFMA calls (32 head dims each) per 16-key score tile
@@ -199,6 +199,8 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     f32x4 O[NT][8];
     float m_run[NT], l_run[NT];
     int lim[NT];
+    uint64_t anc[NT];   // TREE: draft keys (bit u = key prefix + u) each row may see
+    int pfx = 0;        // TREE: the request's prefix length
     int cb = 0;   // LDS page-id buffer of the current piece; the next piece's is (cb + 1) % 3
     {
         const int64_t head = (int64_t)(cp.head_flags & kPieceHeadMask) * P.head_stride;
@@ -213,6 +215,11 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
         for (int nt = 0; nt < NT; ++nt) {
             const int tl = (nt * 16 + m16) / G;
             lim[nt] = tl < cp.n_q ? min(cp.k1, cp.causal0 + tl) : cp.k0;
+            if (TREE) {
+                const u32x4 rec = *(const u32x4*)(P.tree_rows + (int64_t)(cp.q_row0 + (tl < cp.n_q ? tl : 0)) * 4);
+                anc[nt] = (uint64_t)rec[0] | ((uint64_t)rec[1] << 32);
+                pfx = __builtin_amdgcn_readfirstlane((int)rec[2]);
+            }
             if (!carry_in) {
                 m_run[nt] = kNegBig;
                 l_run[nt] = 0.f;
@@ -220,7 +227,8 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
                 for (int jd = 0; jd < 8; ++jd) O[nt][jd] = f32x4{0, 0, 0, 0};
             }
         }
-        const int full_end = min(cp.k1, cp.causal0);   // keys below this are visible to every row
+        // keys below this are visible to every row
+        const int full_end = TREE ? min(min(cp.k1, cp.causal0), pfx) : min(cp.k1, cp.causal0);
         const bool more = p1.k1 > p1.k0;               // another piece follows this one
         const bool new_q = more && !(p1.head_flags & kPieceCarryIn);
 
@@ -290,6 +298,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
                     for (int e = 0; e < 8; ++e) {
                         const int key = kb + (e >> 2) * 16 + g * 4 + (e & 3);
                         if (key >= lim[nt]) s[e] = -INFINITY;
+                        if (TREE && key >= pfx && !((anc[nt] >> ((key - pfx) & 63)) & 1)) s[e] = -INFINITY;
                     }
                 }
                 float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
@@ -337,7 +346,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 
         // ---- result of this piece, unless the next piece carries on with the same accumulators.
         // Lane (row, g) holds, per jd, head dims (g*4 + r)*8 + jd, r = 0..3.
-        if (!(cp.head_flags & kPieceCarryOut) && !(P.exp_flags & 1)) {
+        if (!(cp.head_flags & kPieceCarryOut)) {
             const int kvh = cp.head_flags & kPieceHeadMask;
             const bool direct = cp.head_flags & kPieceDirect;
 #pragma unroll
@@ -407,7 +416,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 // wavefront reads all NW sub-blocks: K in MFMA operand shape, V as eight keys of one 16-byte column
 // chunk per lane, transposed in registers as in the single-wavefront kernel.  Shares, pieces,
 // the look-ahead across pieces and the queue are the same, with the workgroup in the wavefront's place.
-template <int D, int NW>
+template <int D, int NW, bool TREE>
 __global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P) {
     constexpr int DCH = D / 8;
     constexpr int KCALLS = D / 32;
@@ -544,13 +553,20 @@ __global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P
         const int nn = (wave % t_eff) * 16 + m16;                // this lane's row of the strip's (draft row x head) rows
         const int tl = nn / G, hg = nn - tl * G;
         const int lim = tl < cp.n_q ? min(cp.k1, cp.causal0 + tl) : cp.k0;
+        uint64_t anc = 0;   // TREE: draft keys (bit u = key prefix + u) this lane's row may see
+        int pfx = 0;        // TREE: the request's prefix length
+        if (TREE) {
+            const u32x4 rec = *(const u32x4*)(P.tree_rows + (int64_t)(cp.q_row0 + (tl < cp.n_q ? tl : 0)) * 4);
+            anc = (uint64_t)rec[0] | ((uint64_t)rec[1] << 32);
+            pfx = __builtin_amdgcn_readfirstlane((int)rec[2]);
+        }
         if (!(cp.head_flags & kPieceCarryIn)) {
             m_run = kNegBig;
             l_run = 0.f;
 #pragma unroll
             for (int jd = 0; jd < 8; ++jd) O[jd] = f32x4{0, 0, 0, 0};
         }
-        const int full_end = min(cp.k1, cp.causal0);
+        const int full_end = TREE ? min(min(cp.k1, cp.causal0), pfx) : min(cp.k1, cp.causal0);
         const bool more = p1.k1 > p1.k0;
         const bool new_q = more && !(p1.head_flags & kPieceCarryIn);
 
@@ -611,6 +627,7 @@ __global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P
                     for (int e = 0; e < 8; ++e) {
                         const int key = kb2 + (e >> 2) * 16 + g * 4 + (e & 3);
                         if (key >= lim) s[e] = -INFINITY;
+                        if (TREE && key >= pfx && !((anc >> ((key - pfx) & 63)) & 1)) s[e] = -INFINITY;
                     }
                 }
                 float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
@@ -802,14 +819,15 @@ hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, bool TREE>
 static const void* attn_kernel_ptr(int cls) {
-    return cls == 0 ? (const void*)verify_attn_kernel<D, 1>
-         : cls == 1 ? (const void*)verify_attn_group_kernel<D, 2> : (const void*)verify_attn_group_kernel<D, 4>;
+    return cls == 0 ? (const void*)verify_attn_kernel<D, 1, TREE>
+         : cls == 1 ? (const void*)verify_attn_group_kernel<D, 2, TREE> : (const void*)verify_attn_group_kernel<D, 4, TREE>;
 }
 
 hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
-    const void* fn = head_dim == 128 ? attn_kernel_ptr<128>(cls) : attn_kernel_ptr<64>(cls);
+    // (the tree-mask variants differ by a few registers only and are launched with the same counts)
+    const void* fn = head_dim == 128 ? attn_kernel_ptr<128, false>(cls) : attn_kernel_ptr<64, false>(cls);
     int per_cu = 0, dev = 0;
     hipDeviceProp_t prop;
     hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, cls == 0 ? 64 : (cls == 1 ? 128 : 256), 0);
@@ -829,7 +847,6 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
                                 const int32_t* const wave_begin_dev[3], const int32_t n_waves[3],
                                 const int32_t n_queued[3], int32_t* queues_dev, const JoinParams& jp,
                                 hipStream_t stream, hipEvent_t ev_mid) {
-    static const int expf = getenv("SPIN_EXP_FLAGS") ? atoi(getenv("SPIN_EXP_FLAGS")) : 0;
     for (int cls = 0; cls < 3; ++cls) {
         if (n_waves[cls] <= 0) continue;
         AttnParams p = base;
@@ -837,12 +854,10 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         p.wave_begin = wave_begin_dev[cls];
         p.queue = queues_dev + cls;
         p.n_queued = n_queued[cls];
-        p.exp_flags = expf;
         dim3 grid((unsigned)n_waves[cls]);
-        if (cls == 0) hipLaunchKernelGGL((verify_attn_kernel<D, 1>), grid, dim3(64), 0, stream, p);
-        else if (cls == 1) hipLaunchKernelGGL((verify_attn_group_kernel<D, 2>), grid, dim3(128), 0, stream, p);
-        else hipLaunchKernelGGL((verify_attn_group_kernel<D, 4>), grid, dim3(256), 0, stream, p);
-        hipError_t e = hipGetLastError();
+        void* args[] = {&p};
+        const void* fn = p.tree_rows ? attn_kernel_ptr<D, true>(cls) : attn_kernel_ptr<D, false>(cls);
+        hipError_t e = hipLaunchKernel(fn, grid, dim3(64 << cls), args, 0, stream);
         if (e != hipSuccess) return e;
     }
     if (ev_mid) {

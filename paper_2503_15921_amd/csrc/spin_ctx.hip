@@ -100,7 +100,7 @@ constexpr int kMaxWaves = 16384;   // wavefronts per launch the staging buffers 
 size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
     // every share holds at least one piece, so there are at most `items` share boundaries in all
     return align16(items * sizeof(spin::Piece)) + align16(items * 4) + 3 * 32 + 2 * align16(items * 8) +
-           2 * align16((req + 1) * 4) + align16(pages * 4) + align16(rows * 8) + 128;
+           2 * align16((req + 1) * 4) + align16(pages * 4) + align16(rows * 16) + 128;
 }
 
 // Next pinned staging buffer; waits until the copy that last used it has left the host.
@@ -223,9 +223,14 @@ int spin_reserve(spin_ctx* ctx, int64_t max_req, int64_t max_rows, int64_t max_p
     return SPIN_OK;
 }
 
-int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table, const spin_subreq* subs,
-                     int32_t n_sub, const void* q_dev, void* o_dev, int32_t n_q_heads, float softmax_scale,
-                     void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Both attention entry points; tree_mask is null for linear drafts.
+int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table, const spin_subreq* subs,
+                     int32_t n_sub, const uint64_t* tree_mask, const void* q_dev, void* o_dev, int32_t n_q_heads,
+                     float softmax_scale, void* hip_stream) {
     if (!ctx) return SPIN_EINVAL;
     if (!kv || !table) return fail(ctx, SPIN_EINVAL, "kv descriptor or request table is null");
     if (kv->dtype != SPIN_DTYPE_BF16) return fail(ctx, SPIN_EUNSUPPORTED, "only bf16 K/V is supported");
@@ -250,6 +255,20 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     if (subs || n_sub != 0) {
         rc = spin::check_tiling(table, subs, n_sub, err);
         if (rc) return fail(ctx, rc, err);
+    }
+    if (tree_mask) {
+        // draft tokens come in an order that puts every ancestor before its descendants, so row t may
+        // see draft keys 0..t only, and always itself
+        for (int32_t i = 0; i < table->n_req; ++i) {
+            const int32_t g = table->draft_len[i];
+            if (g > 64) return fail(ctx, SPIN_ETABLE, "request " + std::to_string(i) + ": a draft tree holds at most 64 tokens");
+            for (int32_t t = 0; t < g; ++t) {
+                const uint64_t m = tree_mask[table->q_offset[i] + t];
+                if (!((m >> t) & 1) || (t < 63 && (m >> (t + 1))))
+                    return fail(ctx, SPIN_ETABLE, "request " + std::to_string(i) + ", draft row " + std::to_string(t) +
+                                                      ": tree mask must hold the row itself and no later token");
+            }
+        }
     }
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
@@ -308,6 +327,19 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     const size_t off_qoff = put(table->q_offset, (n_req + 1) * 4);
     const size_t off_tasks = put(plan.tasks.data(), plan.tasks.size() * 4);
     const size_t off_pt = put(table->page_table, n_pages_used * 4);
+    const size_t off_tree = off;
+    if (tree_mask) {
+        if (off + (size_t)n_rows * 16 > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
+        uint32_t* rec = (uint32_t*)(h + off);
+        for (int64_t i = 0; i < n_req; ++i)
+            for (int64_t r = table->q_offset[i]; r < table->q_offset[i + 1]; ++r, rec += 4) {
+                rec[0] = (uint32_t)tree_mask[r];
+                rec[1] = (uint32_t)(tree_mask[r] >> 32);
+                rec[2] = (uint32_t)table->prefix_len[i];
+                rec[3] = 0;
+            }
+        off = align16(off + (size_t)n_rows * 16);
+    }
     if (off > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
     // Upload on the context's own stream so that it runs beside the kernels of earlier calls; the
     // caller's stream only waits for it.  d_blob[slot] is free once the kernels of the call that
@@ -349,7 +381,7 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.n_kv_heads = kv->n_kv_heads;
     ap.group = group;
     ap.page_shift = pshift;
-    ap.exp_flags = 0;
+    ap.tree_rows = tree_mask ? (const uint32_t*)(blob + off_tree) : nullptr;
     ap.scale_log2 = scale * 1.4426950408889634f;
     const spin::Piece* pieces_dev[3];
     const int32_t* waves_dev[3];
@@ -383,6 +415,25 @@ int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     ctx->done_pending[slot] = true;
     return SPIN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int spin_verify_attn(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table, const spin_subreq* subs,
+                     int32_t n_sub, const void* q_dev, void* o_dev, int32_t n_q_heads, float softmax_scale,
+                     void* hip_stream) {
+    return verify_attn_impl(ctx, kv, table, subs, n_sub, nullptr, q_dev, o_dev, n_q_heads, softmax_scale, hip_stream);
+}
+
+int spin_verify_attn_tree(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table, const spin_subreq* subs,
+                          int32_t n_sub, const uint64_t* tree_mask, const void* q_dev, void* o_dev, int32_t n_q_heads,
+                          float softmax_scale, void* hip_stream) {
+    if (!ctx) return SPIN_EINVAL;
+    if (!tree_mask && table && table->n_req > 0 && table->q_offset && table->q_offset[table->n_req] > 0)
+        return fail(ctx, SPIN_EINVAL, "tree mask is null");
+    return verify_attn_impl(ctx, kv, table, subs, n_sub, tree_mask, q_dev, o_dev, n_q_heads, softmax_scale, hip_stream);
 }
 
 int spin_append_kv(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table, const void* k_new_dev,

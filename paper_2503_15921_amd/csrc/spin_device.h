@@ -26,9 +26,9 @@ struct AttnParams {
     float* part_o;               // [slots][kPartRow]
     float* part_ml;              // [slots][2]: running max (log2 domain), sum
     uint16_t* o;                 // final rows of pieces flagged direct
+    const uint32_t* tree_rows;   // tree-shaped drafts only, else null: [R][4] = ancestor mask (low, high), prefix length, 0
     int64_t page_stride, head_stride, token_stride;   // elements
     int32_t n_q_heads, n_kv_heads, group, page_shift;
-    int32_t exp_flags;
     float scale_log2;            // softmax scale * log2(e)
 };
 

@@ -234,6 +234,31 @@ def make_accept_batch(draft_len, vocab: int, sigma: float, seed: int, device="cp
     return AcceptBatch(draft_len, tok, target, draft, u_accept, u_sample, vocab)
 
 
+def random_trees(draft_len, rng, shape: str = "random"):
+    """Token trees for the drafts: parents [R] (index of the parent draft token within the request,
+    -1 = child of the last prefix token; always smaller than the token's own index) and the
+    ancestor-or-self bit masks [R] (uint64) that the attention entry point takes.
+    shape: "random" (uniform parent among the earlier tokens or the root), "chain", "star",
+    "wide" (a few long branches)."""
+    parents, masks = [], []
+    for g in np.asarray(draft_len):
+        par, msk = [], []
+        for t in range(int(g)):
+            if shape == "chain":
+                q = t - 1
+            elif shape == "star":
+                q = -1
+            elif shape == "wide":
+                q = t - 3 if t >= 3 else -1
+            else:
+                q = int(rng.integers(-1, t))
+            par.append(q)
+            msk.append((msk[q] if q >= 0 else 0) | (1 << t))
+        parents += par
+        masks += msk
+    return np.asarray(parents, dtype=np.int32), np.asarray(masks, dtype=np.uint64)
+
+
 def bf16_bits(t: torch.Tensor) -> np.ndarray:
     """The raw 16-bit patterns of a bf16 tensor as a uint16 numpy array (host copy)."""
     assert t.dtype == torch.bfloat16

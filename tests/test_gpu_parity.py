@@ -293,6 +293,106 @@ def test_full_size_configs_sampled(ctx, name, seed):
     print(f"{name}: sampled {len(reqs)}x{len(heads)} (request, head) pairs, max abs err {err:.2e}, rel rms {rms:.2e}")
 
 
+# ------------------------------------------------------------------------------ tree-shaped drafts
+def hip_tree_attention(ctx, batch, masks, subs=None, scale=0.0, waves=None):
+    t = batch.table
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    out = torch.full_like(batch.q, float("nan"))
+    if waves is not None:
+        ctx.set_waves(waves)
+    try:
+        ctx.verify_attn(tab, batch.k_pool, batch.v_pool, batch.q, out, batch.cfg.n_q_heads, subs=subs,
+                        softmax_scale=scale, tree_mask=masks)
+        torch.cuda.synchronize()
+    finally:
+        if waves is not None:
+            ctx.set_waves(0)
+    return out
+
+
+def oracle_tree_attention(batch, masks, scale=0.0, requests=None, heads=None):
+    t, cfg = batch.table, batch.cfg
+    if scale <= 0:
+        scale = 1.0 / math.sqrt(cfg.head_dim)
+    return orc.verify_attention(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, cfg.page_size,
+                                si.bf16_bits(batch.q), si.bf16_bits(batch.k_pool), si.bf16_bits(batch.v_pool),
+                                cfg.n_q_heads, cfg.n_kv_heads, scale, requests=requests, heads=heads, tree_mask=masks)
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(4, 4, 128), (2, 2, 64), (8, 2, 128), (16, 2, 64), (8, 1, 128)])
+@pytest.mark.parametrize("shape", ["random", "star", "wide"])
+def test_tree_masks(ctx, hq, hkv, d, shape):
+    cfg = make_cfg("tree", 7, hq, hkv, d)
+    prefix = np.array([0, 1, 15, 16, 333, 1500, 47]); draft = np.array([5, 8, 1, 3, 8, 6, 7])
+    if hq // hkv <= 4:
+        draft = draft * 2
+    b = si.make_verify_batch(cfg, 60, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
+    _, masks = si.random_trees(draft, np.random.default_rng(61), shape)
+    assert_close(hip_tree_attention(ctx, b, masks), oracle_tree_attention(b, masks), f"tree {shape} {hq}/{hkv}/{d}")
+
+
+def test_chain_tree_is_bitwise_the_linear_draft(ctx):
+    for name in ("tiny", "skewed"):
+        b = si.make_verify_batch(si.CONFIGS[name], 62, device="cuda")
+        _, masks = si.random_trees(b.table.draft_len, None, "chain")
+        assert torch.equal(hip_tree_attention(ctx, b, masks).view(torch.int16), hip_attention(ctx, b).view(torch.int16))
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_tree_masks_decomposed(ctx, seed):
+    rng = np.random.default_rng(3000 + seed)
+    group = int(rng.choice([1, 2, 4]))
+    cfg = make_cfg("tree-dec", 5, 2 * group, 2, int(rng.choice([64, 128])), page=int(rng.choice([4, 16])))
+    prefix = rng.integers(0, 900, 5); draft = rng.integers(1, 17, 5)
+    b = si.make_verify_batch(cfg, 3100 + seed, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
+    _, masks = si.random_trees(draft, rng)
+    subs = np.array([(i,) + r for i in range(5) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))],
+                    dtype=np.int32)
+    waves = int(rng.choice([1, 5, 64, 0]))
+    assert_close(hip_tree_attention(ctx, b, masks, subs=subs, waves=waves), oracle_tree_attention(b, masks),
+                 f"decomposed tree, seed {seed}")
+
+
+def test_tree_of_64_tokens(ctx):
+    cfg = make_cfg("tree64", 3, 2, 2, 128)
+    prefix = np.array([100, 0, 1031]); draft = np.array([64, 64, 33])
+    b = si.make_verify_batch(cfg, 63, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
+    _, masks = si.random_trees(draft, np.random.default_rng(64))
+    assert_close(hip_tree_attention(ctx, b, masks), oracle_tree_attention(b, masks), "64-token trees")
+
+
+def test_tree_full_size_sampled(ctx):
+    cfg = si.CONFIGS["13b"]
+    b = si.make_verify_batch(cfg, 5, device="cuda")
+    rng = np.random.default_rng(65)
+    _, masks = si.random_trees(b.table.draft_len, rng)
+    got = hip_tree_attention(ctx, b, masks)
+    assert not torch.isnan(got.float()).any()
+    reqs = sorted({int(np.argmax(b.table.draft_len)), *rng.choice(cfg.n_req, size=3, replace=False).tolist()})
+    want = oracle_tree_attention(b, masks, requests=reqs, heads=[0, cfg.n_q_heads - 1])
+    assert_close(got, want, "13b with trees")
+
+
+def test_tree_mask_errors(ctx):
+    import paper_2503_15921_amd as spin
+    cfg = make_cfg("tree-err", 2, 2, 2, 64)
+    b = si.make_verify_batch(cfg, 66, device="cuda", prefix_len=np.array([4, 9]), draft_len=np.array([3, 2]))
+    _, masks = si.random_trees(b.table.draft_len, None, "chain")
+    for r, bad in [(1, masks[1] & ~np.uint64(2)),      # the row's own bit is missing
+                   (0, masks[0] | np.uint64(4)),       # sees a later draft token
+                   (4, masks[4] | np.uint64(1 << 40))]:
+        m = masks.copy(); m[r] = bad
+        with pytest.raises(spin.SpinError) as ei:
+            hip_tree_attention(ctx, b, m)
+        assert ei.value.code == spin.ETABLE
+    # linear drafts may be longer than 64 tokens, trees may not
+    b = si.make_verify_batch(make_cfg("tree-err2", 1, 1, 1, 64), 67, device="cuda", prefix_len=np.array([4]),
+                             draft_len=np.array([65]))
+    with pytest.raises(spin.SpinError) as ei:
+        hip_tree_attention(ctx, b, np.full(65, 1, dtype=np.uint64))
+    assert ei.value.code == spin.ETABLE
+
+
 # ------------------------------------------------------------------------------ KV append
 def oracle_append(b, k_new, v_new):
     t = b.table

@@ -1,0 +1,102 @@
+"""Pins of the oracle's tree-shaped draft mask (token trees, the related work the paper names beside
+speculative decoding).  The defining property of tree attention -- every node's output equals what a
+linear draft holding just its root-to-node path would give -- is checked against the dense brute force
+of test_oracle_attention, which knows nothing about masks, pages or trees.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import spin_inputs as si
+from oracle import spin_oracle as orc
+from test_oracle_attention import tiny_problem, bits_to_float, run_oracle, random_rectangles
+
+
+def tree_oracle(table, q, kp, vp, hq, hkv, scale, masks):
+    return orc.verify_attention(table.prefix_len, table.draft_len, table.q_offset, table.pt_offset, table.page_table,
+                                table.page_size, q, kp, vp, hq, hkv, scale, tree_mask=masks)
+
+
+def path_to(parents, t):
+    """Draft indices from the tree's first level down to t, by walking the parent pointers."""
+    path = []
+    while t >= 0:
+        path.append(t)
+        t = int(parents[t])
+    return path[::-1]
+
+
+def path_attention(q_row, Kp, Vp, Kd, Vd, path, scale):
+    """Attention of one query over the prefix followed by the draft tokens on `path`: python loops, math.exp."""
+    keys = [Kp[j] for j in range(len(Kp))] + [Kd[u] for u in path]
+    vals = [Vp[j] for j in range(len(Vp))] + [Vd[u] for u in path]
+    s = [scale * sum(float(a) * float(b) for a, b in zip(q_row, k)) for k in keys]
+    mx = max(s)
+    w = [math.exp(x - mx) for x in s]
+    tot = sum(w)
+    return [sum(w[j] * float(vals[j][c]) for j in range(len(keys))) / tot for c in range(len(q_row))]
+
+
+@pytest.mark.parametrize("seed,shape", [(0, "random"), (1, "random"), (2, "wide"), (3, "star")])
+def test_every_node_equals_linear_attention_over_its_path(seed, shape):
+    prefix = np.array([5, 0, 9, 2]); draft = np.array([6, 4, 1, 9])
+    table, q, kp, vp, dk, dv = tiny_problem(seed + 30, prefix, draft, n_q_heads=2, n_kv_heads=1)
+    parents, masks = si.random_trees(draft, np.random.default_rng(seed), shape)
+    got = tree_oracle(table, q, kp, vp, 2, 1, 0.4, masks)
+    qf = bits_to_float(q)
+    for i in range(len(prefix)):
+        p, g, r0 = int(prefix[i]), int(draft[i]), int(table.q_offset[i])
+        for t in range(g):
+            path = path_to(parents[r0:r0 + g], t)
+            for h in range(2):
+                want = path_attention(qf[r0 + t, h], dk[i][:p, 0], dv[i][:p, 0], dk[i][p:, 0], dv[i][p:, 0], path, 0.4)
+                np.testing.assert_allclose(got[r0 + t, h], want, rtol=1e-11, atol=1e-13)
+
+
+def test_chain_tree_is_the_linear_draft():
+    prefix = np.array([7, 0, 3]); draft = np.array([5, 3, 8])
+    table, q, kp, vp, dk, dv = tiny_problem(40, prefix, draft)
+    _, masks = si.random_trees(draft, None, "chain")
+    np.testing.assert_array_equal(tree_oracle(table, q, kp, vp, 2, 2, 0.3, masks), run_oracle(table, q, kp, vp, 2, 2, 0.3))
+
+
+def test_star_tree_rows_ignore_their_siblings():
+    # all draft tokens are children of the last prefix token: changing token u's K/V moves row u only
+    prefix = np.array([6]); draft = np.array([5])
+    table, q, kp, vp, dk, dv = tiny_problem(41, prefix, draft)
+    _, masks = si.random_trees(draft, None, "star")
+    base = tree_oracle(table, q, kp, vp, 2, 2, 0.5, masks)
+    pt = table.page_table
+    pos = 6 + 2                                     # draft token 2
+    kp2, vp2 = kp.copy(), vp.copy()
+    kp2[pt[pos // 4], :, pos % 4, :] ^= 0x8000      # flip the sign of its K and V
+    vp2[pt[pos // 4], :, pos % 4, :] ^= 0x8000
+    moved = tree_oracle(table, q, kp2, vp2, 2, 2, 0.5, masks)
+    changed = np.any(moved != base, axis=(1, 2))
+    assert changed.tolist() == [False, False, True, False, False]
+
+
+def test_masks_from_parents_hold_exactly_the_ancestors():
+    rng = np.random.default_rng(5)
+    draft = np.array([12, 1, 30])
+    parents, masks = si.random_trees(draft, rng)
+    r0 = 0
+    for g in draft:
+        for t in range(g):
+            want = sum(1 << u for u in path_to(parents[r0:r0 + g], t))
+            assert int(masks[r0 + t]) == want
+        r0 += g
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_decomposed_tree_attention_matches_whole(seed):
+    rng = np.random.default_rng(seed + 50)
+    prefix = np.array([9, 0, 17]); draft = np.array([6, 5, 3])
+    table, q, kp, vp, dk, dv = tiny_problem(seed + 50, prefix, draft)
+    _, masks = si.random_trees(draft, rng)
+    whole = tree_oracle(table, q, kp, vp, 2, 2, 0.35, masks)
+    subs = np.array([(i,) + r for i in range(3) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))], dtype=np.int32)
+    parts = orc.verify_attention_decomposed(table.prefix_len, table.draft_len, table.q_offset, table.pt_offset,
+                                            table.page_table, table.page_size, q, kp, vp, 2, 2, 0.35, subs, tree_mask=masks)
+    np.testing.assert_allclose(parts, whole, rtol=1e-12, atol=1e-13)
