@@ -71,12 +71,61 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     constexpr int PTR = (kMaxPiecePages + 63) / 64;   // page ids per lane
     __shared__ __attribute__((aligned(16))) uint16_t sK[32 * LROW];
     __shared__ int32_t sPT[3][PTR * 64];   // page ids of the current piece and the two after it
+    // Finished rows wait here until the share ends (or the space runs out) and leave together: a store
+    // into global memory in the middle of the stream would hold up every load issued after it.
+    // Units of 4 KiB: final rows take one ([4][64] x 16 bytes), partial rows two ([8][64] x 16 bytes).
+    static_assert(NT == 1, "result staging is laid out for one column tile");
+    constexpr int kStageUnits = 6, kStageEntries = 6;
+    __shared__ u32x4 sStage[kStageUnits * 256];
+    __shared__ float sStageML[kStageEntries][32];
+    __shared__ int32_t sStageDesc[kStageEntries][4];   // head | flags, first row, rows, first partial slot
+    int st_n = 0, st_units = 0;
 
     const int lane = threadIdx.x;
     const int m16 = lane & 15, g = lane >> 4;
     const int G = P.group;
     const int pshift = P.page_shift;
     const int pmask = (1 << pshift) - 1;
+    // send the staged rows on their way; lane (m16, g) reads back exactly what it parked
+    auto flush = [&]() {
+        const int tl = m16 / G, hg = m16 - tl * G;
+        int unit = 0;
+        for (int e = 0; e < st_n; ++e) {
+            const int hf = __builtin_amdgcn_readfirstlane(sStageDesc[e][0]);
+            const int q_row0 = __builtin_amdgcn_readfirstlane(sStageDesc[e][1]);
+            const int n_q = __builtin_amdgcn_readfirstlane(sStageDesc[e][2]);
+            const int out_base = __builtin_amdgcn_readfirstlane(sStageDesc[e][3]);
+            const int kvh = hf & kPieceHeadMask;
+            const u32x4* src = sStage + unit * 256 + lane;
+            if (hf & kPieceDirect) {
+                // final rows: for fixed r the eight jd are eight consecutive head dims = 16 bytes
+                if (tl < n_q && g * 4 < DCH) {
+                    uint16_t* op = P.o + ((int64_t)(q_row0 + tl) * P.n_q_heads + kvh * G + hg) * D + g * 32;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) *(u32x4*)(op + r * 8) = src[r * 64];
+                }
+                unit += 1;
+            } else {
+                // partial rows, stored as [jd][16] so that each lane writes 16 contiguous bytes;
+                // the join kernel undoes the permutation
+                if (tl < n_q) {
+                    const int64_t slot = (int64_t)out_base + m16;
+                    float* po = P.part_o + slot * kPartRow;
+                    if (g * 4 < DCH) {
+#pragma unroll
+                        for (int jd = 0; jd < 8; ++jd) *(u32x4*)(po + jd * 16 + g * 4) = src[jd * 64];
+                    }
+                    if (g == 0) {
+                        P.part_ml[slot * 2] = sStageML[e][m16 * 2];
+                        P.part_ml[slot * 2 + 1] = sStageML[e][m16 * 2 + 1];
+                    }
+                }
+                unit += 2;
+            }
+        }
+        st_n = 0;
+        st_units = 0;
+    };
     // A wavefront first streams its own share, then takes queued chunks until none are left.
     for (int share = blockIdx.x;;) {
     const int pc_begin = P.wave_begin[share], pc_end = P.wave_begin[share + 1];
@@ -344,49 +393,38 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
             }
         }
 
-        // ---- result of this piece, unless the next piece carries on with the same accumulators.
-        // Lane (row, g) holds, per jd, head dims (g*4 + r)*8 + jd, r = 0..3.
+        // ---- result of this piece, unless the next piece carries on with the same accumulators:
+        // parked in LDS.  Lane (row, g) holds, per jd, head dims (g*4 + r)*8 + jd, r = 0..3.
         if (!(cp.head_flags & kPieceCarryOut)) {
-            const int kvh = cp.head_flags & kPieceHeadMask;
             const bool direct = cp.head_flags & kPieceDirect;
+            const int need = direct ? 1 : 2;
+            if (st_units + need > kStageUnits || st_n == kStageEntries) flush();
+            float l = l_run[0];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            u32x4* dst = sStage + st_units * 256 + lane;
+            if (direct) {
+                const float inv = 1.0f / l;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                float l = l_run[nt];
-                l += __shfl_xor(l, 16);
-                l += __shfl_xor(l, 32);
-                const int nn = nt * 16 + m16;
-                const int tl = nn / G, hg = nn - tl * G;
-                if (tl < cp.n_q) {
-                    if (direct) {
-                        // final rows: for fixed r the eight jd are eight consecutive head dims = 16 bytes
-                        const float inv = 1.0f / l;
-                        uint16_t* op = P.o + ((int64_t)(cp.q_row0 + tl) * P.n_q_heads + kvh * G + hg) * D + g * 32;
-                        if (g * 4 < DCH) {
+                for (int r = 0; r < 4; ++r)
+                    dst[r * 64] = u32x4{pack_bf16(O[0][0][r] * inv, O[0][1][r] * inv), pack_bf16(O[0][2][r] * inv, O[0][3][r] * inv),
+                                        pack_bf16(O[0][4][r] * inv, O[0][5][r] * inv), pack_bf16(O[0][6][r] * inv, O[0][7][r] * inv)};
+            } else {
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                u32x4 w = {pack_bf16(O[nt][0][r] * inv, O[nt][1][r] * inv),
-                                           pack_bf16(O[nt][2][r] * inv, O[nt][3][r] * inv),
-                                           pack_bf16(O[nt][4][r] * inv, O[nt][5][r] * inv),
-                                           pack_bf16(O[nt][6][r] * inv, O[nt][7][r] * inv)};
-                                *(u32x4*)(op + r * 8) = w;
-                            }
-                        }
-                    } else {
-                        // partial rows, stored as [jd][16] so that each lane writes 16 contiguous bytes;
-                        // the join kernel undoes the permutation
-                        const int64_t slot = (int64_t)cp.out_base + nn;
-                        float* po = P.part_o + slot * kPartRow;
-                        if (g * 4 < DCH) {
-#pragma unroll
-                            for (int jd = 0; jd < 8; ++jd) *(f32x4*)(po + jd * 16 + g * 4) = O[nt][jd];
-                        }
-                        if (g == 0) {
-                            P.part_ml[slot * 2] = m_run[nt];
-                            P.part_ml[slot * 2 + 1] = l;
-                        }
-                    }
+                for (int jd = 0; jd < 8; ++jd) dst[jd * 64] = __builtin_bit_cast(u32x4, O[0][jd]);
+                if (g == 0) {
+                    sStageML[st_n][m16 * 2] = m_run[0];
+                    sStageML[st_n][m16 * 2 + 1] = l;
                 }
             }
+            if (lane == 0) {
+                sStageDesc[st_n][0] = cp.head_flags;
+                sStageDesc[st_n][1] = cp.q_row0;
+                sStageDesc[st_n][2] = cp.n_q;
+                sStageDesc[st_n][3] = cp.out_base;
+            }
+            ++st_n;
+            st_units += need;
         }
         if (!more) break;
 
@@ -397,6 +435,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
         p2 = p3;
         fetch_piece(next_piece++, p3);
     }
+    flush();
     }
     if (P.n_queued == 0) break;
     int next = 0;
