@@ -73,11 +73,12 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     __shared__ int32_t sPT[3][PTR * 64];   // page ids of the current piece and the two after it
     // Finished rows wait here until the share ends (or the space runs out) and leave together: a store
     // into global memory in the middle of the stream would hold up every load issued after it.
-    // Units of 4 KiB: final rows take one ([4][64] x 16 bytes), partial rows two ([8][64] x 16 bytes).
-    static_assert(NT == 1, "result staging is laid out for one column tile");
+    // Units of 4 KiB per column tile: final rows take one ([4][64] x 16 bytes), partial rows two
+    // ([8][64] x 16 bytes).
+    static_assert(NT <= 2, "result staging is laid out for at most two column tiles");
     constexpr int kStageUnits = 6, kStageEntries = 6;
     __shared__ u32x4 sStage[kStageUnits * 256];
-    __shared__ float sStageML[kStageEntries][32];
+    __shared__ float sStageML[kStageEntries][NT * 32];
     __shared__ int32_t sStageDesc[kStageEntries][4];   // head | flags, first row, rows, first partial slot
     int st_n = 0, st_units = 0;
 
@@ -88,7 +89,6 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     const int pmask = (1 << pshift) - 1;
     // send the staged rows on their way; lane (m16, g) reads back exactly what it parked
     auto flush = [&]() {
-        const int tl = m16 / G, hg = m16 - tl * G;
         int unit = 0;
         for (int e = 0; e < st_n; ++e) {
             const int hf = __builtin_amdgcn_readfirstlane(sStageDesc[e][0]);
@@ -96,31 +96,37 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
             const int n_q = __builtin_amdgcn_readfirstlane(sStageDesc[e][2]);
             const int out_base = __builtin_amdgcn_readfirstlane(sStageDesc[e][3]);
             const int kvh = hf & kPieceHeadMask;
-            const u32x4* src = sStage + unit * 256 + lane;
-            if (hf & kPieceDirect) {
-                // final rows: for fixed r the eight jd are eight consecutive head dims = 16 bytes
-                if (tl < n_q && g * 4 < DCH) {
-                    uint16_t* op = P.o + ((int64_t)(q_row0 + tl) * P.n_q_heads + kvh * G + hg) * D + g * 32;
+            const bool direct = hf & kPieceDirect;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) *(u32x4*)(op + r * 8) = src[r * 64];
-                }
-                unit += 1;
-            } else {
-                // partial rows, stored as [jd][16] so that each lane writes 16 contiguous bytes;
-                // the join kernel undoes the permutation
-                if (tl < n_q) {
-                    const int64_t slot = (int64_t)out_base + m16;
-                    float* po = P.part_o + slot * kPartRow;
-                    if (g * 4 < DCH) {
+            for (int nt = 0; nt < NT; ++nt) {
+                const int nn = nt * 16 + m16;
+                const int tl = nn / G, hg = nn - tl * G;
+                const u32x4* src = sStage + unit * 256 + lane;
+                if (direct) {
+                    // final rows: for fixed r the eight jd are eight consecutive head dims = 16 bytes
+                    if (tl < n_q && g * 4 < DCH) {
+                        uint16_t* op = P.o + ((int64_t)(q_row0 + tl) * P.n_q_heads + kvh * G + hg) * D + g * 32;
 #pragma unroll
-                        for (int jd = 0; jd < 8; ++jd) *(u32x4*)(po + jd * 16 + g * 4) = src[jd * 64];
+                        for (int r = 0; r < 4; ++r) *(u32x4*)(op + r * 8) = src[r * 64];
                     }
-                    if (g == 0) {
-                        P.part_ml[slot * 2] = sStageML[e][m16 * 2];
-                        P.part_ml[slot * 2 + 1] = sStageML[e][m16 * 2 + 1];
+                    unit += 1;
+                } else {
+                    // partial rows, stored as [jd][16] so that each lane writes 16 contiguous bytes;
+                    // the join kernel undoes the permutation
+                    if (tl < n_q) {
+                        const int64_t slot = (int64_t)out_base + nn;
+                        float* po = P.part_o + slot * kPartRow;
+                        if (g * 4 < DCH) {
+#pragma unroll
+                            for (int jd = 0; jd < 8; ++jd) *(u32x4*)(po + jd * 16 + g * 4) = src[jd * 64];
+                        }
+                        if (g == 0) {
+                            P.part_ml[slot * 2] = sStageML[e][nn * 2];
+                            P.part_ml[slot * 2 + 1] = sStageML[e][nn * 2 + 1];
+                        }
                     }
+                    unit += 2;
                 }
-                unit += 2;
             }
         }
         st_n = 0;
@@ -397,24 +403,27 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
         // parked in LDS.  Lane (row, g) holds, per jd, head dims (g*4 + r)*8 + jd, r = 0..3.
         if (!(cp.head_flags & kPieceCarryOut)) {
             const bool direct = cp.head_flags & kPieceDirect;
-            const int need = direct ? 1 : 2;
+            const int need = NT * (direct ? 1 : 2);
             if (st_units + need > kStageUnits || st_n == kStageEntries) flush();
-            float l = l_run[0];
-            l += __shfl_xor(l, 16);
-            l += __shfl_xor(l, 32);
-            u32x4* dst = sStage + st_units * 256 + lane;
-            if (direct) {
-                const float inv = 1.0f / l;
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    dst[r * 64] = u32x4{pack_bf16(O[0][0][r] * inv, O[0][1][r] * inv), pack_bf16(O[0][2][r] * inv, O[0][3][r] * inv),
-                                        pack_bf16(O[0][4][r] * inv, O[0][5][r] * inv), pack_bf16(O[0][6][r] * inv, O[0][7][r] * inv)};
-            } else {
+            for (int nt = 0; nt < NT; ++nt) {
+                float l = l_run[nt];
+                l += __shfl_xor(l, 16);
+                l += __shfl_xor(l, 32);
+                u32x4* dst = sStage + (st_units + nt * (direct ? 1 : 2)) * 256 + lane;
+                if (direct) {
+                    const float inv = 1.0f / l;
 #pragma unroll
-                for (int jd = 0; jd < 8; ++jd) dst[jd * 64] = __builtin_bit_cast(u32x4, O[0][jd]);
-                if (g == 0) {
-                    sStageML[st_n][m16 * 2] = m_run[0];
-                    sStageML[st_n][m16 * 2 + 1] = l;
+                    for (int r = 0; r < 4; ++r)
+                        dst[r * 64] = u32x4{pack_bf16(O[nt][0][r] * inv, O[nt][1][r] * inv), pack_bf16(O[nt][2][r] * inv, O[nt][3][r] * inv),
+                                            pack_bf16(O[nt][4][r] * inv, O[nt][5][r] * inv), pack_bf16(O[nt][6][r] * inv, O[nt][7][r] * inv)};
+                } else {
+#pragma unroll
+                    for (int jd = 0; jd < 8; ++jd) dst[jd * 64] = __builtin_bit_cast(u32x4, O[nt][jd]);
+                    if (g == 0) {
+                        sStageML[st_n][(nt * 16 + m16) * 2] = m_run[nt];
+                        sStageML[st_n][(nt * 16 + m16) * 2 + 1] = l;
+                    }
                 }
             }
             if (lane == 0) {
@@ -861,7 +870,7 @@ hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
 template <int D, bool TREE>
 static const void* attn_kernel_ptr(int cls) {
     return cls == 0 ? (const void*)verify_attn_kernel<D, 1, TREE>
-         : cls == 1 ? (const void*)verify_attn_group_kernel<D, 2, TREE> : (const void*)verify_attn_group_kernel<D, 4, TREE>;
+         : cls == 1 ? (const void*)verify_attn_kernel<D, 2, TREE> : (const void*)verify_attn_group_kernel<D, 4, TREE>;
 }
 
 hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
@@ -869,14 +878,14 @@ hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
     const void* fn = head_dim == 128 ? attn_kernel_ptr<128, false>(cls) : attn_kernel_ptr<64, false>(cls);
     int per_cu = 0, dev = 0;
     hipDeviceProp_t prop;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, cls == 0 ? 64 : (cls == 1 ? 128 : 256), 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, cls == 2 ? 256 : 64, 0);
     if (e == hipSuccess) e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e != hipSuccess) return e;
     if (per_cu < 1) per_cu = 1;
     // the single-wavefront kernel streams best with one wavefront per SIMD: more wavefronts mean more,
     // shorter shares (more cuts and partial results) and the stream is not latency-bound
-    if (cls == 0 && per_cu > 4) per_cu = 4;
+    if (cls < 2 && per_cu > 4) per_cu = 4;
     *n_waves = per_cu * prop.multiProcessorCount;
     return hipSuccess;
 }
@@ -896,7 +905,7 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         dim3 grid((unsigned)n_waves[cls]);
         void* args[] = {&p};
         const void* fn = p.tree_rows ? attn_kernel_ptr<D, true>(cls) : attn_kernel_ptr<D, false>(cls);
-        hipError_t e = hipLaunchKernel(fn, grid, dim3(64 << cls), args, 0, stream);
+        hipError_t e = hipLaunchKernel(fn, grid, dim3(cls == 2 ? 256 : 64), args, 0, stream);
         if (e != hipSuccess) return e;
     }
     if (ev_mid) {

@@ -225,11 +225,11 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
             plan.strip_begin[s.parent + 1]++;
         }
     }
-    // One launch per call: every strip runs in the kernel instance of the widest strip (1, 2 or 4
-    // wavefronts per workgroup, 32 keys per wavefront and block).
+    // One launch per call: every strip runs in the kernel instance of the widest strip (a single
+    // wavefront for one or two column tiles, a workgroup of four wavefronts beyond that).
     int call_cls = 0;
     for (const Strip& st : plan.strips) call_cls = std::max(call_cls, st.cls);
-    const int bk = kBlockKeys << call_cls;
+    const int bk = block_keys(call_cls);
     const int window_blocks = (int)std::max<int64_t>(1, window_keys / bk);
     for (Strip& st : plan.strips) {
         st.cls = call_cls;

@@ -139,7 +139,7 @@ def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page
             assert_exact_tiling(prefix, draft, pcs[pcs[:, 5] == h][:, :5])
         widest = int((pcs[:, 2] * group).max())        # one launch per call, sized for the widest strip
         call_cls = 0 if widest <= 16 else 1 if widest <= 32 else 2
-        bk = 32 << call_cls
+        bk = 128 if call_cls == 2 else 32
         for pc in pcs:
             parent, qb, ql, kb, kl, kvh, cls, wave, flags = (int(x) for x in pc)
             assert ql * group <= 64 and cls == call_cls
