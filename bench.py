@@ -221,6 +221,9 @@ def main():
     kv_bytes = si.algorithmic_kv_bytes(t, cfg.n_kv_heads, cfg.head_dim)
     attn_ms = ms["attn"] / max(calls[0], 1)
     achieved = kv_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0
+    # strips of more than 32 (draft row x query head) rows run on the grouped-query kernel
+    group = cfg.n_q_heads // cfg.n_kv_heads
+    attn_kernel = "verify_attn_group_kernel" if min(int(t.draft_len.max()), 64 // group) * group > 32 else "verify_attn_kernel"
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
     if os.path.exists(tpath):
@@ -246,7 +249,7 @@ def main():
                       "row_stats": ms["row_stats"] / max(calls[1], 1), "finish": ms["finish"] / max(calls[1], 1)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "verify_attn_kernel", "algorithmic_bytes_per_launch": kv_bytes},
+                     "kernel": attn_kernel, "algorithmic_bytes_per_launch": kv_bytes},
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, batch, ab)
