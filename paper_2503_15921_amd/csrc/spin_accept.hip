@@ -35,6 +35,7 @@ __device__ __forceinline__ MaxArg better(MaxArg a, MaxArg b) {
 __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(AcceptParams P) {
     __shared__ MaxArg s_ma[kStatThreads / 64];
     __shared__ double s_sum[kStatThreads / 64];
+    __shared__ float s_ref[kStatThreads / 64];
     const int row = blockIdx.x;
     const int n_target = P.n_rows + P.n_req;
     const float* x = row < n_target ? P.target_logits + (int64_t)row * P.vocab
@@ -42,47 +43,101 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(AcceptParams P)
     const int V = P.vocab;
     const int tid = threadIdx.x;
     const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(x) & 15) == 0);
-
-    MaxArg best = {-INFINITY, 0x7fffffff};
-    if (vec) {
-        const float4* x4 = reinterpret_cast<const float4*>(x);
-        for (int i = tid; i < V / 4; i += kStatThreads) {
-            const float4 v = x4[i];
-            best = better(best, MaxArg{v.x, 4 * i});
-            best = better(best, MaxArg{v.y, 4 * i + 1});
-            best = better(best, MaxArg{v.z, 4 * i + 2});
-            best = better(best, MaxArg{v.w, 4 * i + 3});
-        }
-    } else {
-        for (int i = tid; i < V; i += kStatThreads) best = better(best, MaxArg{x[i], i});
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-        MaxArg o = {__shfl_xor(best.v, off), __shfl_xor(best.i, off)};
-        best = better(best, o);
-    }
-    if ((tid & 63) == 0) s_ma[tid >> 6] = best;
-    __syncthreads();
-    best = s_ma[0];
-    for (int w = 1; w < kStatThreads / 64; ++w) best = better(best, s_ma[w]);
+    const float4* x4 = reinterpret_cast<const float4*>(x);
 
     if (P.mode == SPIN_ACCEPT_GREEDY) {          // greedy matching needs the arg-max only
+        MaxArg best = {-INFINITY, 0x7fffffff};
+        if (vec) {
+            for (int i = tid; i < V / 4; i += kStatThreads) {
+                const float4 v = x4[i];
+                best = better(best, MaxArg{v.x, 4 * i});
+                best = better(best, MaxArg{v.y, 4 * i + 1});
+                best = better(best, MaxArg{v.z, 4 * i + 2});
+                best = better(best, MaxArg{v.w, 4 * i + 3});
+            }
+        } else {
+            for (int i = tid; i < V; i += kStatThreads) best = better(best, MaxArg{x[i], i});
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            MaxArg o = {__shfl_xor(best.v, off), __shfl_xor(best.i, off)};
+            best = better(best, o);
+        }
+        if ((tid & 63) == 0) s_ma[tid >> 6] = best;
+        __syncthreads();
         if (tid == 0) {
+            best = s_ma[0];
+            for (int w = 1; w < kStatThreads / 64; ++w) best = better(best, s_ma[w]);
             P.row_max[row] = best.v;
             P.row_sum[row] = 0.0;
             P.row_arg[row] = best.i;
         }
         return;
     }
-    const double mx = (double)best.v;
-    double sum = 0.0;
+
+    // Rejection sampling needs max and sum of exp(x - max).  One sweep: the exponentials are taken
+    // against a reference found in the row's first elements while the true maximum is tracked beside
+    // them, and the sum is moved to the true maximum at the end (float64 has the range for that as
+    // long as the two are within a few hundred of each other; otherwise the row is swept twice).
+    float ref = -INFINITY;
     if (vec) {
-        const float4* x4 = reinterpret_cast<const float4*>(x);
-        for (int i = tid; i < V / 4; i += kStatThreads) {
-            const float4 v = x4[i];
-            sum += exp((double)v.x - mx) + exp((double)v.y - mx) + exp((double)v.z - mx) + exp((double)v.w - mx);
+        if (tid < V / 4) {
+            const float4 v = x4[tid];
+            ref = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+        }
+    } else if (tid < V) {
+        ref = x[tid];
+    }
+    for (int off = 32; off > 0; off >>= 1) ref = fmaxf(ref, __shfl_xor(ref, off));
+    if ((tid & 63) == 0) s_ref[tid >> 6] = ref;
+    __syncthreads();
+    ref = s_ref[0];
+    for (int w = 1; w < kStatThreads / 64; ++w) ref = fmaxf(ref, s_ref[w]);
+    bool one_sweep = ref > -INFINITY && ref < INFINITY;
+
+    float m = -INFINITY;
+    double sum = 0.0;
+    if (one_sweep) {
+        const double rd = (double)ref;
+        if (vec) {
+            for (int i = tid; i < V / 4; i += kStatThreads) {
+                const float4 v = x4[i];
+                m = fmaxf(m, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+                sum += exp((double)v.x - rd) + exp((double)v.y - rd) + exp((double)v.z - rd) + exp((double)v.w - rd);
+            }
+        } else {
+            for (int i = tid; i < V; i += kStatThreads) {
+                m = fmaxf(m, x[i]);
+                sum += exp((double)x[i] - rd);
+            }
         }
     } else {
-        for (int i = tid; i < V; i += kStatThreads) sum += exp((double)x[i] - mx);
+        if (vec) {
+            for (int i = tid; i < V / 4; i += kStatThreads) {
+                const float4 v = x4[i];
+                m = fmaxf(m, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
+            }
+        } else {
+            for (int i = tid; i < V; i += kStatThreads) m = fmaxf(m, x[i]);
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    __syncthreads();                               // s_ref is reused for the maximum
+    if ((tid & 63) == 0) s_ref[tid >> 6] = m;
+    __syncthreads();
+    m = s_ref[0];
+    for (int w = 1; w < kStatThreads / 64; ++w) m = fmaxf(m, s_ref[w]);
+    if (one_sweep && !(m - ref < 500.f)) one_sweep = false;     // (the same decision in every lane)
+    const double mx = (double)m;
+    if (!one_sweep) {
+        sum = 0.0;
+        if (vec) {
+            for (int i = tid; i < V / 4; i += kStatThreads) {
+                const float4 v = x4[i];
+                sum += exp((double)v.x - mx) + exp((double)v.y - mx) + exp((double)v.z - mx) + exp((double)v.w - mx);
+            }
+        } else {
+            for (int i = tid; i < V; i += kStatThreads) sum += exp((double)x[i] - mx);
+        }
     }
     for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
     if ((tid & 63) == 0) s_sum[tid >> 6] = sum;
@@ -90,9 +145,10 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(AcceptParams P)
     if (tid == 0) {
         double tot = 0.0;
         for (int w = 0; w < kStatThreads / 64; ++w) tot += s_sum[w];
-        P.row_max[row] = best.v;
+        if (one_sweep) tot *= exp((double)ref - mx);
+        P.row_max[row] = m;
         P.row_sum[row] = tot;
-        P.row_arg[row] = best.i;
+        P.row_arg[row] = 0;
     }
 }
 

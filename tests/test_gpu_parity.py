@@ -586,6 +586,26 @@ def test_accept_extreme_uniforms(ctx):
     assert 0 <= t_g[1] < 5000
 
 
+@pytest.mark.parametrize("vocab", [6000, 5001])
+def test_accept_rows_with_a_wide_logit_range(ctx, vocab):
+    """Rows whose leading ids are far below (or minus infinity against) the rest: the row-sum kernel's
+    reference taken from the row's first elements is useless there and it has to sweep the row twice."""
+    import paper_2503_15921_amd as spin
+    draft_len = np.array([3, 5, 2, 4, 1, 6], dtype=np.int32)
+    ab = si.make_accept_batch(draft_len, vocab, 2.0, 21, device="cuda", rho=0.9)
+    R = int(draft_len.sum())
+    ab.target_logits[0:4, :1500] -= 1000.0          # first ids 1000 below the rest: beyond the one-sweep range
+    ab.draft_logits[0:3, :1500] -= 1000.0
+    ab.target_logits[5:9, :1100] = float("-inf")    # first ids excluded outright
+    ab.draft_logits[4:7, :1100] = float("-inf")
+    ab.target_logits[10:12, :1024] -= 400.0         # inside the range: still one sweep
+    ab.target_logits[12:14, 2000:] -= 2000.0        # the tail far below the head
+    ab.draft_logits[R - 3:, :1024] -= 300.0
+    # draft tokens must come from ids the (modified) draft rows still give mass to
+    ab.draft_tokens[:] = torch.clamp(ab.draft_tokens, min=1600, max=1999)
+    check_accept(ctx, spin.ACCEPT_REJECTION, ab, f"wide logit range, vocab {vocab}")
+
+
 def test_accept_token_outside_vocabulary_is_rejected(ctx):
     import paper_2503_15921_amd as spin
     draft_len = np.array([3, 2], dtype=np.int32)
