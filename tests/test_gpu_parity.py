@@ -124,6 +124,27 @@ def test_queued_tail_of_long_batch(ctx):
     assert_close(hip_attention(ctx, b, waves=64), oracle_attention(b, 0.0), "queued tail")
 
 
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (16, 2)])
+def test_very_long_context(ctx, hq, hkv):
+    # one request far longer than a piece may be (136 pages), next to short ones
+    cfg = make_cfg("long", 3, hq, hkv, 128)
+    prefix = np.array([150001, 17, 40000]); draft = np.array([8, 3, 5])
+    b = si.make_verify_batch(cfg, 23, device="cuda", prefix_len=prefix, draft_len=draft)
+    got = hip_attention(ctx, b)
+    assert not torch.isnan(got.float()).any()
+    want = oracle_attention(b, 0.0, heads=[0, hq - 1])
+    assert_close(got, want, f"long context {hq}/{hkv}")
+
+
+def test_many_short_requests(ctx):
+    rng = np.random.default_rng(24)
+    n = 3000
+    cfg = make_cfg("many", n, 2, 2, 64)
+    prefix = rng.integers(0, 41, n); draft = rng.integers(1, 5, n)
+    b = si.make_verify_batch(cfg, 24, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
+    assert_close(hip_attention(ctx, b), oracle_attention(b, 0.0), "3000 short requests")
+
+
 def test_unit_scale_peaked_softmax(ctx):
     # the literal Eq. (2) (no 1/sqrt(d)): scores ~ N(0, d), softmax dominated by a few keys, |O| ~ 1
     cfg = make_cfg("peaked", 5, 4, 4, 128)
