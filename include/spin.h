@@ -257,6 +257,11 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
  * kernel, ms[3] acceptance scan / next-token kernel; calls[0] / calls[1] = timed calls of
  * spin_verify_attn / spin_accept.  It disarms the context. */
 int spin_profile_begin(spin_ctx* ctx, int32_t max_calls);
+/* While armed, time only every n-th call of each kind (n >= 1, default 1; the first call after
+ * spin_profile_begin is timed).  Each timed call puts three event records on its stream, a few
+ * microseconds of stream time each: sampling keeps a timed run close to an untimed one.  The
+ * setting stays until changed.  max_calls of spin_profile_begin counts timed calls. */
+int spin_profile_every(spin_ctx* ctx, int32_t n);
 int spin_profile_end(spin_ctx* ctx, double ms[4], int32_t calls[2]);
 
 #ifdef __cplusplus

@@ -65,7 +65,7 @@ class SpinError(RuntimeError):
 EXPORTS = ["spin_create", "spin_reserve", "spin_required", "spin_destroy", "spin_strerror",
            "spin_last_error", "spin_set_waves", "spin_decompose", "spin_kv_padding",
            "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_verify_attn_tree", "spin_append_kv", "spin_accept",
-           "spin_profile_begin", "spin_profile_end"]
+           "spin_profile_begin", "spin_profile_every", "spin_profile_end"]
 
 _lib = None
 
@@ -108,6 +108,7 @@ def load_library():
                                 C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_void_p]
     lib.spin_profile_begin.argtypes = [C.c_void_p, C.c_int32]
+    lib.spin_profile_every.argtypes = [C.c_void_p, C.c_int32]
     lib.spin_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), _i32p]
     for name in EXPORTS:
         if name not in ("spin_destroy", "spin_strerror"):
@@ -247,7 +248,9 @@ class SpinContext:
     def set_waves(self, n_waves: int):
         _check(self._lib.spin_set_waves(self._h, n_waves), self._h)
 
-    def profile_begin(self, max_calls: int):
+    def profile_begin(self, max_calls: int, every: int = 1):
+        """Time up to max_calls calls of each kind, every `every`-th call seen."""
+        _check(self._lib.spin_profile_every(self._h, every), self._h)
         _check(self._lib.spin_profile_begin(self._h, max_calls), self._h)
 
     def profile_end(self):

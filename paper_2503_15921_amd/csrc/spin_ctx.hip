@@ -46,6 +46,8 @@ struct spin_ctx {
     // kernel timing (spin_profile_begin / _end): three events per timed call
     std::vector<hipEvent_t> prof_attn, prof_accept;
     int prof_attn_used = 0, prof_accept_used = 0;
+    int64_t prof_attn_seen = 0, prof_accept_seen = 0;   // calls seen while armed
+    int32_t prof_every = 1;                              // every n-th of them is timed
     bool prof_on = false;
 };
 
@@ -71,8 +73,8 @@ void free_profile(spin_ctx* c) {
 }
 
 // Events of the next timed call, or null when the context is not armed / has run out of slots.
-hipEvent_t* prof_slot(spin_ctx* c, std::vector<hipEvent_t>& pool, int& used) {
-    if (!c->prof_on || (size_t)(used + 1) * 3 > pool.size()) return nullptr;
+hipEvent_t* prof_slot(spin_ctx* c, std::vector<hipEvent_t>& pool, int& used, int64_t& seen) {
+    if (!c->prof_on || (seen++ % c->prof_every) != 0 || (size_t)(used + 1) * 3 > pool.size()) return nullptr;
     hipEvent_t* p = pool.data() + (size_t)used * 3;
     ++used;
     return p;
@@ -405,7 +407,7 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     int32_t max_draft = 1;
     for (int64_t i = 0; i < n_req; ++i) max_draft = std::max(max_draft, table->draft_len[i]);
     jp.max_pairs = max_draft * group;
-    hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used);
+    hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used, ctx->prof_attn_seen);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     e = spin::launch_attn(kv->head_dim, ap, pieces_dev, waves_dev, n_waves_launch, n_queued, (int32_t*)(blob + off_queues),
                           jp, stream, pe ? pe[1] : nullptr);
@@ -567,7 +569,7 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     p.n_rows = (int32_t)rows;
     p.vocab = vocab;
     p.mode = mode;
-    hipEvent_t* pe = prof_slot(ctx, ctx->prof_accept, ctx->prof_accept_used);
+    hipEvent_t* pe = prof_slot(ctx, ctx->prof_accept, ctx->prof_accept_used, ctx->prof_accept_seen);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     e = spin::launch_accept(p, stream, pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "acceptance launch");
@@ -578,8 +580,15 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     return SPIN_OK;
 }
 
+int spin_profile_every(spin_ctx* ctx, int32_t n) {
+    if (!ctx || n < 1) return SPIN_EINVAL;
+    ctx->prof_every = n;
+    return SPIN_OK;
+}
+
 int spin_profile_begin(spin_ctx* ctx, int32_t max_calls) {
     if (!ctx || max_calls < 0) return SPIN_EINVAL;
+    ctx->prof_attn_seen = ctx->prof_accept_seen = 0;
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
     free_profile(ctx);

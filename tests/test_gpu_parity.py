@@ -693,6 +693,21 @@ def test_fixed_reservation_reports_enospc():
         c.close()
 
 
+def test_profile_sampling(ctx):
+    b = si.make_verify_batch(si.CONFIGS["tiny"], 7, device="cuda")
+    ctx.profile_begin(10, every=3)
+    for _ in range(7):
+        hip_attention(ctx, b)
+    ms, calls = ctx.profile_end()
+    assert calls[0] == 3 and calls[1] == 0          # calls 0, 3 and 6 of the seven were timed
+    assert ms["attn"] > 0 and ms["row_stats"] == 0
+    ctx.profile_begin(2)                            # every call, but only two slots
+    for _ in range(4):
+        hip_attention(ctx, b)
+    ms, calls = ctx.profile_end()
+    assert calls[0] == 2
+
+
 def test_empty_batch(ctx):
     import paper_2503_15921_amd as spin
     tab = ctx.make_table(np.zeros(0, np.int32), np.zeros(0, np.int32), np.zeros(1, np.int32),
