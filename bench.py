@@ -196,7 +196,7 @@ def main():
     # The library's events time every fourth step of the timed region: three event records per timed call
     # cost about 27 us of stream time per step, which would otherwise be 4 % of the figure being measured.
     for c in ctxs:
-        c.profile_begin(args.steps * len(mbs), every=args.profile_every if len(mbs) == 1 else 1)
+        c.profile_begin(args.steps * len(mbs), every=args.profile_every)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
