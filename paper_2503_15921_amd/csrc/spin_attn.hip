@@ -26,9 +26,15 @@
 //     page ids of later pieces are fetched pieces ahead, so the stream never drains between
 //     pieces.  K/V loads are non-temporal.
 //   * A (rectangle, KV head) that one wavefront held completely, and that holds every key its
-//     rows may see, is normalised and written as bf16 at once.  Otherwise the un-normalised
-//     result (running max, sum, O) goes to a partial buffer and join_partials_kernel applies
-//     Eq. (13).
+//     rows may see, is normalised to bf16 at once.  Otherwise the un-normalised result (running
+//     max, sum, O) goes to a partial buffer and join_partials_kernel applies Eq. (13).  Either
+//     way the rows wait in LDS and are stored when the wavefront's share ends: a global store in
+//     the middle of the stream would hold up the loads issued after it.
+//   * Rectangles of up to 16 (draft row x query head) rows use one MFMA column tile per wavefront,
+//     up to 32 rows two (verify_attn_kernel<D, 1 | 2>); wider ones, up to 64 rows, go to
+//     verify_attn_group_kernel, where four wavefronts share one K/V stream through LDS.
+//   * TREE = true: drafts are token trees; a draft key is visible to a row only if the row's
+//     ancestor mask says so (checked only in the blocks that reach into the draft region).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -456,14 +462,16 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     }
 }
 
-// Grouped-query variant: a workgroup of NW wavefronts shares one K/V stream.  With G query heads
-// per KV head a strip has up to 64 (draft row x query head) rows; wavefront w owns row tile w (16
-// rows), so the per-block work of all rows runs on NW SIMDs at once while every K/V byte is
-// fetched from HBM once.  A block is 32*NW keys: each wavefront fetches its own 32 keys of it
-// (K and V both as 1 KiB-contiguous loads), parks them in LDS, and after a barrier every
-// wavefront reads all NW sub-blocks: K in MFMA operand shape, V as eight keys of one 16-byte column
-// chunk per lane, transposed in registers as in the single-wavefront kernel.  Shares, pieces,
-// the look-ahead across pieces and the queue are the same, with the workgroup in the wavefront's place.
+// Grouped-query variant (instantiated with NW = 4): a workgroup of NW wavefronts shares one K/V
+// stream.  With G query heads per KV head a strip has up to 64 (draft row x query head) rows;
+// wavefront w owns row tile w (16 rows), so the per-block work of all rows runs on NW SIMDs at once
+// while every K/V byte is fetched from HBM once.  A block is 32*NW keys: each wavefront fetches its
+// own 32 keys of it (K and V both as 1 KiB-contiguous loads) and parks them in LDS -- K in MFMA
+// operand shape, V already transposed into MFMA operands (the 8x8 register transpose of the
+// single-wavefront kernel, done once by the loading wavefront) -- and after a barrier every
+// wavefront reads the sub-blocks it needs.  Shares, pieces, the look-ahead across pieces and the
+// queue are the same, with the workgroup in the wavefront's place; results are stored as they
+// finish (a workgroup meets few ends of a (request, KV head) per share).
 template <int D, int NW, bool TREE>
 __global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P) {
     constexpr int DCH = D / 8;

@@ -15,8 +15,7 @@ namespace spin {
 // Rows of the (draft row x query head of one KV group) tile one wavefront works on: up to 4 MFMA
 // column tiles of 16.
 constexpr int kMaxTileRows = 64;
-// Keys per wavefront and streaming block of the attention kernels (a block of the grouped-query
-// kernel holds 32 keys per wavefront of its workgroup).
+// Keys per wavefront and streaming block of the attention kernels.
 constexpr int kBlockKeys = 32;
 // Keys per streaming block of the kernel that serves column-tile class c: classes 0 and 1 (one or two
 // tiles) run on single wavefronts, class 2 (up to four tiles) on workgroups of four.
