@@ -180,6 +180,7 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
     __shared__ int s_last[kWaves];
     __shared__ double s_total, s_before;
     __shared__ int s_cross;
+    __shared__ double s_tab[64];                 // 2^(j/64) for exp_table64
     const int req = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r0 = P.row_off[req];
@@ -188,6 +189,7 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
     const int n_target = P.n_rows + P.n_req;
     const int V = P.vocab;
 
+    if (wave == 1) s_tab[lane] = exp2((double)lane * (1.0 / 64.0));   // ready at the barrier below
     // ---- first-reject scan: wavefront 0 tests 64 draft rows at a time, one per lane
     if (wave == 0) {
         int n = g;
@@ -263,9 +265,9 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
             for (int j = 0; j < 4; ++j) {
                 double v = 0.0;
                 if (x0 + j < V) {
-                    v = exp((double)a[j] - tmax) * tinv;
+                    v = exp_table64((double)a[j] - tmax, s_tab) * tinv;
                     if (use_residual) {
-                        v -= exp((double)b[j] - dmax) * dinv;
+                        v -= exp_table64((double)b[j] - dmax, s_tab) * dinv;
                         v = v > 0.0 ? v : 0.0;
                     }
                 }
