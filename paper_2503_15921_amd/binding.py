@@ -224,6 +224,7 @@ class SpinContext:
         h = C.c_void_p()
         _check(self._lib.spin_create(C.byref(h), device))
         self._h = h
+        self._device = device
         self.auto_reserve = auto_reserve
 
     def close(self):
@@ -268,11 +269,12 @@ class SpinContext:
             rc = call()
         _check(rc, self._h)
 
-    @staticmethod
-    def _stream(stream):
+    def _stream(self, stream):
         import torch
         if stream is None:
-            stream = torch.cuda.current_stream()
+            # the raw handle of torch's current stream on the context's device (torch.cuda.current_stream()
+            # builds a Stream object and costs several microseconds per call)
+            return C.c_void_p(torch._C._cuda_getCurrentRawStream(self._device))
         return C.c_void_p(stream.cuda_stream)
 
     def make_table(self, prefix_len, draft_len, q_offset, pt_offset, page_table) -> _Table:
