@@ -590,6 +590,27 @@ def test_accept_odd_vocabularies_and_long_drafts(ctx, vocab):
         check_accept(ctx, spin.ACCEPT_GREEDY, ab, f"vocab {vocab} greedy rho {rho}")
 
 
+@pytest.mark.parametrize("vocab", [128256, 1048576])
+def test_accept_large_vocabularies(ctx, vocab):
+    # a current 128k-id vocabulary and the largest one the library takes
+    import paper_2503_15921_amd as spin
+    draft_len = np.array([2, 4, 1], dtype=np.int32)
+    for rho in (None, 0.98):
+        ab = si.make_accept_batch(draft_len, vocab, 2.0, 31, device="cuda", rho=rho)
+        check_accept(ctx, spin.ACCEPT_REJECTION, ab, f"vocab {vocab} rho {rho}")
+    ab = si.make_accept_batch(draft_len, vocab, 2.0, 32, device="cuda", rho=0.98, draft_token_mode="argmax")
+    check_accept(ctx, spin.ACCEPT_GREEDY, ab, f"vocab {vocab} greedy")
+
+
+def test_accept_vocabulary_beyond_the_limit_is_refused(ctx):
+    import paper_2503_15921_amd as spin
+    draft_len = np.array([1], dtype=np.int32)
+    ab = si.make_accept_batch(draft_len, (1 << 20) + 1, 2.0, 33, device="cuda")
+    with pytest.raises(spin.SpinError) as ei:
+        hip_accept(ctx, spin.ACCEPT_REJECTION, ab)
+    assert ei.value.code == spin.EUNSUPPORTED
+
+
 def test_accept_extreme_uniforms(ctx):
     # u' = 0 picks the first id with mass; u' just below 1 picks (one of) the last; u = 0 keeps, u near 1 rejects
     import paper_2503_15921_amd as spin
