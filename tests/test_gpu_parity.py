@@ -714,6 +714,29 @@ def test_fixed_reservation_reports_enospc():
         c.close()
 
 
+def test_two_contexts_on_two_streams(ctx):
+    """Calls of two contexts queued on two streams with nothing in between give what each gives alone."""
+    import paper_2503_15921_amd as spin
+    b1 = si.make_verify_batch(si.CONFIGS["7b"], 8, device="cuda")
+    b2 = si.make_verify_batch(si.CONFIGS["skewed"], 9, device="cuda")
+    alone = [hip_attention(ctx, b1), hip_attention(ctx, b2)]
+    other = spin.SpinContext(0)
+    try:
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        outs = [torch.full_like(b1.q, float("nan")), torch.full_like(b2.q, float("nan"))]
+        tabs = [c.make_table(b.table.prefix_len, b.table.draft_len, b.table.q_offset, b.table.pt_offset, b.table.page_table)
+                for c, b in ((ctx, b1), (other, b2))]
+        torch.cuda.synchronize()
+        for _ in range(6):
+            for c, b, tab, out, st in ((ctx, b1, tabs[0], outs[0], streams[0]), (other, b2, tabs[1], outs[1], streams[1])):
+                c.verify_attn(tab, b.k_pool, b.v_pool, b.q, out, b.cfg.n_q_heads, stream=st)
+        torch.cuda.synchronize()
+        for got, want in zip(outs, alone):
+            assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    finally:
+        other.close()
+
+
 def test_profile_sampling(ctx):
     b = si.make_verify_batch(si.CONFIGS["tiny"], 7, device="cuda")
     ctx.profile_begin(10, every=3)
