@@ -185,6 +185,7 @@ int spin_schedule(const spin_req_table* table, const spin_subreq* subs, int32_t 
 /* Sec. II-A1 Eq. (2) with the normalisation of Sec. V-A Eq. (13).
  *   q_dev  device, bf16 [R][n_q_heads][head_dim], R = q_offset[n_req]   (read)
  *   o_dev  device, bf16 [R][n_q_heads][head_dim]                         (every row written once)
+ *          both 16-byte aligned
  *   subs   host, n_sub sub-requests that tile the batch exactly once, or NULL for none
  *   softmax_scale  multiplies Q.K before exp; <= 0 selects 1/sqrt(head_dim); 1 is the literal
  *                  formula of Eq. (2)

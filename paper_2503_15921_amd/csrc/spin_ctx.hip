@@ -251,8 +251,8 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     if (rc) return fail(ctx, rc, err);
     if (table->n_req == 0) return SPIN_OK;
     if (!kv->k_pool || !kv->v_pool || !q_dev || !o_dev) return fail(ctx, SPIN_EINVAL, "null device pointer");
-    if (((uintptr_t)kv->k_pool | (uintptr_t)kv->v_pool | (uintptr_t)q_dev) & 15)
-        return fail(ctx, SPIN_EINVAL, "K/V pools and Q must be 16-byte aligned");
+    if (((uintptr_t)kv->k_pool | (uintptr_t)kv->v_pool | (uintptr_t)q_dev | (uintptr_t)o_dev) & 15)
+        return fail(ctx, SPIN_EINVAL, "K/V pools, Q and O must be 16-byte aligned");
     if (std::isnan(softmax_scale) || std::isinf(softmax_scale)) return fail(ctx, SPIN_EINVAL, "softmax_scale is not finite");
     if (subs || n_sub != 0) {
         rc = spin::check_tiling(table, subs, n_sub, err);
