@@ -96,6 +96,7 @@ void free_workspace(spin_ctx* c) {
     for (int s = 0; s < kStages; ++s) c->h_stage[s] = c->d_blob[s] = nullptr;
 }
 
+constexpr size_t kInPlaceBytes = 4096;   // tables up to this size are read by the kernels where the host wrote them
 constexpr int kMaxWaves = 16384;   // wavefronts per launch the staging buffers are sized for
 
 // pieces | per-class wavefront ranges | (strip, head) piece ranges | strip ranges | row offsets | tasks | page table
@@ -346,19 +347,30 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     // Upload on the context's own stream so that it runs beside the kernels of earlier calls; the
     // caller's stream only waits for it.  d_blob[slot] is free once the kernels of the call that
     // last used it are done.
+    // Small tables (a few requests) are not copied at all: the kernels read them from the pinned,
+    // device-mapped staging buffer, which saves the host four runtime calls and the stream a
+    // dependency on another stream -- what counts when the whole step takes tens of microseconds.
     const int slot = ctx->stage;
+    const bool in_place = off <= kInPlaceBytes && n_queued[0] + n_queued[1] + n_queued[2] == 0;
     char* blob = ctx->d_blob[slot];
-    if (ctx->done_pending[slot]) {
-        e = hipStreamWaitEvent(ctx->copy_stream, ctx->ev_done[slot], 0);
+    if (in_place) {
+        void* mapped = nullptr;
+        e = hipHostGetDevicePointer(&mapped, h, 0);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
+        blob = (char*)mapped;
+    } else {
+        if (ctx->done_pending[slot]) {
+            e = hipStreamWaitEvent(ctx->copy_stream, ctx->ev_done[slot], 0);
+            if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
+        }
+        e = hipMemcpyAsync(blob, h, off, hipMemcpyHostToDevice, ctx->copy_stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync");
+        e = hipEventRecord(ctx->ev[slot], ctx->copy_stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+        ctx->ev_pending[slot] = true;
+        e = hipStreamWaitEvent(stream, ctx->ev[slot], 0);
         if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
     }
-    e = hipMemcpyAsync(blob, h, off, hipMemcpyHostToDevice, ctx->copy_stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync");
-    e = hipEventRecord(ctx->ev[slot], ctx->copy_stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    ctx->ev_pending[slot] = true;
-    e = hipStreamWaitEvent(stream, ctx->ev[slot], 0);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
 
     // ---- launch
     int pshift = 0;
@@ -413,9 +425,16 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
                           jp, stream, pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
     if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    e = hipEventRecord(ctx->ev_done[slot], stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    ctx->done_pending[slot] = true;
+    if (in_place) {
+        // the staging buffer is free again once the kernels that read it are done
+        e = hipEventRecord(ctx->ev[slot], stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+        ctx->ev_pending[slot] = true;
+    } else {
+        e = hipEventRecord(ctx->ev_done[slot], stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+        ctx->done_pending[slot] = true;
+    }
     return SPIN_OK;
 }
 
