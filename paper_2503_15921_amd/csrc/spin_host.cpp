@@ -263,7 +263,31 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
         const int64_t T_dyn = (W >= kMinDynamicWaves && T / W * bk >= kMinKeysForQueue) ? T * kDynamicPercent / 100 : 0;
         const int64_t T_static = T - T_dyn;
         for (int64_t w = 1; w <= W; ++w) bounds.push_back(w * T_static / W);
-        plan.n_static[c] = (int32_t)W;
+        if (T_dyn == 0 && T / W <= kSnapShareBlocks) {
+            // Short shares (small batches, where a launch costs as much as the work): a boundary that
+            // falls within a few blocks of the end of a (strip, head) moves there, so that many such
+            // pairs stay whole, are written directly, and the join kernel may not be needed at all.
+            std::vector<int64_t>& ends = plan.unit_ends;
+            ends.clear();
+            int64_t at = 0;
+            for (const Strip& st : plan.strips) {
+                if (st.cls != c) continue;
+                const int64_t nb = (st.k1 - st.k0 + bk - 1) / bk;
+                for (int kvh = 0; kvh < n_kv_heads; ++kvh) ends.push_back(at += nb);
+            }
+            size_t u = 0, kept = 0;
+            for (size_t w = 0; w < bounds.size(); ++w) {
+                int64_t b = bounds[w];
+                while (u + 1 < ends.size() && ends[u] < b) ++u;       // ends[u]: first pair end at or after b
+                const int64_t hi = ends[u], lo = u > 0 ? ends[u - 1] : 0;
+                if (hi - b <= kSnapBlocks && hi - b <= b - lo) b = hi;
+                else if (b - lo <= kSnapBlocks) b = lo;
+                if (b > (kept ? bounds[kept - 1] : 0)) bounds[kept++] = b;   // drop shares left empty
+            }
+            bounds.resize(kept);
+            if (bounds.empty() || bounds.back() != T) bounds.push_back(T);
+        }
+        plan.n_static[c] = (int32_t)bounds.size();
         for (int64_t at = T_static; at < T;) {
             const int64_t left = T - at;
             const int64_t chunk = std::min<int64_t>(left, std::max<int64_t>(kMinChunkKeys / bk, std::min<int64_t>(kMaxChunkKeys / bk, left / W)));

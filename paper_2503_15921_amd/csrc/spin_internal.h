@@ -32,6 +32,11 @@ constexpr int kMaxChunkKeys = 1024;
 constexpr int kMinDynamicWaves = 64;
 constexpr int kMinKeysForQueue = 6144;   // keys per share below which queueing does not pay
 
+// Shares of at most kSnapShareBlocks blocks have their boundaries moved to the end of a (strip, head)
+// when one lies within kSnapBlocks blocks.
+constexpr int kSnapShareBlocks = 8;
+constexpr int kSnapBlocks = 4;
+
 constexpr int32_t kPieceHeadMask = 0xffff;
 constexpr int32_t kPieceCarryIn = 1 << 16;   // accumulators continue from the wavefront's previous piece
 constexpr int32_t kPieceCarryOut = 1 << 17;  // nothing is written; the next piece continues
@@ -69,6 +74,7 @@ struct Plan {
                                           // first the n_static per-wavefront shares, then the queued chunks
     int32_t n_static[3] = {0, 0, 0};
     std::vector<int64_t> bounds;
+    std::vector<int64_t> unit_ends;       // scratch: cumulative block count at the end of every (strip, head)
     std::vector<int32_t> ppos;            // [n_strips * n_kv_heads][2]: first piece (global index) and count
     std::vector<int32_t> tasks;           // [n_tasks][2]: (request, KV head) pairs that have partial results to join
     int64_t part_slots = 0;

@@ -157,7 +157,11 @@ def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page
             queued = np.zeros(len(per_share), dtype=bool)
             queued[c[(c[:, 8] & spin.PIECE_QUEUED) != 0][:, 7]] = True
             static = per_share[~queued]
-            assert len(static) <= n_waves and static.min() >= 1 and static.max() - static.min() <= 1
+            assert len(static) <= n_waves and static.min() >= 1
+            if static.mean() > 8.5:
+                assert static.max() - static.min() <= 1
+            else:      # short shares: boundaries within 4 blocks of the end of a (rectangle, head) moved there
+                assert static.max() <= static.mean() + 9
             if queued.any():
                 assert queued[len(static):].all() and n_waves >= 64
                 assert per_share[queued].min() >= 1 and per_share[queued].max() * bk <= 1024
@@ -179,6 +183,24 @@ def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page
                     chain_start -= 1
                 assert pcs[chain_start][3] == 0 and kb + kl == prefix[parent] + qb + ql
                 assert not (flags & spin.PIECE_CARRY_OUT)
+
+
+def test_scheduler_keeps_short_pairs_whole():
+    # many short requests: every (request, head) fits a few blocks, so no share boundary cuts one,
+    # everything is written directly and nothing is left for the join kernel
+    rng = np.random.default_rng(8)
+    prefix = rng.integers(0, 120, size=40); draft = rng.integers(1, 6, size=40)
+    pcs = spin.schedule(prefix, draft, None, 16, 1, 2, 1024)
+    ends = pcs[(pcs[:, 8] & spin.PIECE_CARRY_OUT) == 0]
+    assert len(ends) == 40 * 2 and (ends[:, 8] & spin.PIECE_DIRECT).all()
+    for h in range(2):
+        assert_exact_tiling(prefix, draft, pcs[pcs[:, 5] == h][:, :5])
+    # a long request among them is still cut
+    prefix[7] = 4000
+    pcs = spin.schedule(prefix, draft, None, 16, 1, 2, 1024)
+    assert (pcs[pcs[:, 0] == 7][:, 8] & spin.PIECE_DIRECT).sum() == 0
+    short = pcs[(pcs[:, 0] != 7) & ((pcs[:, 8] & spin.PIECE_CARRY_OUT) == 0)]
+    assert (short[:, 8] & spin.PIECE_DIRECT).mean() > 0.9
 
 
 def test_scheduler_rejoins_row_bands_sharing_a_prefix():
