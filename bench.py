@@ -90,6 +90,9 @@ def main():
                     help="split the batch into this many micro-batches of about equal K/V volume, issued round-robin "
                          "on --streams streams (acceptance of one overlaps attention of the next)")
     ap.add_argument("--streams", type=int, default=2)
+    ap.add_argument("--reuse-plan", action="store_true",
+                    help="let the library launch from the tables of the previous step (what the other layers of "
+                         "one step do); off by default: every timed step plans and uploads afresh")
     ap.add_argument("--profile-every", type=int, default=4,
                     help="the library's HIP events time every n-th step of the timed region")
     ap.add_argument("--calib-copy", action="store_true",
@@ -123,8 +126,9 @@ def main():
     M = max(1, args.microbatches)
     S = 1 if M == 1 else max(1, min(args.streams, M))
     ctxs = [spin.SpinContext(0) for _ in range(S)]
-    if args.waves:
-        for c in ctxs:
+    for c in ctxs:
+        c.set_plan_reuse(args.reuse_plan)
+        if args.waves:
             c.set_waves(args.waves)
     streams = [torch.cuda.current_stream()] if S == 1 else [torch.cuda.Stream() for _ in range(S)]
     out = torch.empty_like(batch.q)
@@ -247,7 +251,7 @@ def main():
                                f"draft {cfg.draft_dist} {cfg.draft_lo}-{cfg.draft_hi}, page {cfg.page_size}, "
                                f"vocab {cfg.vocab}; " + ("KV append + " if args.append else "") + (f"{args.tree} draft trees, " if args.tree else "") +
                                "one attention layer + one rejection-sampling accept",
-                   "decomposition": args.decomp, "microbatches": len(mbs), "streams": S,
+                   "decomposition": args.decomp, "microbatches": len(mbs), "streams": S, "plan_reuse": bool(args.reuse_plan),
                    "seed": args.seed, "draft_rows": t.n_rows, "kv_tokens": t.kv_tokens(),
                    "kv_gb_per_step": kv_bytes / 1e9, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS},
         "kernel_ms": {"attn": attn_ms, "join": ms["join"] / max(calls[0], 1),

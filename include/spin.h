@@ -248,6 +248,14 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
                 const double* u_sample_dev, int32_t* n_accepted_dev, int32_t* next_token_dev,
                 void* hip_stream);
 
+/* A transformer calls spin_verify_attn once per layer with the same request table.  The context
+ * therefore keeps the tables of its most recent attention call on the device, with a copy of what they
+ * were made from; a call whose request table, sub-requests, tree mask, head counts and page geometry are
+ * equal in content (the caller's arrays are compared, never trusted to be unchanged) launches from them
+ * again: no validation, scheduling or upload.  Pool, Q and O pointers, strides and the softmax scale may
+ * differ between such calls.  On by default; enable = 0 makes every call plan afresh. */
+int spin_set_plan_reuse(spin_ctx* ctx, int32_t enable);
+
 /* ---- measurement aid ------------------------------------------------------------------------ */
 
 /* Time the kernels of the next calls with HIP events recorded on the stream each call is given

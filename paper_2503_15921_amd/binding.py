@@ -65,7 +65,7 @@ class SpinError(RuntimeError):
 EXPORTS = ["spin_create", "spin_reserve", "spin_required", "spin_destroy", "spin_strerror",
            "spin_last_error", "spin_set_waves", "spin_decompose", "spin_kv_padding",
            "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_verify_attn_tree", "spin_append_kv", "spin_accept",
-           "spin_profile_begin", "spin_profile_every", "spin_profile_end"]
+           "spin_set_plan_reuse", "spin_profile_begin", "spin_profile_every", "spin_profile_end"]
 
 _lib = None
 
@@ -107,6 +107,7 @@ def load_library():
     lib.spin_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_void_p]
+    lib.spin_set_plan_reuse.argtypes = [C.c_void_p, C.c_int32]
     lib.spin_profile_begin.argtypes = [C.c_void_p, C.c_int32]
     lib.spin_profile_every.argtypes = [C.c_void_p, C.c_int32]
     lib.spin_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), _i32p]
@@ -248,6 +249,10 @@ class SpinContext:
 
     def set_waves(self, n_waves: int):
         _check(self._lib.spin_set_waves(self._h, n_waves), self._h)
+
+    def set_plan_reuse(self, enable: bool):
+        """Whether a call with the same tables as the previous one launches from the tables already staged."""
+        _check(self._lib.spin_set_plan_reuse(self._h, 1 if enable else 0), self._h)
 
     def profile_begin(self, max_calls: int, every: int = 1):
         """Time up to max_calls calls of each kind, every `every`-th call seen."""

@@ -17,6 +17,27 @@ inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
 }  // namespace
 
+// The tables of the most recent attention call, as staged for the GPU, and what they were made for:
+// a call with the same request table, decomposition and geometry (the other layers of the same
+// step) launches from them again without re-planning or re-uploading.
+struct StagedPlan {
+    bool valid = false;
+    int slot = -1;                  // ring slot holding the tables; kept out of the rotation while valid
+    bool in_place = false;          // read by the kernels from the pinned buffer, not copied
+    // key
+    int32_t page_size = 0, n_kv_heads = 0, head_dim = 0, n_pages = 0, n_q_heads = 0, n_sub = -1;
+    int32_t waves[3] = {0, 0, 0};
+    bool has_subs = false, has_tree = false;
+    std::vector<int32_t> prefix, draft, q_off, pt_off, pages;
+    std::vector<spin_subreq> subs;
+    std::vector<uint64_t> tree;
+    // launch data
+    size_t off_pieces = 0, off_waves[3] = {0, 0, 0}, off_queues = 0, off_ppos = 0, off_strips = 0, off_qoff = 0,
+           off_tasks = 0, off_pt = 0, off_tree = 0;
+    int32_t n_waves_launch[3] = {0, 0, 0}, n_queued[3] = {0, 0, 0}, class_piece_begin[3] = {0, 0, 0};
+    int32_t n_tasks = 0, max_pairs = 0;
+};
+
 struct spin_ctx {
     int device = 0;
     std::string err;
@@ -41,6 +62,8 @@ struct spin_ctx {
     hipEvent_t ev[kStages] = {nullptr, nullptr, nullptr, nullptr};
     bool ev_pending[kStages] = {false, false, false, false};
     int stage = 0;
+    StagedPlan staged;
+    bool reuse_plans = true;
     spin::Plan plan;
     std::vector<int32_t> row_off_host;
     // kernel timing (spin_profile_begin / _end): three events per timed call
@@ -81,6 +104,7 @@ hipEvent_t* prof_slot(spin_ctx* c, std::vector<hipEvent_t>& pool, int& used, int
 }
 
 void free_workspace(spin_ctx* c) {
+    c->staged.valid = false;
     for (int s = 0; s < kStages; ++s)
         if (c->d_blob[s]) (void)hipFree(c->d_blob[s]);
     if (c->d_part_o) (void)hipFree(c->d_part_o);
@@ -109,6 +133,7 @@ size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
 // Next pinned staging buffer; waits until the copy that last used it has left the host.
 int next_stage(spin_ctx* c, char** out) {
     c->stage = (c->stage + 1) % kStages;
+    if (c->staged.valid && c->stage == c->staged.slot) c->stage = (c->stage + 1) % kStages;   // holds a reusable plan
     const int s = c->stage;
     if (c->ev_pending[s]) {
         hipError_t e = hipEventSynchronize(c->ev[s]);
@@ -247,34 +272,9 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     if (kv->n_pages < 0 || kv->token_stride < kv->head_dim || kv->token_stride % 8 || kv->page_stride % 8 ||
         kv->head_stride % 8 || kv->page_stride < 0 || kv->head_stride < 0)
         return fail(ctx, SPIN_EINVAL, "bad K/V strides (must be non-negative multiples of 8 elements)");
-    std::string err;
-    int rc = spin::validate_table(table, kv->page_size, kv->n_pages, true, err);
-    if (rc) return fail(ctx, rc, err);
-    if (table->n_req == 0) return SPIN_OK;
-    if (!kv->k_pool || !kv->v_pool || !q_dev || !o_dev) return fail(ctx, SPIN_EINVAL, "null device pointer");
-    if (((uintptr_t)kv->k_pool | (uintptr_t)kv->v_pool | (uintptr_t)q_dev | (uintptr_t)o_dev) & 15)
-        return fail(ctx, SPIN_EINVAL, "K/V pools, Q and O must be 16-byte aligned");
-    if (std::isnan(softmax_scale) || std::isinf(softmax_scale)) return fail(ctx, SPIN_EINVAL, "softmax_scale is not finite");
-    if (subs || n_sub != 0) {
-        rc = spin::check_tiling(table, subs, n_sub, err);
-        if (rc) return fail(ctx, rc, err);
-    }
-    if (tree_mask) {
-        // draft tokens come in an order that puts every ancestor before its descendants, so row t may
-        // see draft keys 0..t only, and always itself
-        for (int32_t i = 0; i < table->n_req; ++i) {
-            const int32_t g = table->draft_len[i];
-            if (g > 64) return fail(ctx, SPIN_ETABLE, "request " + std::to_string(i) + ": a draft tree holds at most 64 tokens");
-            for (int32_t t = 0; t < g; ++t) {
-                const uint64_t m = tree_mask[table->q_offset[i] + t];
-                if (!((m >> t) & 1) || (t < 63 && (m >> (t + 1))))
-                    return fail(ctx, SPIN_ETABLE, "request " + std::to_string(i) + ", draft row " + std::to_string(t) +
-                                                      ": tree mask must hold the row itself and no later token");
-            }
-        }
-    }
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+    hipStream_t stream = (hipStream_t)hip_stream;
     // wavefronts per launch: what the device keeps resident for each kernel variant, unless overridden
     int32_t waves[3];
     const int di = kv->head_dim == 128 ? 1 : 0;
@@ -287,92 +287,169 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
         }
         waves[c] = ctx->waves_override > 0 ? ctx->waves_override : ctx->resident[di][c];
     }
-    rc = spin::build_plan(table, subs, n_sub, kv->page_size, group, kv->n_kv_heads, waves, ctx->plan, err);
-    if (rc) return fail(ctx, rc, err);
-    const spin::Plan& plan = ctx->plan;
-    const int64_t n_req = table->n_req, n_rows = table->q_offset[n_req], n_pages_used = table->pt_offset[n_req];
-    const int64_t n_items = (int64_t)plan.pieces.size();
-    if (n_req > ctx->cap_req || n_rows > ctx->cap_rows || n_pages_used > ctx->cap_pages || n_items > ctx->cap_items ||
-        plan.part_slots > ctx->cap_slots) {
-        ctx->need_req = n_req;
-        ctx->need_rows = n_rows;
-        ctx->need_pages = n_pages_used;
-        ctx->need_items = n_items;
-        ctx->need_slots = plan.part_slots;
-        return fail(ctx, SPIN_ENOSPC, "reserved workspace too small for this batch (see spin_required)");
-    }
-    hipStream_t stream = (hipStream_t)hip_stream;
+    StagedPlan& sp = ctx->staged;
+    std::string err;
+    int rc;
 
-    // ---- stage the tables
-    char* h = nullptr;
-    rc = next_stage(ctx, &h);
-    if (rc) return rc;
-    size_t off = 0;
-    auto put = [&](const void* src, size_t bytes) {
-        const size_t at = off;
-        if (bytes) memcpy(h + off, src, bytes);
-        off = align16(off + bytes);
-        return at;
-    };
-    const size_t off_pieces = put(plan.pieces.data(), n_items * sizeof(spin::Piece));
-    size_t off_waves[3];
-    int32_t n_waves_launch[3], n_queued[3];
-    for (int c = 0; c < 3; ++c) {
-        const int32_t n_shares = plan.wave_begin[c].empty() ? 0 : (int32_t)plan.wave_begin[c].size() - 1;
-        n_waves_launch[c] = plan.n_static[c];
-        n_queued[c] = n_shares - plan.n_static[c];
-        off_waves[c] = put(plan.wave_begin[c].data(), plan.wave_begin[c].size() * 4);
+    // ---- the same tables as last time?  (compared by content: the caller's arrays may have been rewritten)
+    bool hit = false;
+    if (ctx->reuse_plans && sp.valid && table->n_req > 0 && table->prefix_len && table->draft_len && table->q_offset &&
+        table->pt_offset && table->page_table && (size_t)table->n_req == sp.prefix.size() &&
+        sp.page_size == kv->page_size && sp.n_kv_heads == kv->n_kv_heads && sp.head_dim == kv->head_dim &&
+        sp.n_pages == kv->n_pages && sp.n_q_heads == n_q_heads && sp.waves[0] == waves[0] && sp.waves[1] == waves[1] &&
+        sp.waves[2] == waves[2] && sp.has_subs == (subs != nullptr) && sp.n_sub == n_sub && sp.has_tree == (tree_mask != nullptr)) {
+        const size_t n = sp.prefix.size();
+        hit = !memcmp(sp.prefix.data(), table->prefix_len, n * 4) && !memcmp(sp.draft.data(), table->draft_len, n * 4) &&
+              !memcmp(sp.q_off.data(), table->q_offset, (n + 1) * 4) && !memcmp(sp.pt_off.data(), table->pt_offset, (n + 1) * 4) &&
+              !memcmp(sp.pages.data(), table->page_table, sp.pages.size() * 4) &&
+              (!subs || !memcmp(sp.subs.data(), subs, sp.subs.size() * sizeof(spin_subreq))) &&
+              (!tree_mask || !memcmp(sp.tree.data(), tree_mask, sp.tree.size() * 8));
     }
-    const int32_t zero_queues[4] = {0, 0, 0, 0};   // the chunk queues start at zero with every upload
-    const size_t off_queues = put(zero_queues, sizeof zero_queues);
-    const size_t off_ppos = put(plan.ppos.data(), plan.ppos.size() * 4);
-    const size_t off_strips = put(plan.strip_begin.data(), (n_req + 1) * 4);
-    const size_t off_qoff = put(table->q_offset, (n_req + 1) * 4);
-    const size_t off_tasks = put(plan.tasks.data(), plan.tasks.size() * 4);
-    const size_t off_pt = put(table->page_table, n_pages_used * 4);
-    const size_t off_tree = off;
-    if (tree_mask) {
-        if (off + (size_t)n_rows * 16 > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
-        uint32_t* rec = (uint32_t*)(h + off);
-        for (int64_t i = 0; i < n_req; ++i)
-            for (int64_t r = table->q_offset[i]; r < table->q_offset[i + 1]; ++r, rec += 4) {
-                rec[0] = (uint32_t)tree_mask[r];
-                rec[1] = (uint32_t)(tree_mask[r] >> 32);
-                rec[2] = (uint32_t)table->prefix_len[i];
-                rec[3] = 0;
-            }
-        off = align16(off + (size_t)n_rows * 16);
-    }
-    if (off > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
-    // Upload on the context's own stream so that it runs beside the kernels of earlier calls; the
-    // caller's stream only waits for it.  d_blob[slot] is free once the kernels of the call that
-    // last used it are done.
-    // Small tables (a few requests) are not copied at all: the kernels read them from the pinned,
-    // device-mapped staging buffer, which saves the host four runtime calls and the stream a
-    // dependency on another stream -- what counts when the whole step takes tens of microseconds.
-    const int slot = ctx->stage;
-    const bool in_place = off <= kInPlaceBytes && n_queued[0] + n_queued[1] + n_queued[2] == 0;
-    char* blob = ctx->d_blob[slot];
-    if (in_place) {
-        void* mapped = nullptr;
-        e = hipHostGetDevicePointer(&mapped, h, 0);
-        if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
-        blob = (char*)mapped;
-    } else {
-        if (ctx->done_pending[slot]) {
-            e = hipStreamWaitEvent(ctx->copy_stream, ctx->ev_done[slot], 0);
-            if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
+    if (hit && (!kv->k_pool || !kv->v_pool || !q_dev || !o_dev)) return fail(ctx, SPIN_EINVAL, "null device pointer");
+    if (((uintptr_t)kv->k_pool | (uintptr_t)kv->v_pool | (uintptr_t)q_dev | (uintptr_t)o_dev) & 15)
+        return fail(ctx, SPIN_EINVAL, "K/V pools, Q and O must be 16-byte aligned");
+    if (std::isnan(softmax_scale) || std::isinf(softmax_scale)) return fail(ctx, SPIN_EINVAL, "softmax_scale is not finite");
+
+    if (!hit) {
+        rc = spin::validate_table(table, kv->page_size, kv->n_pages, true, err);
+        if (rc) return fail(ctx, rc, err);
+        if (table->n_req == 0) return SPIN_OK;
+        if (!kv->k_pool || !kv->v_pool || !q_dev || !o_dev) return fail(ctx, SPIN_EINVAL, "null device pointer");
+        if (subs || n_sub != 0) {
+            rc = spin::check_tiling(table, subs, n_sub, err);
+            if (rc) return fail(ctx, rc, err);
         }
-        e = hipMemcpyAsync(blob, h, off, hipMemcpyHostToDevice, ctx->copy_stream);
-        if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync");
-        e = hipEventRecord(ctx->ev[slot], ctx->copy_stream);
-        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-        ctx->ev_pending[slot] = true;
-        e = hipStreamWaitEvent(stream, ctx->ev[slot], 0);
-        if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
+        const int64_t n_req = table->n_req, n_rows = table->q_offset[n_req], n_pages_used = table->pt_offset[n_req];
+        if (tree_mask) {
+            // draft tokens come in an order that puts every ancestor before its descendants, so row t may
+            // see draft keys 0..t only, and always itself
+            for (int32_t i = 0; i < table->n_req; ++i) {
+                const int32_t g = table->draft_len[i];
+                if (g > 64) return fail(ctx, SPIN_ETABLE, "request " + std::to_string(i) + ": a draft tree holds at most 64 tokens");
+                for (int32_t t = 0; t < g; ++t) {
+                    const uint64_t m = tree_mask[table->q_offset[i] + t];
+                    if (!((m >> t) & 1) || (t < 63 && (m >> (t + 1))))
+                        return fail(ctx, SPIN_ETABLE, "request " + std::to_string(i) + ", draft row " + std::to_string(t) +
+                                                          ": tree mask must hold the row itself and no later token");
+                }
+            }
+        }
+        rc = spin::build_plan(table, subs, n_sub, kv->page_size, group, kv->n_kv_heads, waves, ctx->plan, err);
+        if (rc) return fail(ctx, rc, err);
+        const spin::Plan& plan = ctx->plan;
+        const int64_t n_items = (int64_t)plan.pieces.size();
+        if (n_req > ctx->cap_req || n_rows > ctx->cap_rows || n_pages_used > ctx->cap_pages || n_items > ctx->cap_items ||
+            plan.part_slots > ctx->cap_slots) {
+            ctx->need_req = n_req;
+            ctx->need_rows = n_rows;
+            ctx->need_pages = n_pages_used;
+            ctx->need_items = n_items;
+            ctx->need_slots = plan.part_slots;
+            return fail(ctx, SPIN_ENOSPC, "reserved workspace too small for this batch (see spin_required)");
+        }
+
+        // ---- stage the tables (the slot of the previous plan goes back into the rotation)
+        sp.valid = false;
+        char* h = nullptr;
+        rc = next_stage(ctx, &h);
+        if (rc) return rc;
+        size_t off = 0;
+        auto put = [&](const void* src, size_t bytes) {
+            const size_t at = off;
+            if (bytes) memcpy(h + off, src, bytes);
+            off = align16(off + bytes);
+            return at;
+        };
+        sp.off_pieces = put(plan.pieces.data(), n_items * sizeof(spin::Piece));
+        for (int c = 0; c < 3; ++c) {
+            const int32_t n_shares = plan.wave_begin[c].empty() ? 0 : (int32_t)plan.wave_begin[c].size() - 1;
+            sp.n_waves_launch[c] = plan.n_static[c];
+            sp.n_queued[c] = n_shares - plan.n_static[c];
+            sp.class_piece_begin[c] = plan.class_piece_begin[c];
+            sp.off_waves[c] = put(plan.wave_begin[c].data(), plan.wave_begin[c].size() * 4);
+        }
+        const int32_t zero_queues[4] = {0, 0, 0, 0};   // the chunk queues start at zero
+        sp.off_queues = put(zero_queues, sizeof zero_queues);
+        sp.off_ppos = put(plan.ppos.data(), plan.ppos.size() * 4);
+        sp.off_strips = put(plan.strip_begin.data(), (n_req + 1) * 4);
+        sp.off_qoff = put(table->q_offset, (n_req + 1) * 4);
+        sp.off_tasks = put(plan.tasks.data(), plan.tasks.size() * 4);
+        sp.off_pt = put(table->page_table, n_pages_used * 4);
+        sp.off_tree = off;
+        if (tree_mask) {
+            if (off + (size_t)n_rows * 16 > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
+            uint32_t* rec = (uint32_t*)(h + off);
+            for (int64_t i = 0; i < n_req; ++i)
+                for (int64_t r = table->q_offset[i]; r < table->q_offset[i + 1]; ++r, rec += 4) {
+                    rec[0] = (uint32_t)tree_mask[r];
+                    rec[1] = (uint32_t)(tree_mask[r] >> 32);
+                    rec[2] = (uint32_t)table->prefix_len[i];
+                    rec[3] = 0;
+                }
+            off = align16(off + (size_t)n_rows * 16);
+        }
+        if (off > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
+        sp.n_tasks = (int32_t)(plan.tasks.size() / 2);
+        int32_t max_draft = 1;
+        for (int64_t i = 0; i < n_req; ++i) max_draft = std::max(max_draft, table->draft_len[i]);
+        sp.max_pairs = max_draft * group;
+        // Upload on the context's own stream so that it runs beside the kernels of earlier calls; the
+        // caller's stream only waits for it.  d_blob[slot] is free once the kernels of the call that
+        // last used it are done.
+        // Small tables (a few requests) are not copied at all: the kernels read them from the pinned,
+        // device-mapped staging buffer, which saves the host four runtime calls and the stream a
+        // dependency on another stream -- what counts when the whole step takes tens of microseconds.
+        sp.slot = ctx->stage;
+        sp.in_place = off <= kInPlaceBytes && sp.n_queued[0] + sp.n_queued[1] + sp.n_queued[2] == 0;
+        if (!sp.in_place) {
+            if (ctx->done_pending[sp.slot]) {
+                e = hipStreamWaitEvent(ctx->copy_stream, ctx->ev_done[sp.slot], 0);
+                if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
+            }
+            e = hipMemcpyAsync(ctx->d_blob[sp.slot], h, off, hipMemcpyHostToDevice, ctx->copy_stream);
+            if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync");
+            e = hipEventRecord(ctx->ev[sp.slot], ctx->copy_stream);
+            if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+            ctx->ev_pending[sp.slot] = true;
+        }
+        // remember what these tables were made for
+        if (ctx->reuse_plans) {
+            sp.page_size = kv->page_size;
+            sp.n_kv_heads = kv->n_kv_heads;
+            sp.head_dim = kv->head_dim;
+            sp.n_pages = kv->n_pages;
+            sp.n_q_heads = n_q_heads;
+            sp.n_sub = n_sub;
+            for (int c = 0; c < 3; ++c) sp.waves[c] = waves[c];
+            sp.has_subs = subs != nullptr;
+            sp.has_tree = tree_mask != nullptr;
+            sp.prefix.assign(table->prefix_len, table->prefix_len + n_req);
+            sp.draft.assign(table->draft_len, table->draft_len + n_req);
+            sp.q_off.assign(table->q_offset, table->q_offset + n_req + 1);
+            sp.pt_off.assign(table->pt_offset, table->pt_offset + n_req + 1);
+            sp.pages.assign(table->page_table, table->page_table + n_pages_used);
+            sp.subs.assign(subs ? subs : nullptr, subs ? subs + n_sub : nullptr);
+            sp.tree.assign(tree_mask ? tree_mask : nullptr, tree_mask ? tree_mask + n_rows : nullptr);
+            sp.valid = true;
+        }
+    } else if (!sp.in_place && sp.n_queued[0] + sp.n_queued[1] + sp.n_queued[2] > 0) {
+        // the previous launch from these tables used up the chunk queues
+        e = hipMemsetAsync(ctx->d_blob[sp.slot] + sp.off_queues, 0, 16, stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipMemsetAsync");
     }
 
     // ---- launch
+    const int slot = sp.slot;
+    char* blob = ctx->d_blob[slot];
+    if (sp.in_place) {
+        void* mapped = nullptr;
+        e = hipHostGetDevicePointer(&mapped, ctx->h_stage[slot], 0);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
+        blob = (char*)mapped;
+    } else {
+        e = hipStreamWaitEvent(stream, ctx->ev[slot], 0);   // the upload (long done on a hit)
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
+    }
     int pshift = 0;
     while ((1 << pshift) < kv->page_size) ++pshift;
     const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)kv->head_dim);
@@ -384,7 +461,7 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.wave_begin = nullptr;
     ap.queue = nullptr;
     ap.n_queued = 0;
-    ap.page_table = (const int32_t*)(blob + off_pt);
+    ap.page_table = (const int32_t*)(blob + sp.off_pt);
     ap.part_o = ctx->d_part_o;
     ap.part_ml = ctx->d_part_ml;
     ap.o = (uint16_t*)o_dev;
@@ -395,37 +472,35 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.n_kv_heads = kv->n_kv_heads;
     ap.group = group;
     ap.page_shift = pshift;
-    ap.tree_rows = tree_mask ? (const uint32_t*)(blob + off_tree) : nullptr;
+    ap.tree_rows = tree_mask ? (const uint32_t*)(blob + sp.off_tree) : nullptr;
     ap.scale_log2 = scale * 1.4426950408889634f;
     const spin::Piece* pieces_dev[3];
     const int32_t* waves_dev[3];
     for (int c = 0; c < 3; ++c) {
-        pieces_dev[c] = (const spin::Piece*)(blob + off_pieces) + plan.class_piece_begin[c];
-        waves_dev[c] = (const int32_t*)(blob + off_waves[c]);
+        pieces_dev[c] = (const spin::Piece*)(blob + sp.off_pieces) + sp.class_piece_begin[c];
+        waves_dev[c] = (const int32_t*)(blob + sp.off_waves[c]);
     }
     spin::JoinParams jp = {};
-    jp.pieces = (const spin::Piece*)(blob + off_pieces);
-    jp.ppos = (const int32_t*)(blob + off_ppos);
-    jp.strip_begin = (const int32_t*)(blob + off_strips);
-    jp.q_offset = (const int32_t*)(blob + off_qoff);
-    jp.tasks = (const int32_t*)(blob + off_tasks);
+    jp.pieces = (const spin::Piece*)(blob + sp.off_pieces);
+    jp.ppos = (const int32_t*)(blob + sp.off_ppos);
+    jp.strip_begin = (const int32_t*)(blob + sp.off_strips);
+    jp.q_offset = (const int32_t*)(blob + sp.off_qoff);
+    jp.tasks = (const int32_t*)(blob + sp.off_tasks);
     jp.part_o = ctx->d_part_o;
     jp.part_ml = ctx->d_part_ml;
     jp.o = (uint16_t*)o_dev;
     jp.n_q_heads = n_q_heads;
     jp.n_kv_heads = kv->n_kv_heads;
     jp.group = group;
-    jp.n_tasks = (int32_t)(plan.tasks.size() / 2);
-    int32_t max_draft = 1;
-    for (int64_t i = 0; i < n_req; ++i) max_draft = std::max(max_draft, table->draft_len[i]);
-    jp.max_pairs = max_draft * group;
+    jp.n_tasks = sp.n_tasks;
+    jp.max_pairs = sp.max_pairs;
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used, ctx->prof_attn_seen);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    e = spin::launch_attn(kv->head_dim, ap, pieces_dev, waves_dev, n_waves_launch, n_queued, (int32_t*)(blob + off_queues),
-                          jp, stream, pe ? pe[1] : nullptr);
+    e = spin::launch_attn(kv->head_dim, ap, pieces_dev, waves_dev, sp.n_waves_launch, sp.n_queued,
+                          (int32_t*)(blob + sp.off_queues), jp, stream, pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
     if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    if (in_place) {
+    if (sp.in_place) {
         // the staging buffer is free again once the kernels that read it are done
         e = hipEventRecord(ctx->ev[slot], stream);
         if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
@@ -596,6 +671,13 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     e = hipEventRecord(ctx->ev[slot], stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     ctx->ev_pending[slot] = true;
+    return SPIN_OK;
+}
+
+int spin_set_plan_reuse(spin_ctx* ctx, int32_t enable) {
+    if (!ctx) return SPIN_EINVAL;
+    ctx->reuse_plans = enable != 0;
+    if (!enable) ctx->staged.valid = false;
     return SPIN_OK;
 }
 

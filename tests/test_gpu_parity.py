@@ -714,6 +714,83 @@ def test_fixed_reservation_reports_enospc():
         c.close()
 
 
+def test_plan_reuse_follows_the_tables_content(ctx):
+    """Calls with the same tables launch from the tables already on the device; a change of content in the
+    caller's own arrays (same objects, same addresses) is noticed; results do not depend on the reuse."""
+    cfg = make_cfg("reuse", 5, 4, 2, 128)
+    prefix = np.array([300, 17, 1000, 0, 64]); draft = np.array([4, 2, 8, 1, 3])
+    b = si.make_verify_batch(cfg, 71, device="cuda", prefix_len=prefix, draft_len=draft)
+    t = b.table
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    outs = []
+    for k in range(3):                                  # miss, hit, hit
+        out = torch.full_like(b.q, float("nan"))
+        ctx.verify_attn(tab, b.k_pool, b.v_pool, b.q, out, cfg.n_q_heads)
+        outs.append(out)
+    torch.cuda.synchronize()
+    assert_close(outs[0], oracle_attention(b, 0.0), "first call")
+    assert torch.equal(outs[1].view(torch.int16), outs[0].view(torch.int16))
+    assert torch.equal(outs[2].view(torch.int16), outs[0].view(torch.int16))
+    # other pools, queries and scale with the same tables: still a hit, different numbers
+    q2 = torch.randn_like(b.q.float()).to(torch.bfloat16)
+    out = torch.full_like(b.q, float("nan"))
+    ctx.verify_attn(tab, b.v_pool, b.k_pool, q2, out, cfg.n_q_heads, softmax_scale=0.2)
+    torch.cuda.synchronize()
+    want = orc.verify_attention(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, cfg.page_size,
+                                si.bf16_bits(q2), si.bf16_bits(b.v_pool), si.bf16_bits(b.k_pool), cfg.n_q_heads,
+                                cfg.n_kv_heads, 0.2)
+    assert_close(out, want, "same tables, other tensors")
+    # shorten two prefixes in place: the arrays the table object points to change, nothing else does
+    tab.prefix_len[0] = 123
+    tab.prefix_len[2] = 5
+    t.prefix_len[0] = 123
+    t.prefix_len[2] = 5
+    out = torch.full_like(b.q, float("nan"))
+    ctx.verify_attn(tab, b.k_pool, b.v_pool, b.q, out, cfg.n_q_heads)
+    torch.cuda.synchronize()
+    assert_close(out, oracle_attention(b, 0.0), "after an in-place change")
+    # and with reuse switched off
+    ctx.set_plan_reuse(False)
+    try:
+        again = torch.full_like(b.q, float("nan"))
+        ctx.verify_attn(tab, b.k_pool, b.v_pool, b.q, again, cfg.n_q_heads)
+        ctx.verify_attn(tab, b.k_pool, b.v_pool, b.q, again, cfg.n_q_heads)
+        torch.cuda.synchronize()
+        assert torch.equal(again.view(torch.int16), out.view(torch.int16))
+    finally:
+        ctx.set_plan_reuse(True)
+
+
+def test_plan_reuse_with_queued_chunks_and_other_calls_between(ctx):
+    # a plan with a chunk queue is launched three times (the queue counters are used up by every launch)
+    # while acceptance calls in between take staging buffers from the same ring
+    import paper_2503_15921_amd as spin
+    cfg = make_cfg("reuse-queued", 6, 8, 8, 128)
+    prefix = np.array([8100, 9000, 7000, 8500, 9500, 8000]); draft = np.array([4, 8, 1, 6, 2, 5])
+    b = si.make_verify_batch(cfg, 72, device="cuda", prefix_len=prefix, draft_len=draft)
+    ab = si.make_accept_batch(draft, 1000, 2.0, 72, device="cuda", rho=0.9)
+    n_o, t_o, margin = oracle_accept(spin.ACCEPT_REJECTION, ab)
+    t = b.table
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    ctx.set_waves(64)
+    try:
+        outs = []
+        for k in range(3):
+            out = torch.full_like(b.q, float("nan"))
+            ctx.verify_attn(tab, b.k_pool, b.v_pool, b.q, out, cfg.n_q_heads)
+            outs.append(out)
+            for _ in range(3):
+                n_g, t_g = hip_accept(ctx, spin.ACCEPT_REJECTION, ab)
+                np.testing.assert_array_equal(n_g, n_o)
+                np.testing.assert_array_equal(t_g, t_o)
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_waves(0)
+    assert_close(outs[0], oracle_attention(b, 0.0), "queued plan, first launch")
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
+
+
 def test_two_contexts_on_two_streams(ctx):
     """Calls of two contexts queued on two streams with nothing in between give what each gives alone."""
     import paper_2503_15921_amd as spin
