@@ -125,6 +125,60 @@ def blocks_of(piece, bk=32):
     return -(-int(piece[4]) // bk)
 
 
+def check_schedule(prefix, draft, subs, page, group, n_kv, n_waves):
+    """Everything a schedule must satisfy, whatever the inputs."""
+    pcs = spin.schedule(prefix, draft, subs, page, group, n_kv, n_waves)
+    for h in range(n_kv):
+        assert_exact_tiling(prefix, draft, pcs[pcs[:, 5] == h][:, :5])
+    widest = int((pcs[:, 2] * group).max())        # one launch per call, sized for the widest strip
+    call_cls = 0 if widest <= 16 else 1 if widest <= 32 else 2
+    bk = 128 if call_cls == 2 else 32
+    for pc in pcs:
+        parent, qb, ql, kb, kl, kvh, cls, wave, flags = (int(x) for x in pc)
+        assert ql * group <= 64 and cls == call_cls
+        assert kl >= 1 and (kb + kl - 1) // page - kb // page + 1 <= 136
+        assert wave >= 0
+    for cls in range(3):
+        c = pcs[pcs[:, 6] == cls]
+        if len(c) == 0:
+            continue
+        # equal shares: the wavefronts of a class differ by at most one block; queued chunks
+        # (handed out at run time) come after them and hold 1..64 blocks
+        per_share = np.zeros(int(c[:, 7].max()) + 1, dtype=np.int64)
+        for pc in c:
+            per_share[pc[7]] += blocks_of(pc, bk)
+        queued = np.zeros(len(per_share), dtype=bool)
+        queued[c[(c[:, 8] & spin.PIECE_QUEUED) != 0][:, 7]] = True
+        static = per_share[~queued]
+        assert len(static) <= n_waves and static.min() >= 1
+        if static.mean() > 8.5:
+            assert static.max() - static.min() <= 1
+        else:      # short shares: boundaries within 4 blocks of the end of a (rectangle, head) moved there
+            assert static.max() <= static.mean() + 9
+        if queued.any():
+            assert queued[len(static):].all() and n_waves >= 64
+            assert per_share[queued].min() >= 1 and per_share[queued].max() * bk <= 1024
+            assert static.min() * bk >= 5000 and 0.05 < per_share[queued].sum() / per_share.sum() < 0.15
+        # a share's pieces are consecutive in the class's streaming order
+        assert list(c[:, 7]) == sorted(c[:, 7])
+    # flags: CARRY_IN / CARRY_OUT link neighbours of one (rectangle, head) inside one wavefront;
+    # DIRECT only where one wavefront holds a whole rectangle that reaches from key 0 to its causal edge
+    for k, pc in enumerate(pcs):
+        parent, qb, ql, kb, kl, kvh, cls, wave, flags = (int(x) for x in pc)
+        same_prev = k > 0 and tuple(pcs[k - 1][[0, 1, 2, 5, 6, 7]]) == (parent, qb, ql, kvh, cls, wave) \
+            and pcs[k - 1][3] + pcs[k - 1][4] == kb
+        assert bool(flags & spin.PIECE_CARRY_IN) == bool(same_prev)
+        if flags & spin.PIECE_CARRY_IN:
+            assert pcs[k - 1][8] & spin.PIECE_CARRY_OUT
+        if flags & spin.PIECE_DIRECT:
+            chain_start = k
+            while pcs[chain_start][8] & spin.PIECE_CARRY_IN:
+                chain_start -= 1
+            assert pcs[chain_start][3] == 0 and kb + kl == prefix[parent] + qb + ql
+            assert not (flags & spin.PIECE_CARRY_OUT)
+    return pcs
+
+
 @pytest.mark.parametrize("group,n_kv,n_waves,page,top", [(1, 4, 64, 16, 3000), (1, 2, 7, 16, 3000), (8, 2, 100, 16, 3000),
                                                          (4, 1, 3, 4, 3000), (1, 3, 1000, 1, 3000), (3, 2, 16, 16, 3000),
                                                          (1, 8, 64, 16, 30000)])
@@ -134,55 +188,28 @@ def test_scheduler_pieces_tile_every_request_and_head(group, n_kv, n_waves, page
     decomps = [None, orc.decompose_q_split(prefix, draft, 4), orc.decompose_kv_split(prefix, draft, 100),
                np.array([(i,) + r for i in range(7) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))])]
     for subs in decomps:
-        pcs = spin.schedule(prefix, draft, subs, page, group, n_kv, n_waves)
-        for h in range(n_kv):
-            assert_exact_tiling(prefix, draft, pcs[pcs[:, 5] == h][:, :5])
-        widest = int((pcs[:, 2] * group).max())        # one launch per call, sized for the widest strip
-        call_cls = 0 if widest <= 16 else 1 if widest <= 32 else 2
-        bk = 128 if call_cls == 2 else 32
-        for pc in pcs:
-            parent, qb, ql, kb, kl, kvh, cls, wave, flags = (int(x) for x in pc)
-            assert ql * group <= 64 and cls == call_cls
-            assert kl >= 1 and (kb + kl - 1) // page - kb // page + 1 <= 136
-            assert wave >= 0
-        for cls in range(3):
-            c = pcs[pcs[:, 6] == cls]
-            if len(c) == 0:
-                continue
-            # equal shares: the wavefronts of a class differ by at most one block; queued chunks
-            # (handed out at run time) come after them and hold 1..64 blocks
-            per_share = np.zeros(int(c[:, 7].max()) + 1, dtype=np.int64)
-            for pc in c:
-                per_share[pc[7]] += blocks_of(pc, bk)
-            queued = np.zeros(len(per_share), dtype=bool)
-            queued[c[(c[:, 8] & spin.PIECE_QUEUED) != 0][:, 7]] = True
-            static = per_share[~queued]
-            assert len(static) <= n_waves and static.min() >= 1
-            if static.mean() > 8.5:
-                assert static.max() - static.min() <= 1
-            else:      # short shares: boundaries within 4 blocks of the end of a (rectangle, head) moved there
-                assert static.max() <= static.mean() + 9
-            if queued.any():
-                assert queued[len(static):].all() and n_waves >= 64
-                assert per_share[queued].min() >= 1 and per_share[queued].max() * bk <= 1024
-                assert static.min() * bk >= 5000 and 0.05 < per_share[queued].sum() / per_share.sum() < 0.15
-            # a share's pieces are consecutive in the class's streaming order
-            assert list(c[:, 7]) == sorted(c[:, 7])
-        # flags: CARRY_IN / CARRY_OUT link neighbours of one (rectangle, head) inside one wavefront;
-        # DIRECT only where one wavefront holds a whole rectangle that reaches from key 0 to its causal edge
-        for k, pc in enumerate(pcs):
-            parent, qb, ql, kb, kl, kvh, cls, wave, flags = (int(x) for x in pc)
-            same_prev = k > 0 and tuple(pcs[k - 1][[0, 1, 2, 5, 6, 7]]) == (parent, qb, ql, kvh, cls, wave) \
-                and pcs[k - 1][3] + pcs[k - 1][4] == kb
-            assert bool(flags & spin.PIECE_CARRY_IN) == bool(same_prev)
-            if flags & spin.PIECE_CARRY_IN:
-                assert pcs[k - 1][8] & spin.PIECE_CARRY_OUT
-            if flags & spin.PIECE_DIRECT:
-                chain_start = k
-                while pcs[chain_start][8] & spin.PIECE_CARRY_IN:
-                    chain_start -= 1
-                assert pcs[chain_start][3] == 0 and kb + kl == prefix[parent] + qb + ql
-                assert not (flags & spin.PIECE_CARRY_OUT)
+        check_schedule(prefix, draft, subs, page, group, n_kv, n_waves)
+
+
+def test_scheduler_on_many_random_small_batches():
+    rng = np.random.default_rng(77)
+    for case in range(120):
+        n_req = int(rng.integers(1, 12))
+        group = int(rng.choice([1, 1, 2, 4, 8, 16, 64]))
+        n_kv = int(rng.integers(1, 5))
+        page = int(rng.choice([1, 4, 16, 64]))
+        n_waves = int(rng.choice([1, 2, 5, 64, 300, 1024, 16384]))
+        top = int(rng.choice([8, 40, 200, 1500]))
+        prefix = rng.integers(0, top + 1, size=n_req)
+        draft = rng.integers(1, max(2, 64 // group) + 1 if rng.random() < 0.5 else 9, size=n_req)
+        kind = int(rng.integers(3))
+        subs = None if kind == 0 else orc.decompose_kv_split(prefix, draft, int(rng.integers(1, 300))) if kind == 1 else \
+            np.array([(i,) + r for i in range(n_req) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))])
+        try:
+            check_schedule(prefix, draft, subs, page, group, n_kv, n_waves)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: n_req {n_req} group {group} n_kv {n_kv} page {page} waves {n_waves} "
+                                 f"prefix {prefix.tolist()} draft {draft.tolist()} kind {kind}: {e}") from e
 
 
 def test_scheduler_keeps_short_pairs_whole():
