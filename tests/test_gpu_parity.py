@@ -153,6 +153,19 @@ def test_unit_scale_peaked_softmax(ctx):
     assert_close(hip_attention(ctx, b, scale=1.0), oracle_attention(b, 1.0), "scale 1")
 
 
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (16, 2)])
+def test_large_scores(ctx, hq, hkv):
+    # queries and keys 8x larger with the literal scale: scores of several thousand either sign, so almost
+    # every exponential underflows and each row follows one key (a hard arg-max over the visible keys)
+    cfg = make_cfg("large", 4, hq, hkv, 128)
+    prefix = np.array([33, 400, 1500, 0]); draft = np.array([4, 8, 2, 3])
+    b = si.make_verify_batch(cfg, 15, device="cuda", prefix_len=prefix, draft_len=draft)
+    b.q.mul_(8.0); b.k_pool.mul_(8.0)
+    got = hip_attention(ctx, b, scale=1.0)
+    assert torch.isfinite(got.float()).all()
+    assert_close(got, oracle_attention(b, 1.0), f"large scores {hq}/{hkv}")
+
+
 def test_draft_len_one_is_decode(ctx):
     cfg = make_cfg("decode", 8, 8, 8, 128)
     prefix = np.array([0, 17, 100, 256, 511, 512, 900, 2000]); draft = np.ones(8, dtype=np.int64)
