@@ -104,6 +104,19 @@ def test_wide_group_many_rows(ctx):
     assert_close(hip_attention(ctx, b), oracle_attention(b, 0.0), "gqa8 row bands")
 
 
+@pytest.mark.parametrize("group", [5, 6, 7, 12, 16, 32, 64])
+@pytest.mark.parametrize("d", [64, 128])
+def test_unusual_group_sizes(ctx, group, d):
+    # query heads per KV head that do not divide a 16-row tile, and multi-query extremes up to the limit of 64
+    hkv = 2 if group <= 16 else 1
+    cfg = make_cfg(f"group{group}", 5, group * hkv, hkv, d)
+    prefix = np.array([0, 31, 333, 1200, 64]); draft = np.array([1, 3, 5, 2, 13])
+    b = si.make_verify_batch(cfg, 16 + group, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True)
+    assert_close(hip_attention(ctx, b), oracle_attention(b, 0.0), f"group {group} d {d}")
+    _, masks = si.random_trees(draft, np.random.default_rng(group))
+    assert_close(hip_tree_attention(ctx, b, masks), oracle_tree_attention(b, masks), f"group {group} d {d} trees")
+
+
 @pytest.mark.parametrize("waves", [1, 2, 5, 64, 1000, 16384])
 def test_wavefront_counts(ctx, waves):
     # the same batch cut into 1 ... many shares: everything direct, long carried runs, many partial joins
