@@ -573,6 +573,33 @@ def test_accept_full_vocab(ctx, name, seed):
     assert len(seen) >= 3, "the correlated draw should spread accepted lengths"
 
 
+def test_accept_many_random_small_batches(ctx):
+    """150 random small problems (vocabularies 2-700, drafts 1-9, correlation anywhere from none to near
+    identity, both modes).  A case whose decisions sit within 1e-9 of a threshold is skipped, not failed."""
+    import paper_2503_15921_amd as spin
+    rng = np.random.default_rng(4242)
+    compared = 0
+    for case in range(150):
+        n_req = int(rng.integers(1, 7))
+        draft_len = rng.integers(1, 10, n_req).astype(np.int32)
+        vocab = int(rng.choice([2, 3, 5, 17, 64, 255, 256, 257, 700]))
+        rho = None if rng.random() < 0.2 else float(rng.choice([0.5, 0.9, 0.99, 0.9999]))
+        sigma = float(rng.choice([0.5, 2.0, 6.0]))
+        greedy = rng.random() < 0.3
+        ab = si.make_accept_batch(draft_len, vocab, sigma, 5000 + case, device="cuda", rho=rho,
+                                  draft_token_mode="argmax" if greedy else "sample")
+        mode = spin.ACCEPT_GREEDY if greedy else spin.ACCEPT_REJECTION
+        n_o, t_o, margin = oracle_accept(mode, ab)
+        if margin.min() <= 1e-9:
+            continue
+        n_g, t_g = hip_accept(ctx, mode, ab)
+        what = f"case {case}: vocab {vocab} drafts {draft_len.tolist()} rho {rho} sigma {sigma} greedy {greedy}"
+        np.testing.assert_array_equal(n_g, n_o, err_msg=what)
+        np.testing.assert_array_equal(t_g, t_o, err_msg=what)
+        compared += 1
+    assert compared >= 120
+
+
 def test_accept_planted_lengths(ctx):
     import paper_2503_15921_amd as spin
     draft_len = np.array([1, 2, 3, 4, 5, 5, 5, 5, 5, 5, 16, 16], dtype=np.int32)
