@@ -286,7 +286,7 @@ def test_other_page_sizes(ctx, page):
     assert_close(hip_attention(ctx, b), oracle_attention(b, 0.0), f"page size {page}")
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(24))
 def test_random_batches(ctx, seed):
     """Random shapes, groups, page sizes, decompositions and share counts against the oracle."""
     rng = np.random.default_rng(1000 + seed)
