@@ -71,7 +71,8 @@ _lib = None
 
 
 def lib_path() -> str:
-    return os.path.join(HERE, "libspin.so")
+    # SPIN_LIB names another build of the library (for comparing two builds in one session)
+    return os.environ.get("SPIN_LIB") or os.path.join(HERE, "libspin.so")
 
 
 def load_library():

@@ -68,10 +68,8 @@ __device__ __forceinline__ u32x4 stream_load(const char* base, uint32_t byte_off
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + byte_off));
 }
 
-// (Launched with one wavefront per SIMD; saying so lets the compiler spread the accumulators over the
-// whole register file, accumulation registers included, instead of squeezing two wavefronts' worth in.)
 template <int D, int NT, bool TREE>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1, 2))) void verify_attn_kernel(AttnParams P) {
+__global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     constexpr int DCH = D / 8;      // 16-byte chunks per key row
     constexpr int KCALLS = D / 32;  // MFMA calls (32 head dims each) per 16-key score tile
     constexpr int KLOADS = DCH / 2; // 16-byte loads per lane for 32 keys of K
