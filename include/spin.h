@@ -24,7 +24,10 @@
  *   - Request i has prefix length p_i >= 0 (tokens whose K/V are cached and that ask nothing)
  *     and draft length g_i >= 1 (tokens whose K/V are ALSO already in the cache, at positions
  *     p_i .. p_i+g_i-1, and which each issue one query row).  Draft row t sees keys 0 .. p_i+t.
- *   - One context must not be used from two host threads at once.
+ *   - One context must not be used from two host threads at once, and its calls share one
+ *     workspace (partial results, row statistics): give them one stream, or order the streams
+ *     yourself.  Work that is meant to overlap on the GPU takes one context per stream.
+ *   - "never writes to an input" has one exception, stated there: spin_append_kv writes the pools.
  */
 #ifndef SPIN_H
 #define SPIN_H
