@@ -251,6 +251,21 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
                 const double* u_sample_dev, int32_t* n_accepted_dev, int32_t* next_token_dev,
                 void* hip_stream);
 
+/* Greedy verification of token trees, the companion of spin_verify_attn_tree.  Draft token t of request
+ * i hangs below token parent_host[q_offset[i] + t] of the same request (an earlier token, or -1 = the
+ * last prefix token); draft_len <= 64.  Target row q_offset[i] + i is the model's output after the
+ * prefix, row q_offset[i] + i + 1 + t its output after token t (for a chain this is the layout of
+ * spin_accept).  The walk starts below the last prefix token and moves to the lowest-numbered child
+ * whose token equals the arg-max (lowest id on ties) of the current node's row, until no child does:
+ *   n_accepted_dev[i]            number of tokens on that path
+ *   path_dev[q_offset[i] + k]    its k-th token, k < n_accepted; -1 in the request's other entries
+ *   next_token_dev[i]            the arg-max of the row of the last token reached (the root's if none)
+ * The vocabulary is not limited here.  Acceptance by rejection sampling over trees (several candidate
+ * children per node) is not provided.  Errors as for spin_accept, plus SPIN_ETABLE for a bad parent. */
+int spin_accept_tree(spin_ctx* ctx, int32_t n_req, const int32_t* draft_len_host, const int32_t* parent_host,
+                     const int32_t* draft_tokens_dev, const float* target_logits_dev, int32_t vocab,
+                     int32_t* n_accepted_dev, int32_t* path_dev, int32_t* next_token_dev, void* hip_stream);
+
 /* A transformer calls spin_verify_attn once per layer with the same request table.  The context
  * therefore keeps the tables of its most recent attention call on the device, with a copy of what they
  * were made from; a call whose request table, sub-requests, tree mask, head counts and page geometry are

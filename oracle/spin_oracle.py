@@ -14,6 +14,7 @@ What it follows
                                  all tokens of the ORIGINAL request in the batch.
   * append_kv                -- the KV cache of Sec. II-A1: the candidate tokens' K/V enter the
                                  cache at the positions after the prefix (plain scatter).
+  * accept_tree_greedy       -- greedy verification of token trees (related work of Sec. I).
   * decompose_*              -- Sec. V-A: request decomposition and the choice of the
                                  KV-tensor length L for a fixed width B.
   * accept_greedy / accept_rejection -- the verification phase of Sec. II-A2 ("tokens
@@ -285,6 +286,45 @@ def accept_greedy(draft_len, draft_tokens, target_logits):
         n_acc[i] = n
         r += g
     return n_acc, nxt, margin
+
+
+def accept_tree_greedy(draft_len, parents, draft_tokens, target_logits):
+    """Greedy verification of token trees (the token trees of the related work named in Sec. I).
+
+    Draft token t of request i hangs below token parents[r+t] of the same request (-1: the last
+    prefix token).  Request i owns target rows base..base+g_i, base = q_offset[i] + i: row base is the
+    model's output after the prefix, row base+1+t its output after token t.  From the root, move to
+    the lowest-numbered child whose token equals the arg-max of the current node's row; stop when
+    no child does.  Returns (n_accepted[B], path[R] (-1 beyond each request's path), next_token[B],
+    margin[B]) with margin the smallest top-1/top-2 logit gap over the rows that were consulted.
+    """
+    B = len(draft_len)
+    R = int(np.sum(draft_len))
+    n_acc = np.zeros(B, dtype=np.int32)
+    nxt = np.zeros(B, dtype=np.int32)
+    path = np.full(R, -1, dtype=np.int32)
+    margin = np.full(B, np.inf)
+    r = 0
+    for i in range(B):
+        g = int(draft_len[i])
+        base = r + i
+        cur, n = -1, 0
+        while True:
+            row = target_logits[base + cur + 1]
+            top = _first_argmax(row)
+            if len(row) > 1:
+                part = np.partition(row, -2)[-2:]
+                margin[i] = min(margin[i], float(part[1] - part[0]))
+            step = [t for t in range(g) if int(parents[r + t]) == cur and int(draft_tokens[r + t]) == top]
+            if not step:
+                nxt[i] = top
+                break
+            cur = step[0]
+            path[r + n] = cur
+            n += 1
+        n_acc[i] = n
+        r += g
+    return n_acc, path, nxt, margin
 
 
 def _inverse_cdf(mass: np.ndarray, u: float):

@@ -64,7 +64,7 @@ class SpinError(RuntimeError):
 
 EXPORTS = ["spin_create", "spin_reserve", "spin_required", "spin_destroy", "spin_strerror",
            "spin_last_error", "spin_set_waves", "spin_decompose", "spin_kv_padding",
-           "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_verify_attn_tree", "spin_append_kv", "spin_accept",
+           "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_verify_attn_tree", "spin_append_kv", "spin_accept", "spin_accept_tree",
            "spin_set_plan_reuse", "spin_profile_begin", "spin_profile_every", "spin_profile_end"]
 
 _lib = None
@@ -108,6 +108,8 @@ def load_library():
     lib.spin_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_void_p]
+    lib.spin_accept_tree.argtypes = [C.c_void_p, C.c_int32, _i32p, _i32p, C.c_void_p, C.c_void_p, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.spin_set_plan_reuse.argtypes = [C.c_void_p, C.c_int32]
     lib.spin_profile_begin.argtypes = [C.c_void_p, C.c_int32]
     lib.spin_profile_every.argtypes = [C.c_void_p, C.c_int32]
@@ -250,6 +252,17 @@ class SpinContext:
 
     def set_waves(self, n_waves: int):
         _check(self._lib.spin_set_waves(self._h, n_waves), self._h)
+
+    def accept_tree(self, draft_len, parents, draft_tokens, target_logits, n_accepted, path, next_token, stream=None):
+        """spin_accept_tree.  draft_len, parents: host int32; the rest torch device tensors."""
+        dl = _i32(draft_len)
+        par = _i32(parents)
+        vocab = target_logits.shape[-1]
+        st = self._stream(stream)
+        self._retry(lambda: self._lib.spin_accept_tree(
+            self._h, dl.shape[0], _ptr(dl), _ptr(par), C.c_void_p(draft_tokens.data_ptr()),
+            C.c_void_p(target_logits.data_ptr()), vocab, C.c_void_p(n_accepted.data_ptr()),
+            C.c_void_p(path.data_ptr()), C.c_void_p(next_token.data_ptr()), st))
 
     def set_plan_reuse(self, enable: bool):
         """Whether a call with the same tables as the previous one launches from the tables already staged."""

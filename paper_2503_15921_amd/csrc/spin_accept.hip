@@ -384,6 +384,44 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
     }
 }
 
+// Greedy verification of token trees: one wavefront per request, one lane per draft token (at most
+// 64).  A token "matches" when it equals the arg-max of its parent's target row; the walk starts below
+// the last prefix token and moves to the lowest-numbered matching child until there is none.
+__global__ __launch_bounds__(64) void accept_tree_kernel(AcceptParams P, const int32_t* parent, int32_t* path) {
+    const int req = blockIdx.x, lane = threadIdx.x;
+    const int r0 = P.row_off[req];
+    const int g = P.row_off[req + 1] - r0;
+    const int base = r0 + req;                  // target row of the root; node t owns row base + 1 + t
+    int par = -2;
+    bool match = false;
+    if (lane < g) {
+        par = parent[r0 + lane];
+        match = P.draft_tokens[r0 + lane] == P.row_arg[base + par + 1];
+    }
+    int cur = -1, n = 0;
+    while (true) {
+        const unsigned long long next = __ballot(match && par == cur);
+        if (!next) break;
+        cur = __ffsll((long long)next) - 1;
+        if (lane == 0) path[r0 + n] = cur;
+        ++n;
+    }
+    if (lane >= n && lane < g) path[r0 + lane] = -1;
+    if (lane == 0) {
+        P.n_accepted[req] = n;
+        P.next_token[req] = P.row_arg[base + cur + 1];
+    }
+}
+
+hipError_t launch_accept_tree(const AcceptParams& p, const int32_t* parent, int32_t* path, hipStream_t stream) {
+    if (p.n_req <= 0) return hipSuccess;
+    hipLaunchKernelGGL(row_stats_kernel, dim3(p.n_rows + p.n_req), dim3(kStatThreads), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(accept_tree_kernel, dim3(p.n_req), dim3(64), 0, stream, p, parent, path);
+    return hipGetLastError();
+}
+
 hipError_t launch_accept(const AcceptParams& p, hipStream_t stream, hipEvent_t ev_mid) {
     const int n_stat_rows = p.mode == SPIN_ACCEPT_GREEDY ? p.n_rows + p.n_req : 2 * p.n_rows + p.n_req;
     if (n_stat_rows > 0) {

@@ -674,6 +674,75 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     return SPIN_OK;
 }
 
+int spin_accept_tree(spin_ctx* ctx, int32_t n_req, const int32_t* draft_len_host, const int32_t* parent_host,
+                     const int32_t* draft_tokens_dev, const float* target_logits_dev, int32_t vocab,
+                     int32_t* n_accepted_dev, int32_t* path_dev, int32_t* next_token_dev, void* hip_stream) {
+    if (!ctx) return SPIN_EINVAL;
+    if (n_req < 0 || vocab < 1) return fail(ctx, SPIN_EINVAL, "n_req < 0 or vocab < 1");
+    if (n_req == 0) return SPIN_OK;
+    if (!draft_len_host || !parent_host) return fail(ctx, SPIN_EINVAL, "draft_len or parent is null");
+    ctx->row_off_host.resize(n_req + 1);
+    int64_t rows = 0;
+    for (int32_t i = 0; i < n_req; ++i) {
+        const int32_t g = draft_len_host[i];
+        if (g < 1) return fail(ctx, SPIN_EINVAL, "draft_len < 1");
+        if (g > 64) return fail(ctx, SPIN_ETABLE, "request " + std::to_string(i) + ": a draft tree holds at most 64 tokens");
+        for (int32_t t = 0; t < g; ++t) {
+            const int32_t par = parent_host[rows + t];
+            if (par < -1 || par >= t)
+                return fail(ctx, SPIN_ETABLE, "request " + std::to_string(i) + ", draft token " + std::to_string(t) +
+                                                  ": the parent must be an earlier token of the request or -1");
+        }
+        ctx->row_off_host[i] = (int32_t)rows;
+        rows += g;
+        if (rows > INT32_MAX / 2) return fail(ctx, SPIN_EINVAL, "too many draft rows");
+    }
+    ctx->row_off_host[n_req] = (int32_t)rows;
+    if (!draft_tokens_dev || !target_logits_dev || !n_accepted_dev || !path_dev || !next_token_dev)
+        return fail(ctx, SPIN_EINVAL, "null device pointer");
+    if (n_req > ctx->cap_req || rows > ctx->cap_rows) {
+        ctx->need_req = std::max<int64_t>(n_req, ctx->cap_req);
+        ctx->need_rows = std::max<int64_t>(rows, ctx->cap_rows);
+        ctx->need_pages = ctx->cap_pages;
+        ctx->need_items = ctx->cap_items;
+        ctx->need_slots = ctx->cap_slots;
+        return fail(ctx, SPIN_ENOSPC, "reserved workspace too small for this batch (see spin_required)");
+    }
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // row offsets and parents are read by the kernels from the pinned, device-mapped staging buffer
+    char* h = nullptr;
+    int rc = next_stage(ctx, &h);
+    if (rc) return rc;
+    const size_t off_parent = align16((size_t)(n_req + 1) * 4);
+    memcpy(h, ctx->row_off_host.data(), (size_t)(n_req + 1) * 4);
+    memcpy(h + off_parent, parent_host, (size_t)rows * 4);
+    void* mapped = nullptr;
+    e = hipHostGetDevicePointer(&mapped, h, 0);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
+    const int slot = ctx->stage;
+    spin::AcceptParams p = {};
+    p.row_off = (const int32_t*)mapped;
+    p.draft_tokens = draft_tokens_dev;
+    p.target_logits = target_logits_dev;
+    p.row_max = ctx->d_row_max;
+    p.row_sum = ctx->d_row_sum;
+    p.row_arg = ctx->d_row_arg;
+    p.n_accepted = n_accepted_dev;
+    p.next_token = next_token_dev;
+    p.n_req = n_req;
+    p.n_rows = (int32_t)rows;
+    p.vocab = vocab;
+    p.mode = SPIN_ACCEPT_GREEDY;
+    e = spin::launch_accept_tree(p, (const int32_t*)((char*)mapped + off_parent), path_dev, stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "tree acceptance launch");
+    e = hipEventRecord(ctx->ev[slot], stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    ctx->ev_pending[slot] = true;
+    return SPIN_OK;
+}
+
 int spin_set_plan_reuse(spin_ctx* ctx, int32_t enable) {
     if (!ctx) return SPIN_EINVAL;
     ctx->reuse_plans = enable != 0;

@@ -87,5 +87,10 @@ constexpr int kMaxVocab = 1 << 20;
 
 hipError_t launch_accept(const AcceptParams& p, hipStream_t stream, hipEvent_t ev_mid);
 
+// Greedy walk down token trees; p is the (greedy-mode) parameter block of the row statistics, parent
+// [R] (device) the index of every draft token's parent within its request (-1: the last prefix token),
+// path [R] (device) receives the accepted nodes.
+hipError_t launch_accept_tree(const AcceptParams& p, const int32_t* parent, int32_t* path, hipStream_t stream);
+
 }  // namespace spin
 #endif

@@ -713,6 +713,68 @@ def test_accept_token_outside_vocabulary_is_rejected(ctx):
     assert ((0 <= t_g) & (t_g < 1000)).all()
 
 
+# ------------------------------------------------------------------------------ greedy tree acceptance
+def hip_accept_tree(ctx, draft_len, parents, tokens, logits):
+    B, R = len(draft_len), int(np.sum(draft_len))
+    n_acc = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    nxt = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    path = torch.full((R,), -7, dtype=torch.int32, device="cuda")
+    ctx.accept_tree(draft_len, parents, tokens, logits, n_acc, path, nxt)
+    torch.cuda.synchronize()
+    return n_acc.cpu().numpy(), path.cpu().numpy(), nxt.cpu().numpy()
+
+
+@pytest.mark.parametrize("vocab", [3, 8, 1000, 32000])
+@pytest.mark.parametrize("shape", ["random", "wide", "star", "chain"])
+def test_accept_tree_greedy(ctx, vocab, shape):
+    rng = np.random.default_rng(vocab + len(shape))
+    draft_len = np.array([64, 1, 7, 30, 2, 12], dtype=np.int32)
+    parents, _ = si.random_trees(draft_len, rng, shape)
+    R, B = int(draft_len.sum()), len(draft_len)
+    g = torch.Generator(device="cuda").manual_seed(vocab)
+    logits = torch.randn((R + B, vocab), generator=g, device="cuda") * 2.0
+    # tokens: a mix of the parent's arg-max (so that walks go deep) and random ids
+    top = logits.argmax(dim=-1).cpu().numpy()
+    tokens = rng.integers(0, vocab, R).astype(np.int32)
+    r = 0
+    for i, gl in enumerate(draft_len):
+        for t in range(gl):
+            if rng.random() < 0.6:
+                tokens[r + t] = top[r + i + parents[r + t] + 1]
+        r += gl
+    tok_dev = torch.from_numpy(tokens).cuda()
+    n_o, path_o, nxt_o, margin = orc.accept_tree_greedy(draft_len, parents, tokens, logits.cpu().numpy())
+    assert margin.min() > 0
+    n_g, path_g, nxt_g = hip_accept_tree(ctx, draft_len, parents, tok_dev, logits)
+    np.testing.assert_array_equal(n_g, n_o)
+    np.testing.assert_array_equal(path_g, path_o)
+    np.testing.assert_array_equal(nxt_g, nxt_o)
+    if vocab >= 8 and shape != "star":              # (a star is one level deep)
+        assert n_o.max() >= 2
+    if shape == "chain":        # the layout and the result of the linear greedy acceptance
+        ab_n = torch.full((B,), -7, dtype=torch.int32, device="cuda"); ab_t = torch.full_like(ab_n, -7)
+        import paper_2503_15921_amd as spin
+        ctx.accept(spin.ACCEPT_GREEDY, draft_len, tok_dev, logits, None, None, None, ab_n, ab_t)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(ab_n.cpu().numpy(), n_o)
+        np.testing.assert_array_equal(ab_t.cpu().numpy(), nxt_o)
+
+
+def test_accept_tree_errors(ctx):
+    import paper_2503_15921_amd as spin
+    draft_len = np.array([3, 2], dtype=np.int32)
+    logits = torch.randn((7, 16), device="cuda")
+    tokens = torch.zeros(5, dtype=torch.int32, device="cuda")
+    for bad in ([-1, 0, 2, -1, 0], [-1, 0, 1, 0, 0], [-2, 0, 1, -1, 0]):      # own index, first token with a parent, below -1
+        with pytest.raises(spin.SpinError) as ei:
+            hip_accept_tree(ctx, draft_len, np.array(bad, dtype=np.int32), tokens, logits)
+        assert ei.value.code == spin.ETABLE
+    with pytest.raises(spin.SpinError) as ei:
+        hip_accept_tree(ctx, np.array([65], dtype=np.int32), np.full(65, -1, dtype=np.int32),
+                        torch.zeros(65, dtype=torch.int32, device="cuda"), torch.randn((66, 16), device="cuda"))
+    assert ei.value.code == spin.ETABLE
+
+
 # ------------------------------------------------------------------------------ error paths
 def test_errors_before_launch(ctx):
     import paper_2503_15921_amd as spin

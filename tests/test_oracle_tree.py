@@ -100,3 +100,74 @@ def test_decomposed_tree_attention_matches_whole(seed):
     parts = orc.verify_attention_decomposed(table.prefix_len, table.draft_len, table.q_offset, table.pt_offset,
                                             table.page_table, table.page_size, q, kp, vp, 2, 2, 0.35, subs, tree_mask=masks)
     np.testing.assert_allclose(parts, whole, rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------------------ greedy tree acceptance
+def greedy_paths_brute_force(g, parents, tokens, rows):
+    """All root-to-node paths along which every token equals the arg-max of its parent's row; the
+    accepted one is maximal and, among those, the first in child order at every fork."""
+    tops = [int(np.flatnonzero(r == r.max())[0]) for r in rows]           # rows[0]: root, rows[1+t]: node t
+    matched = [t for t in range(g) if int(tokens[t]) == tops[int(parents[t]) + 1]]
+    paths = [[]]
+    for t in matched:                                                     # parents come first, so one sweep builds all
+        for p in list(paths):
+            if (p[-1] if p else -1) == int(parents[t]):
+                paths.append(p + [t])
+    maximal = [p for p in paths if not any(q[:len(p)] == p and len(q) > len(p) for q in paths)]
+    best = min(maximal, key=lambda p: p)      # lists compare element by element: lowest child first, then onwards
+    return best, tops[(best[-1] if best else -1) + 1]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_tree_greedy_against_path_enumeration(seed):
+    rng = np.random.default_rng(seed + 100)
+    draft = np.array([7, 1, 12, 5]); vocab = 4                            # tiny vocabulary: many matches, many forks
+    parents, _ = si.random_trees(draft, rng, "random" if seed % 2 else "wide")
+    R, B = int(draft.sum()), len(draft)
+    tokens = rng.integers(0, vocab, R)
+    logits = rng.normal(0, 1, (R + B, vocab)).astype(np.float32)
+    n_acc, path, nxt, margin = orc.accept_tree_greedy(draft, parents, tokens, logits)
+    r = 0
+    for i, g in enumerate(draft):
+        want_path, want_next = greedy_paths_brute_force(int(g), parents[r:r + g], tokens[r:r + g], logits[r + i:r + i + g + 1])
+        assert n_acc[i] == len(want_path)
+        assert path[r:r + n_acc[i]].tolist() == want_path and (path[r + n_acc[i]:r + g] == -1).all()
+        assert nxt[i] == want_next
+        r += g
+    assert n_acc.max() >= 1
+
+
+def test_tree_greedy_on_a_chain_is_linear_greedy():
+    rng = np.random.default_rng(7)
+    draft = np.array([4, 9, 1, 6]); vocab = 50
+    parents, _ = si.random_trees(draft, None, "chain")
+    R, B = int(draft.sum()), len(draft)
+    logits = rng.normal(0, 2, (R + B, vocab)).astype(np.float32)
+    # plant accepted prefixes of lengths 2, 9 (all), 0, 3
+    tokens = rng.integers(0, vocab, R)
+    r = 0
+    for i, (g, keep) in enumerate(zip(draft, [2, 9, 0, 3])):
+        for t in range(g):
+            top = int(np.argmax(logits[r + i + t]))
+            tokens[r + t] = top if t < keep else (top + 1) % vocab
+        r += g
+    n_t, path, nxt_t, _ = orc.accept_tree_greedy(draft, parents, tokens, logits)
+    n_l, nxt_l, _ = orc.accept_greedy(draft, tokens, logits)
+    assert n_t.tolist() == n_l.tolist() == [2, 9, 0, 3] and nxt_t.tolist() == nxt_l.tolist()
+    r = 0
+    for g, n in zip(draft, n_t):
+        assert path[r:r + n].tolist() == list(range(n))
+        r += g
+
+
+def test_tree_greedy_takes_the_lowest_numbered_of_equal_children():
+    # two children of the root carry the arg-max token; only the first one's subtree may be walked
+    draft = np.array([5]); parents = np.array([-1, -1, 0, 1, 1])
+    logits = np.zeros((6, 3), dtype=np.float32)
+    logits[0, 2] = 1.0          # root -> token 2
+    logits[1, 0] = 1.0          # after node 0 -> token 0
+    logits[2, 1] = 1.0          # after node 1 -> token 1 (never consulted)
+    logits[3, 1] = 1.0          # after node 2 -> token 1
+    tokens = np.array([2, 2, 0, 1, 1])
+    n_acc, path, nxt, _ = orc.accept_tree_greedy(draft, parents, tokens, logits)
+    assert n_acc[0] == 2 and path.tolist() == [0, 2, -1, -1, -1] and nxt[0] == 1
