@@ -35,7 +35,10 @@ values, one dominant key, empty prefix), invariances (key shift, joint permutati
 prefix pairs, page relocation, NaN in unowned slots, grouped-query = repeated heads),
 decomposition invariance under Eq. (13), planted greedy cases, p == q, u == 0, exact
 enumeration of the accept/resample distribution on a tiny vocabulary, and the expected
-emitted length for i.i.d. rows.  No function here is "parity unpinned".
+emitted length for i.i.d. rows; the KV append against a cache filled position by position and
+against dense brute-force attention; tree masks against plain attention over every node's
+root-to-node path; the greedy tree acceptance against an enumeration of all matched paths and
+against the linear acceptance on chains.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
