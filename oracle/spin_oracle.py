@@ -14,7 +14,8 @@ What it follows
                                  all tokens of the ORIGINAL request in the batch.
   * append_kv                -- the KV cache of Sec. II-A1: the candidate tokens' K/V enter the
                                  cache at the positions after the prefix (plain scatter).
-  * accept_tree_greedy       -- greedy verification of token trees (related work of Sec. I).
+  * accept_tree_greedy / accept_tree_rejection -- verification of token trees (related work of Sec. I):
+                                 greedy matching, and multi-round rejection sampling over the children.
   * decompose_*              -- Sec. V-A: request decomposition and the choice of the
                                  KV-tensor length L for a fixed width B.
   * accept_greedy / accept_rejection -- the verification phase of Sec. II-A2 ("tokens
@@ -390,3 +391,66 @@ def accept_rejection(draft_len, draft_tokens, target_logits, draft_logits, u_acc
         nxt[i] = k
         r += g
     return n_acc, nxt, margin
+
+
+def accept_tree_rejection(draft_len, parents, draft_tokens, target_logits, draft_logits, u_accept, u_sample):
+    """Rejection-sampling verification of token trees: at every node the children are tried one after
+    the other, and every rejected child takes its draft distribution out of what is left of the
+    target distribution (the multi-round speculative sampling of the token-tree systems named in
+    Sec. I; for a chain it is accept_rejection).
+
+    Rows as in accept_tree_greedy; token t was drawn from q_t = softmax(draft row t).  At the node
+    reached so far let R_0 = p = softmax(its target row) and s_0 = 1.  Child c (in index order,
+    token d_c) is accepted iff  u_c * q_c(d_c) * s_k < R_k(d_c)  (u < min(1, r/q) for the residual
+    r = R_k / s_k, without a division); the walk then moves to c with a fresh R_0.  A rejected child
+    gives  R_{k+1}(x) = max(0, R_k(x) - s_k q_c(x)),  s_{k+1} = sum_x R_{k+1}(x); if that sum is zero
+    (residual and q_c equal up to rounding) the child is ignored and R_k, s_k stay.  When no child is
+    accepted (or there is none) the next token is drawn from R_k by inverse CDF with u'_i.
+    Returns (n_accepted[B], path[R], next_token[B], margin[B]).
+    """
+    B = len(draft_len)
+    R_rows = int(np.sum(draft_len))
+    n_acc = np.zeros(B, dtype=np.int32)
+    nxt = np.zeros(B, dtype=np.int32)
+    path = np.full(R_rows, -1, dtype=np.int32)
+    margin = np.full(B, np.inf)
+    r = 0
+    for i in range(B):
+        g = int(draft_len[i])
+        base = r + i
+        V = target_logits.shape[1]
+        cur, n = -1, 0
+        while True:
+            Rk = _softmax64(target_logits[base + cur + 1])
+            sk = 1.0
+            moved = False
+            for c in range(g):
+                if int(parents[r + c]) != cur:
+                    continue
+                q = _softmax64(draft_logits[r + c])
+                d = int(draft_tokens[r + c])
+                if 0 <= d < V:
+                    lhs = float(u_accept[r + c]) * q[d] * sk
+                    rhs = Rk[d]
+                    if rhs > 0:
+                        margin[i] = min(margin[i], abs(lhs - rhs) / rhs)
+                    if lhs < rhs:
+                        cur = c
+                        path[r + n] = c
+                        n += 1
+                        moved = True
+                        break
+                nxt_R = np.maximum(Rk - sk * q, 0.0)
+                tot = nxt_R.sum()
+                if tot > 0:
+                    Rk, sk = nxt_R, tot
+            if moved:
+                continue
+            k, near = _inverse_cdf(Rk, float(u_sample[i]))
+            margin[i] = min(margin[i], near)
+            nxt[i] = k
+            break
+        n_acc[i] = n
+        r += g
+    return n_acc, path, nxt, margin
+

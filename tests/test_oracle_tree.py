@@ -171,3 +171,119 @@ def test_tree_greedy_takes_the_lowest_numbered_of_equal_children():
     tokens = np.array([2, 2, 0, 1, 1])
     n_acc, path, nxt, _ = orc.accept_tree_greedy(draft, parents, tokens, logits)
     assert n_acc[0] == 2 and path.tolist() == [0, 2, -1, -1, -1] and nxt[0] == 1
+
+
+# ------------------------------------------------------------------------------ rejection sampling over trees
+@pytest.mark.parametrize("seed", range(8))
+def test_tree_rejection_on_a_chain_is_linear_rejection(seed):
+    rng = np.random.default_rng(seed + 200)
+    draft = np.array([4, 7, 1, 5]); V = int(rng.choice([3, 30, 500]))
+    parents, _ = si.random_trees(draft, None, "chain")
+    R, B = int(draft.sum()), len(draft)
+    tl = rng.normal(0, 2, (R + B, V)).astype(np.float32)
+    own = np.delete(tl, np.cumsum(draft) + np.arange(B), axis=0)          # the target row each draft token is checked against
+    dl = (0.9 * own + 0.44 * rng.normal(0, 2, (R, V))).astype(np.float32)
+    tok = np.array([rng.choice(V, p=orc._softmax64(dl[k])) for k in range(R)])
+    ua, us = rng.random(R), rng.random(B)
+    n_t, path, nxt_t, m_t = orc.accept_tree_rejection(draft, parents, tok, tl, dl, ua, us)
+    n_l, nxt_l, m_l = orc.accept_rejection(draft, tok, tl, dl, ua, us)
+    assert n_t.tolist() == n_l.tolist() and nxt_t.tolist() == nxt_l.tolist()
+    np.testing.assert_allclose(m_t, m_l, rtol=1e-12)
+    r = 0
+    for g, n in zip(draft, n_t):
+        assert path[r:r + n].tolist() == list(range(n)) and (path[r + n:r + g] == -1).all()
+        r += g
+
+
+def first_emitted_distribution(p_logits, q_logits, k):
+    """Distribution of the first emitted token when the root has k children drawn i.i.d. from q, by
+    treating the oracle as a black box: acceptance thresholds by bisection on each child's uniform,
+    the final draw by a fine grid of u'."""
+    V = len(p_logits)
+    q = orc._softmax64(q_logits)
+    draft = np.array([k]); parents = np.full(k, -1)
+    tl = np.stack([p_logits] + [p_logits] * k).astype(np.float32)         # rows after the children are never emitted first
+    dl = np.stack([q_logits] * k).astype(np.float32)
+    out = np.zeros(V)
+    grid = (np.arange(4000) + 0.5) / 4000
+    for combo in np.ndindex(*([V] * k)):
+        w = float(np.prod([q[x] for x in combo]))
+        tok = np.array(combo)
+        reach = 1.0                                                        # probability that children 0..c-1 were all rejected
+        for c in range(k):
+            ua = np.full(k, 0.999999)                                      # earlier children: rejected (p/q < 1 is needed, else unreachable)
+            lo, hi = 0.0, 1.0
+            for _ in range(40):                                            # largest u_c that still accepts child c
+                mid = 0.5 * (lo + hi)
+                ua[c] = mid
+                n, path, _, _ = orc.accept_tree_rejection(draft, parents, tok, tl, dl, ua, np.array([0.5]))
+                if n[0] >= 1 and path[0] == c:
+                    lo = mid
+                else:
+                    hi = mid
+            # (if an earlier child is accepted even at u = 0.999999 the later ones are unreachable: reach is then ~0)
+            ua_prev = np.full(k, 0.999999)
+            n, path, _, _ = orc.accept_tree_rejection(draft, parents, tok, tl, dl, ua_prev, np.array([0.5]))
+            first_acc = path[0] if n[0] >= 1 else k
+            if first_acc < c:
+                reach = 0.0
+            out[tok[c]] += w * reach * lo
+            reach *= 1.0 - lo
+        if reach > 0:
+            ua = np.full(k, 0.999999)
+            counts = np.zeros(V)
+            for u in grid:
+                _, _, nx, _ = orc.accept_tree_rejection(draft, parents, tok, tl, dl, ua, np.array([u]))
+                counts[nx[0]] += 1
+            out += w * reach * counts / len(grid)
+    return out
+
+
+@pytest.mark.parametrize("k", [1, 2])
+def test_tree_rejection_emits_the_target_distribution(k):
+    # the point of the rule: whatever the draft distribution and however many children are tried,
+    # the first emitted token is distributed exactly as the target says
+    rng = np.random.default_rng(300 + k)
+    V = 3
+    p_logits = rng.normal(0, 1.5, V)
+    q_logits = rng.normal(0, 1.5, V)
+    got = first_emitted_distribution(p_logits, q_logits, k)
+    np.testing.assert_allclose(got, orc._softmax64(p_logits.astype(np.float32)), atol=2e-3)
+    assert abs(got.sum() - 1.0) < 1e-3
+
+
+def test_tree_rejection_child_outside_vocabulary_and_vanishing_residual():
+    # target == draft: a child whose token id is invalid is rejected, the residual max(0, p - q) vanishes,
+    # the child is ignored and the next token comes from p itself; a valid sibling after it is then accepted
+    V = 6
+    rng = np.random.default_rng(9)
+    row = rng.normal(0, 1, V).astype(np.float32)
+    draft = np.array([2]); parents = np.array([-1, -1])
+    tl = np.stack([row, row, row]); dl = np.stack([row, row])
+    tok = np.array([V + 3, 4])
+    n, path, nxt, _ = orc.accept_tree_rejection(draft, parents, tok, tl, dl, np.array([0.0, 0.5]), np.array([0.3]))
+    assert n[0] == 1 and path.tolist() == [1, -1]
+    tok = np.array([V + 3, -1])
+    n, path, nxt, _ = orc.accept_tree_rejection(draft, parents, tok, tl, dl, np.array([0.0, 0.5]), np.array([0.3]))
+    p = orc._softmax64(row)
+    assert n[0] == 0 and nxt[0] == int(np.searchsorted(np.cumsum(p), 0.3 * p.sum(), side="right"))
+
+
+def test_tree_rejection_walks_into_the_accepted_subtree_only():
+    # root children 0 and 1; 0 is rejected (u = 1 - eps against p/q < 1), 1 accepted (u = 0); 1's child 3 accepted, 0's child 2 never looked at
+    V = 5
+    rng = np.random.default_rng(10)
+    draft = np.array([4]); parents = np.array([-1, -1, 0, 1])
+    tl = rng.normal(0, 1, (5, V)).astype(np.float32)
+    dl = rng.normal(0, 1, (4, V)).astype(np.float32)
+    p0, q0 = orc._softmax64(tl[0]), orc._softmax64(dl[0])
+    tok = np.array([int(np.argmin(p0 / q0)), 0, 1, 2])
+    assert p0[tok[0]] / q0[tok[0]] < 1
+    res = np.maximum(p0 - q0, 0)
+    tok[1] = int(np.argmax(res))                                           # has residual mass, so u = 0 accepts it
+    ua = np.array([1 - 1e-12, 0.0, 0.0, 0.0])
+    n, path, nxt, _ = orc.accept_tree_rejection(draft, parents, tok, tl, dl, ua, np.array([0.5]))
+    assert n[0] == 2 and path.tolist() == [1, 3, -1, -1]
+    # the bonus draw comes from node 3's row
+    p_last = orc._softmax64(tl[4])
+    assert nxt[0] == int(np.searchsorted(np.cumsum(p_last), 0.5 * np.cumsum(p_last)[-1], side="right"))
