@@ -173,6 +173,140 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(AcceptParams P)
     }
 }
 
+// The inverse CDF shared by the next-token kernels: the smallest id k with sum_{x<=k} mass(x) > u * total.
+// mass4(x0, m) gives the masses of the four ids starting at x0 (zero beyond the vocabulary).  The
+// vocabulary is walked in steps of 4 * kFinishThreads ids; in a step thread t owns the four ids
+// step*4T + 4t .. +3 (16-byte loads, consecutive lanes read consecutive memory), so wavefront w owns a
+// contiguous run of 256 ids.  Pass 1 leaves the mass of every (step, wavefront) run in LDS; a scan over
+// those finds the run that holds u * total; its wavefront recomputes the run and scans inside it.
+// Called by all threads of the workgroup; returns false, with nothing written, when the total is not positive.
+struct DrawShared {
+    double* run;      // [kMaxRuns]
+    int* last;        // [kFinishThreads / 64]
+    double* total;
+    double* before;
+    int* cross;
+};
+
+template <class Mass4>
+__device__ __forceinline__ bool draw_inverse_cdf(Mass4 mass4, int V, double u, int32_t* out, const DrawShared& sh) {
+    constexpr int kWaves = kFinishThreads / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_steps = (V + 4 * kFinishThreads - 1) / (4 * kFinishThreads);
+    const int n_runs = n_steps * kWaves;
+    double* const s_run = sh.run;
+    int* const s_last = sh.last;
+    double& s_total = *sh.total;
+    double& s_before = *sh.before;
+    int& s_cross = *sh.cross;
+    int last = -1;
+    for (int st = 0; st < n_steps; ++st) {
+        const int x0 = st * 4 * kFinishThreads + 4 * tid;
+        double m[4];
+        mass4(x0, m);
+        double run = (m[0] + m[1]) + (m[2] + m[3]);
+        for (int j = 0; j < 4; ++j)
+            if (m[j] > 0.0) last = x0 + j;
+        for (int off = 32; off > 0; off >>= 1) run += __shfl_xor(run, off);
+        if (lane == 0) s_run[st * kWaves + wave] = run;
+    }
+    for (int off = 32; off > 0; off >>= 1) last = max(last, __shfl_xor(last, off));
+    if (lane == 0) s_last[wave] = last;
+    __syncthreads();
+    // wavefront 0 scans the run masses in id order: lane L takes a contiguous slice of them
+    if (wave == 0) {
+        const int per = (n_runs + 63) / 64;
+        const int lo = min(n_runs, lane * per), hi = min(n_runs, lo + per);
+        double mine = 0.0;
+        for (int k = lo; k < hi; ++k) mine += s_run[k];
+        double incl = mine;
+        for (int off = 1; off < 64; off <<= 1) {
+            const double up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        const double total = __shfl(incl, 63);
+        const double thr = u * total;
+        double excl = __shfl_up(incl, 1);
+        if (lane == 0) excl = 0.0;
+        if (lane == 0) {
+            s_total = total;
+            s_cross = -1;
+        }
+        // exactly the lanes where the running sum first passes the threshold look inside their slice
+        if (incl > thr && !(excl > thr)) {
+            double run = excl;
+            int k = lo;
+            for (; k < hi; ++k) {
+                if (run + s_run[k] > thr) break;
+                run += s_run[k];
+            }
+            if (k == hi) k = hi - 1;             // summation orders may differ in the last bit
+            // several lanes can only get here when the sums are not monotone by rounding: lowest wins
+            const unsigned long long who = __ballot(1);
+            if (lane == __ffsll((long long)who) - 1) {
+                s_cross = k;
+                s_before = run;
+            }
+        }
+    }
+    __syncthreads();
+    const double total = s_total;
+    if (!(total > 0.0)) {                    // nothing to draw from: the caller decides what else to use
+        __syncthreads();
+        return false;
+    }
+    const int cross = s_cross;
+    if (cross < 0) {                         // u'*Z at or beyond the total: last id with mass
+        if (tid == 0) {
+            int k = -1;
+            for (int w = 0; w < kWaves; ++w) k = max(k, s_last[w]);
+            *out = k >= 0 ? k : V - 1;
+        }
+        return true;
+    }
+    if (wave == cross % kWaves) {
+        const int x0 = (cross / kWaves) * 4 * kFinishThreads + 4 * tid;
+        const double thr = u * total;
+        double m[4];
+        mass4(x0, m);
+        const double mine = (m[0] + m[1]) + (m[2] + m[3]);
+        double incl = mine;
+        for (int off = 1; off < 64; off <<= 1) {
+            const double up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        incl += s_before;
+        double excl = __shfl_up(incl, 1);
+        if (lane == 0) excl = s_before;
+        const bool hit = incl > thr && !(excl > thr);
+        int k = 0x7fffffff;
+        if (hit) {
+            double run = excl;
+            k = -1;
+            for (int j = 0; j < 4; ++j) {
+                run += m[j];
+                if (run > thr) { k = x0 + j; break; }
+            }
+            if (k < 0)
+                for (int j = 3; j >= 0 && k < 0; --j)
+                    if (m[j] > 0.0) k = x0 + j;
+            if (k < 0) k = min(x0, V - 1);
+        }
+        const unsigned long long who = __ballot(hit);
+        if (who) {
+            if (lane == __ffsll((long long)who) - 1) *out = k;
+        } else {
+            // the recomputed run fell short of its first sum by rounding: its last id with mass
+            int lastpos = -1;
+            for (int j = 0; j < 4; ++j)
+                if (m[j] > 0.0) lastpos = x0 + j;
+            for (int off = 32; off > 0; off >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, off));
+            if (lane == 0) *out = lastpos >= 0 ? lastpos : min(x0, V - 1);
+        }
+    }
+    return true;
+}
+
 __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptParams P) {
     constexpr int kWaves = kFinishThreads / 64;
     __shared__ int s_n;
@@ -181,6 +315,7 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
     __shared__ double s_total, s_before;
     __shared__ int s_cross;
     __shared__ double s_tab[64];                 // 2^(j/64) for exp_table64
+    const DrawShared sh = {s_run, s_last, &s_total, &s_before, &s_cross};
     const int req = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r0 = P.row_off[req];
@@ -226,12 +361,7 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
     __syncthreads();
     if (P.mode == SPIN_ACCEPT_GREEDY) return;
 
-    // ---- next token: inverse CDF over the residual max(0, p - q), or over the bonus row's p.
-    // The vocabulary is walked in steps of 4 * kFinishThreads ids; in a step thread t owns the four
-    // ids step*4T + 4t .. +3 (16-byte loads, consecutive lanes read consecutive memory), so wavefront
-    // w owns a contiguous run of 256 ids.  Pass 1 leaves the mass of every (step, wavefront) run in
-    // LDS; a scan over those finds the run that holds u' * Z; its wavefront recomputes the run and
-    // scans inside it.
+    // ---- next token: inverse CDF over the residual max(0, p - q), or over the bonus row's p
     const int n = s_n;
     const float* tl = P.target_logits + (int64_t)(base + n) * V;
     const double tmax = (double)P.row_max[base + n], tinv = 1.0 / P.row_sum[base + n];
@@ -240,8 +370,6 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
     const double dmax = residual ? (double)P.row_max[n_target + r0 + n] : 0.0;
     const double dinv = residual ? 1.0 / P.row_sum[n_target + r0 + n] : 1.0;
     const bool vec = (V % 4 == 0) && (((reinterpret_cast<uintptr_t>(tl) | reinterpret_cast<uintptr_t>(dl)) & 15) == 0);
-    const int n_steps = (V + 4 * kFinishThreads - 1) / (4 * kFinishThreads);
-    const int n_runs = n_steps * kWaves;
 
     bool use_residual = residual;
     for (int attempt = 0; attempt < 2; ++attempt) {
@@ -274,113 +402,8 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
                 m[j] = v;
             }
         };
-        int last = -1;
-        for (int st = 0; st < n_steps; ++st) {
-            const int x0 = st * 4 * kFinishThreads + 4 * tid;
-            double m[4];
-            mass4(x0, m);
-            double run = (m[0] + m[1]) + (m[2] + m[3]);
-            for (int j = 0; j < 4; ++j)
-                if (m[j] > 0.0) last = x0 + j;
-            for (int off = 32; off > 0; off >>= 1) run += __shfl_xor(run, off);
-            if (lane == 0) s_run[st * kWaves + wave] = run;
-        }
-        for (int off = 32; off > 0; off >>= 1) last = max(last, __shfl_xor(last, off));
-        if (lane == 0) s_last[wave] = last;
-        __syncthreads();
-        // wavefront 0 scans the run masses in id order: lane L takes a contiguous slice of them
-        if (wave == 0) {
-            const int per = (n_runs + 63) / 64;
-            const int lo = min(n_runs, lane * per), hi = min(n_runs, lo + per);
-            double mine = 0.0;
-            for (int k = lo; k < hi; ++k) mine += s_run[k];
-            double incl = mine;
-            for (int off = 1; off < 64; off <<= 1) {
-                const double up = __shfl_up(incl, off);
-                if (lane >= off) incl += up;
-            }
-            const double total = __shfl(incl, 63);
-            const double thr = P.u_sample[req] * total;
-            double excl = __shfl_up(incl, 1);
-            if (lane == 0) excl = 0.0;
-            if (lane == 0) {
-                s_total = total;
-                s_cross = -1;
-            }
-            // exactly the lanes where the running sum first passes the threshold look inside their slice
-            if (incl > thr && !(excl > thr)) {
-                double run = excl;
-                int k = lo;
-                for (; k < hi; ++k) {
-                    if (run + s_run[k] > thr) break;
-                    run += s_run[k];
-                }
-                if (k == hi) k = hi - 1;             // summation orders may differ in the last bit
-                // several lanes can only get here when the sums are not monotone by rounding: lowest wins
-                const unsigned long long who = __ballot(1);
-                if (lane == __ffsll((long long)who) - 1) {
-                    s_cross = k;
-                    s_before = run;
-                }
-            }
-        }
-        __syncthreads();
-        const double total = s_total;
-        if (use_residual && !(total > 0.0)) {   // p == q up to rounding: draw from p instead
-            use_residual = false;
-            __syncthreads();
-            continue;
-        }
-        const int cross = s_cross;
-        if (cross < 0) {                         // u'*Z at or beyond the total: last id with mass
-            if (tid == 0) {
-                int k = -1;
-                for (int w = 0; w < kWaves; ++w) k = max(k, s_last[w]);
-                P.next_token[req] = k >= 0 ? k : V - 1;
-            }
-            break;
-        }
-        if (wave == cross % kWaves) {
-            const int x0 = (cross / kWaves) * 4 * kFinishThreads + 4 * tid;
-            const double thr = P.u_sample[req] * total;
-            double m[4];
-            mass4(x0, m);
-            const double mine = (m[0] + m[1]) + (m[2] + m[3]);
-            double incl = mine;
-            for (int off = 1; off < 64; off <<= 1) {
-                const double up = __shfl_up(incl, off);
-                if (lane >= off) incl += up;
-            }
-            incl += s_before;
-            double excl = __shfl_up(incl, 1);
-            if (lane == 0) excl = s_before;
-            const bool hit = incl > thr && !(excl > thr);
-            int k = 0x7fffffff;
-            if (hit) {
-                double run = excl;
-                k = -1;
-                for (int j = 0; j < 4; ++j) {
-                    run += m[j];
-                    if (run > thr) { k = x0 + j; break; }
-                }
-                if (k < 0)
-                    for (int j = 3; j >= 0 && k < 0; --j)
-                        if (m[j] > 0.0) k = x0 + j;
-                if (k < 0) k = min(x0, V - 1);
-            }
-            const unsigned long long who = __ballot(hit);
-            if (who) {
-                if (lane == __ffsll((long long)who) - 1) P.next_token[req] = k;
-            } else {
-                // the recomputed run fell short of its first sum by rounding: its last id with mass
-                int lastpos = -1;
-                for (int j = 0; j < 4; ++j)
-                    if (m[j] > 0.0) lastpos = x0 + j;
-                for (int off = 32; off > 0; off >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, off));
-                if (lane == 0) P.next_token[req] = lastpos >= 0 ? lastpos : min(x0, V - 1);
-            }
-        }
-        break;
+        if (draw_inverse_cdf(mass4, V, P.u_sample[req], &P.next_token[req], sh)) break;
+        use_residual = false;                    // p == q up to rounding: draw from p instead
     }
 }
 
