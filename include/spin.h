@@ -251,20 +251,34 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
                 const double* u_sample_dev, int32_t* n_accepted_dev, int32_t* next_token_dev,
                 void* hip_stream);
 
-/* Greedy verification of token trees, the companion of spin_verify_attn_tree.  Draft token t of request
- * i hangs below token parent_host[q_offset[i] + t] of the same request (an earlier token, or -1 = the
- * last prefix token); draft_len <= 64.  Target row q_offset[i] + i is the model's output after the
- * prefix, row q_offset[i] + i + 1 + t its output after token t (for a chain this is the layout of
- * spin_accept).  The walk starts below the last prefix token and moves to the lowest-numbered child
- * whose token equals the arg-max (lowest id on ties) of the current node's row, until no child does:
- *   n_accepted_dev[i]            number of tokens on that path
+/* Verification of token trees, the companion of spin_verify_attn_tree.  Draft token t of request i hangs
+ * below token parent_host[q_offset[i] + t] of the same request (an earlier token, or -1 = the last prefix
+ * token); draft_len <= 64.  Target row q_offset[i] + i is the model's output after the prefix, row
+ * q_offset[i] + i + 1 + t its output after token t (for a chain this is the layout of spin_accept, and the
+ * results are those of spin_accept); draft row q_offset[i] + t is the distribution token t was drawn from.
+ * The walk starts below the last prefix token.
+ *   SPIN_ACCEPT_GREEDY     move to the lowest-numbered child whose token equals the arg-max (lowest id on
+ *                          ties) of the current node's target row, until no child does; next token = the
+ *                          arg-max of the row of the last token reached.  draft_logits_dev, u_accept_dev and
+ *                          u_sample_dev are not read and the vocabulary is not limited.
+ *   SPIN_ACCEPT_REJECTION  multi-round speculative sampling (float64): with R_0 = p = softmax(target row of
+ *                          the current node) and s_0 = 1, the children are tried in index order; child c with
+ *                          token d and q_c = softmax(its draft row) is accepted iff
+ *                          u_accept[c] * q_c(d) * s_k < R_k(d), and the walk moves on from c.  A rejected
+ *                          child gives R_{k+1} = max(0, R_k - s_k q_c), s_{k+1} = sum R_{k+1}; if that sum is
+ *                          zero the child is ignored.  A token id outside [0, vocab) is never accepted.  When
+ *                          no child is accepted the next token is the smallest k with
+ *                          sum_{x<=k} R_k(x) > u_sample[i] * s_k.  vocab <= 1048576.
+ * Outputs:
+ *   n_accepted_dev[i]            number of tokens on the accepted path
  *   path_dev[q_offset[i] + k]    its k-th token, k < n_accepted; -1 in the request's other entries
- *   next_token_dev[i]            the arg-max of the row of the last token reached (the root's if none)
- * The vocabulary is not limited here.  Acceptance by rejection sampling over trees (several candidate
- * children per node) is not provided.  Errors as for spin_accept, plus SPIN_ETABLE for a bad parent. */
-int spin_accept_tree(spin_ctx* ctx, int32_t n_req, const int32_t* draft_len_host, const int32_t* parent_host,
-                     const int32_t* draft_tokens_dev, const float* target_logits_dev, int32_t vocab,
-                     int32_t* n_accepted_dev, int32_t* path_dev, int32_t* next_token_dev, void* hip_stream);
+ *   next_token_dev[i]            the token that follows the path
+ * Errors as for spin_accept, plus SPIN_ETABLE for a bad parent or more than 64 draft tokens. */
+int spin_accept_tree(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft_len_host,
+                     const int32_t* parent_host, const int32_t* draft_tokens_dev,
+                     const float* target_logits_dev, const float* draft_logits_dev, int32_t vocab,
+                     const double* u_accept_dev, const double* u_sample_dev, int32_t* n_accepted_dev,
+                     int32_t* path_dev, int32_t* next_token_dev, void* hip_stream);
 
 /* A transformer calls spin_verify_attn once per layer with the same request table.  The context
  * therefore keeps the tables of its most recent attention call on the device, with a copy of what they

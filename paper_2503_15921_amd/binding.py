@@ -108,8 +108,8 @@ def load_library():
     lib.spin_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_void_p]
-    lib.spin_accept_tree.argtypes = [C.c_void_p, C.c_int32, _i32p, _i32p, C.c_void_p, C.c_void_p, C.c_int32,
-                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.spin_accept_tree.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, _i32p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.spin_set_plan_reuse.argtypes = [C.c_void_p, C.c_int32]
     lib.spin_profile_begin.argtypes = [C.c_void_p, C.c_int32]
     lib.spin_profile_every.argtypes = [C.c_void_p, C.c_int32]
@@ -253,16 +253,20 @@ class SpinContext:
     def set_waves(self, n_waves: int):
         _check(self._lib.spin_set_waves(self._h, n_waves), self._h)
 
-    def accept_tree(self, draft_len, parents, draft_tokens, target_logits, n_accepted, path, next_token, stream=None):
-        """spin_accept_tree.  draft_len, parents: host int32; the rest torch device tensors."""
+    def accept_tree(self, mode: int, draft_len, parents, draft_tokens, target_logits, draft_logits, u_accept, u_sample,
+                    n_accepted, path, next_token, stream=None):
+        """spin_accept_tree.  draft_len, parents: host int32; the rest torch device tensors (draft_logits and
+        the uniforms may be None in greedy mode)."""
         dl = _i32(draft_len)
         par = _i32(parents)
         vocab = target_logits.shape[-1]
         st = self._stream(stream)
+
+        def ptr(t):
+            return C.c_void_p(None if t is None else t.data_ptr())
         self._retry(lambda: self._lib.spin_accept_tree(
-            self._h, dl.shape[0], _ptr(dl), _ptr(par), C.c_void_p(draft_tokens.data_ptr()),
-            C.c_void_p(target_logits.data_ptr()), vocab, C.c_void_p(n_accepted.data_ptr()),
-            C.c_void_p(path.data_ptr()), C.c_void_p(next_token.data_ptr()), st))
+            self._h, mode, dl.shape[0], _ptr(dl), _ptr(par), ptr(draft_tokens), ptr(target_logits), ptr(draft_logits),
+            vocab, ptr(u_accept), ptr(u_sample), ptr(n_accepted), ptr(path), ptr(next_token), st))
 
     def set_plan_reuse(self, enable: bool):
         """Whether a call with the same tables as the previous one launches from the tables already staged."""

@@ -436,12 +436,150 @@ __global__ __launch_bounds__(64) void accept_tree_kernel(AcceptParams P, const i
     }
 }
 
+// Rejection-sampling verification of token trees: one workgroup per request walks down from the
+// root.  At a node with target distribution p the children are tried in index order against what is
+// left of p: with R_0 = p, s_0 = 1, child c (token d, drawn from q_c) is accepted iff
+// u_c q_c(d) s_k < R_k(d); a rejected child gives R_{k+1} = max(0, R_k - s_k q_c), s_{k+1} = sum R_{k+1}
+// (one sweep over the vocabulary by the whole workgroup; a child that would leave nothing is ignored).
+// When no child is accepted the next token is drawn from R_k.  R_k(x) is never stored: it is
+// re-evaluated from the k+1 logits rows involved, whose pointers and scale factors sit in LDS.
+constexpr int kMaxSiblings = 64;
+
+__global__ __launch_bounds__(kFinishThreads) void accept_tree_reject_kernel(AcceptParams P, const int32_t* parent,
+                                                                            int32_t* path) {
+    constexpr int kWaves = kFinishThreads / 64;
+    __shared__ double s_run[kMaxRuns];
+    __shared__ int s_last[kWaves];
+    __shared__ double s_total, s_before;
+    __shared__ int s_cross;
+    __shared__ double s_tab[64];
+    __shared__ const float* s_row[kMaxSiblings];     // draft rows of the rejected children of the current node
+    __shared__ double s_dmax[kMaxSiblings], s_coef[kMaxSiblings];   // their maxima and s_j / (their sums)
+    __shared__ double s_part[kWaves];
+    __shared__ int s_flag;
+    const DrawShared sh = {s_run, s_last, &s_total, &s_before, &s_cross};
+    const int req = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r0 = P.row_off[req];
+    const int g = P.row_off[req + 1] - r0;
+    const int base = r0 + req;                  // target row of the root; node t owns row base + 1 + t
+    const int n_target = P.n_rows + P.n_req;
+    const int V = P.vocab;
+    if (wave == 1) s_tab[lane] = exp2((double)lane * (1.0 / 64.0));
+    __syncthreads();
+
+    int cur = -1, n = 0;
+    while (true) {
+        const float* tl = P.target_logits + (int64_t)(base + cur + 1) * V;
+        const double tmax = (double)P.row_max[base + cur + 1], tinv = 1.0 / P.row_sum[base + cur + 1];
+        int k = 0;              // rejected children of this node that count
+        double sk = 1.0;
+        // R_depth(x) for one id
+        auto mass1 = [&](int x, int depth) {
+            double v = exp_table64((double)tl[x] - tmax, s_tab) * tinv;
+            for (int j = 0; j < depth; ++j) {
+                v -= exp_table64((double)s_row[j][x] - s_dmax[j], s_tab) * s_coef[j];
+                v = v > 0.0 ? v : 0.0;
+            }
+            return v;
+        };
+        bool moved = false;
+        for (int c = cur + 1; c < g; ++c) {         // children come after their parent
+            if (parent[r0 + c] != cur) continue;
+            const float* dl = P.draft_logits + (int64_t)(r0 + c) * V;
+            const double dmax = (double)P.row_max[n_target + r0 + c], dinv = 1.0 / P.row_sum[n_target + r0 + c];
+            if (tid == 0) {
+                const int d = P.draft_tokens[r0 + c];
+                bool keep = false;
+                if (d >= 0 && d < V) {
+                    const double q = exp_table64((double)dl[d] - dmax, s_tab) * dinv;
+                    keep = P.u_accept[r0 + c] * q * sk < mass1(d, k);
+                }
+                s_flag = keep;
+            }
+            __syncthreads();
+            const bool keep = s_flag;
+            if (keep) {
+                if (tid == 0) path[r0 + n] = c;
+                cur = c;
+                ++n;
+                moved = true;
+                __syncthreads();                     // s_flag is written again at the next node
+                break;
+            }
+            // rejected: what would be left after taking s_k q_c out of R_k?
+            if (k < kMaxSiblings) {
+                if (tid == 0) {
+                    s_row[k] = dl;
+                    s_dmax[k] = dmax;
+                    s_coef[k] = sk * dinv;
+                }
+                __syncthreads();
+                double sum = 0.0;
+                for (int x = tid; x < V; x += kFinishThreads) sum += mass1(x, k + 1);
+                for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+                if (lane == 0) s_part[wave] = sum;
+                __syncthreads();
+                double tot = 0.0;
+                for (int w = 0; w < kWaves; ++w) tot += s_part[w];
+                if (tot > 0.0) {
+                    ++k;
+                    sk = tot;
+                }
+            }
+            __syncthreads();
+        }
+        if (moved) continue;
+
+        // ---- no child was accepted: the next token comes from R_k
+        const bool vec = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(tl) & 15) == 0) &&
+                         ((reinterpret_cast<uintptr_t>(P.draft_logits) & 15) == 0);
+        auto mass4 = [&](int x0, double m[4]) {
+            float a[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            if (vec && x0 + 3 < V) {
+                const float4 va = *reinterpret_cast<const float4*>(tl + x0);
+                a[0] = va.x; a[1] = va.y; a[2] = va.z; a[3] = va.w;
+            } else {
+                for (int j = 0; j < 4; ++j)
+                    if (x0 + j < V) a[j] = tl[x0 + j];
+            }
+            for (int j = 0; j < 4; ++j) m[j] = x0 + j < V ? exp_table64((double)a[j] - tmax, s_tab) * tinv : 0.0;
+            for (int s = 0; s < k; ++s) {
+                float b[4] = {0.f, 0.f, 0.f, 0.f};
+                if (vec && x0 + 3 < V) {
+                    const float4 vb = *reinterpret_cast<const float4*>(s_row[s] + x0);
+                    b[0] = vb.x; b[1] = vb.y; b[2] = vb.z; b[3] = vb.w;
+                } else {
+                    for (int j = 0; j < 4; ++j)
+                        if (x0 + j < V) b[j] = s_row[s][x0 + j];
+                }
+                for (int j = 0; j < 4; ++j)
+                    if (x0 + j < V) {
+                        const double v = m[j] - exp_table64((double)b[j] - s_dmax[s], s_tab) * s_coef[s];
+                        m[j] = v > 0.0 ? v : 0.0;
+                    }
+            }
+        };
+        if (!draw_inverse_cdf(mass4, V, P.u_sample[req], &P.next_token[req], sh)) {
+            // cannot happen (R_0 sums to one and a child that leaves nothing is ignored); be defined anyway
+            if (tid == 0) P.next_token[req] = P.row_arg[base + cur + 1];
+        }
+        break;
+    }
+    if (tid >= n && tid < g) path[r0 + tid] = -1;
+    if (tid == 0) P.n_accepted[req] = n;
+}
+
 hipError_t launch_accept_tree(const AcceptParams& p, const int32_t* parent, int32_t* path, hipStream_t stream) {
     if (p.n_req <= 0) return hipSuccess;
-    hipLaunchKernelGGL(row_stats_kernel, dim3(p.n_rows + p.n_req), dim3(kStatThreads), 0, stream, p);
+    const int n_stat_rows = p.mode == SPIN_ACCEPT_GREEDY ? p.n_rows + p.n_req : 2 * p.n_rows + p.n_req;
+    hipLaunchKernelGGL(row_stats_kernel, dim3(n_stat_rows), dim3(kStatThreads), 0, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(accept_tree_kernel, dim3(p.n_req), dim3(64), 0, stream, p, parent, path);
+    if (p.mode == SPIN_ACCEPT_GREEDY)
+        hipLaunchKernelGGL(accept_tree_kernel, dim3(p.n_req), dim3(64), 0, stream, p, parent, path);
+    else
+        hipLaunchKernelGGL(accept_tree_reject_kernel, dim3(p.n_req), dim3(kFinishThreads), 0, stream, p, parent, path);
     return hipGetLastError();
 }
 

@@ -674,11 +674,16 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     return SPIN_OK;
 }
 
-int spin_accept_tree(spin_ctx* ctx, int32_t n_req, const int32_t* draft_len_host, const int32_t* parent_host,
-                     const int32_t* draft_tokens_dev, const float* target_logits_dev, int32_t vocab,
-                     int32_t* n_accepted_dev, int32_t* path_dev, int32_t* next_token_dev, void* hip_stream) {
+int spin_accept_tree(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft_len_host,
+                     const int32_t* parent_host, const int32_t* draft_tokens_dev, const float* target_logits_dev,
+                     const float* draft_logits_dev, int32_t vocab, const double* u_accept_dev,
+                     const double* u_sample_dev, int32_t* n_accepted_dev, int32_t* path_dev, int32_t* next_token_dev,
+                     void* hip_stream) {
     if (!ctx) return SPIN_EINVAL;
+    if (mode != SPIN_ACCEPT_GREEDY && mode != SPIN_ACCEPT_REJECTION) return fail(ctx, SPIN_EINVAL, "unknown mode");
     if (n_req < 0 || vocab < 1) return fail(ctx, SPIN_EINVAL, "n_req < 0 or vocab < 1");
+    if (mode == SPIN_ACCEPT_REJECTION && vocab > spin::kMaxVocab)
+        return fail(ctx, SPIN_EUNSUPPORTED, "vocabulary larger than 1048576 ids");
     if (n_req == 0) return SPIN_OK;
     if (!draft_len_host || !parent_host) return fail(ctx, SPIN_EINVAL, "draft_len or parent is null");
     ctx->row_off_host.resize(n_req + 1);
@@ -700,6 +705,8 @@ int spin_accept_tree(spin_ctx* ctx, int32_t n_req, const int32_t* draft_len_host
     ctx->row_off_host[n_req] = (int32_t)rows;
     if (!draft_tokens_dev || !target_logits_dev || !n_accepted_dev || !path_dev || !next_token_dev)
         return fail(ctx, SPIN_EINVAL, "null device pointer");
+    if (mode == SPIN_ACCEPT_REJECTION && (!draft_logits_dev || !u_accept_dev || !u_sample_dev))
+        return fail(ctx, SPIN_EINVAL, "rejection mode needs draft logits and both uniform arrays");
     if (n_req > ctx->cap_req || rows > ctx->cap_rows) {
         ctx->need_req = std::max<int64_t>(n_req, ctx->cap_req);
         ctx->need_rows = std::max<int64_t>(rows, ctx->cap_rows);
@@ -726,6 +733,9 @@ int spin_accept_tree(spin_ctx* ctx, int32_t n_req, const int32_t* draft_len_host
     p.row_off = (const int32_t*)mapped;
     p.draft_tokens = draft_tokens_dev;
     p.target_logits = target_logits_dev;
+    p.draft_logits = draft_logits_dev;
+    p.u_accept = u_accept_dev;
+    p.u_sample = u_sample_dev;
     p.row_max = ctx->d_row_max;
     p.row_sum = ctx->d_row_sum;
     p.row_arg = ctx->d_row_arg;
@@ -734,7 +744,7 @@ int spin_accept_tree(spin_ctx* ctx, int32_t n_req, const int32_t* draft_len_host
     p.n_req = n_req;
     p.n_rows = (int32_t)rows;
     p.vocab = vocab;
-    p.mode = SPIN_ACCEPT_GREEDY;
+    p.mode = mode;
     e = spin::launch_accept_tree(p, (const int32_t*)((char*)mapped + off_parent), path_dev, stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "tree acceptance launch");
     e = hipEventRecord(ctx->ev[slot], stream);

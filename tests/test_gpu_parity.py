@@ -714,12 +714,14 @@ def test_accept_token_outside_vocabulary_is_rejected(ctx):
 
 
 # ------------------------------------------------------------------------------ greedy tree acceptance
-def hip_accept_tree(ctx, draft_len, parents, tokens, logits):
+def hip_accept_tree(ctx, draft_len, parents, tokens, logits, draft_logits=None, u_accept=None, u_sample=None):
+    import paper_2503_15921_amd as spin
     B, R = len(draft_len), int(np.sum(draft_len))
     n_acc = torch.full((B,), -7, dtype=torch.int32, device="cuda")
     nxt = torch.full((B,), -7, dtype=torch.int32, device="cuda")
     path = torch.full((R,), -7, dtype=torch.int32, device="cuda")
-    ctx.accept_tree(draft_len, parents, tokens, logits, n_acc, path, nxt)
+    mode = spin.ACCEPT_GREEDY if draft_logits is None else spin.ACCEPT_REJECTION
+    ctx.accept_tree(mode, draft_len, parents, tokens, logits, draft_logits, u_accept, u_sample, n_acc, path, nxt)
     torch.cuda.synchronize()
     return n_acc.cpu().numpy(), path.cpu().numpy(), nxt.cpu().numpy()
 
@@ -758,6 +760,72 @@ def test_accept_tree_greedy(ctx, vocab, shape):
         torch.cuda.synchronize()
         np.testing.assert_array_equal(ab_n.cpu().numpy(), n_o)
         np.testing.assert_array_equal(ab_t.cpu().numpy(), nxt_o)
+
+
+@pytest.mark.parametrize("vocab", [3, 37, 1000, 32000])
+@pytest.mark.parametrize("shape", ["random", "wide", "star", "chain"])
+def test_accept_tree_rejection(ctx, vocab, shape):
+    import paper_2503_15921_amd as spin
+    rng = np.random.default_rng(10 * vocab + len(shape))
+    draft_len = np.array([64, 1, 7, 30, 2, 12] if vocab <= 1000 else [20, 1, 7, 9], dtype=np.int32)
+    parents, _ = si.random_trees(draft_len, rng, shape)
+    R, B = int(draft_len.sum()), len(draft_len)
+    # target rows; every draft token is drawn from a draft row correlated with its parent's target row
+    tl = rng.normal(0, 2, (R + B, vocab)).astype(np.float32)
+    dl = np.empty((R, vocab), dtype=np.float32)
+    tokens = np.empty(R, dtype=np.int32)
+    r = 0
+    for i, g in enumerate(draft_len):
+        for t in range(g):
+            prow = tl[r + i + parents[r + t] + 1]
+            dl[r + t] = 0.95 * prow + 0.31 * rng.normal(0, 2, vocab)
+            tokens[r + t] = rng.choice(vocab, p=orc._softmax64(dl[r + t]))
+        r += g
+    ua, us = rng.random(R), rng.random(B)
+    n_o, path_o, nxt_o, margin = orc.accept_tree_rejection(draft_len, parents, tokens, tl, dl, ua, us)
+    assert margin.min() > 1e-9, f"decision margin {margin.min():.2e} too small to compare bit for bit"
+    dev = lambda a: torch.from_numpy(a).cuda()
+    n_g, path_g, nxt_g = hip_accept_tree(ctx, draft_len, parents, dev(tokens), dev(tl), dev(dl), dev(ua), dev(us))
+    np.testing.assert_array_equal(n_g, n_o)
+    np.testing.assert_array_equal(path_g, path_o)
+    np.testing.assert_array_equal(nxt_g, nxt_o)
+    if shape != "star":
+        assert n_o.max() >= 2
+    if shape == "chain":        # the linear rule gives the same
+        n_l = torch.full((B,), -7, dtype=torch.int32, device="cuda"); t_l = torch.full_like(n_l, -7)
+        ctx.accept(spin.ACCEPT_REJECTION, draft_len, dev(tokens), dev(tl), dev(dl), dev(ua), dev(us), n_l, t_l)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(n_l.cpu().numpy(), n_o)
+        np.testing.assert_array_equal(t_l.cpu().numpy(), nxt_o)
+
+
+def test_accept_tree_rejection_many_rejected_siblings(ctx):
+    # a node with many children that are all turned down (uniforms at 1 - eps): the residual is taken apart
+    # child by child; some children carry invalid token ids, two carry the same distribution as the target
+    rng = np.random.default_rng(77)
+    vocab = 200
+    draft_len = np.array([24, 10], dtype=np.int32)
+    parents = np.concatenate([np.full(24, -1), np.array([-1, 0, 0, 0, 0, 0, 0, 0, 0, 0])]).astype(np.int32)
+    R, B = 34, 2
+    tl = rng.normal(0, 2, (R + B, vocab)).astype(np.float32)
+    dl = rng.normal(0, 2, (R, vocab)).astype(np.float32)
+    dl[3] = tl[0]; dl[9] = tl[0]
+    # every child carries the token its parent's target row likes least, so that u = 1 - eps turns it down
+    tokens = np.empty(R, dtype=np.int32)
+    tokens[:24] = int(np.argmin(tl[0]))
+    tokens[24] = int(np.argmax(tl[24 + 1]))
+    tokens[25:] = int(np.argmin(tl[24 + 1 + 1]))
+    dl[24, tokens[24]] -= 5.0                            # (and the accepted one is under-proposed: p/q > 1)
+    tokens[5] = vocab + 4; tokens[11] = -3
+    ua = np.full(R, 1.0 - 1e-12); ua[24] = 0.0          # second request: its first token is accepted, its nine children are not
+    us = rng.random(B)
+    n_o, path_o, nxt_o, margin = orc.accept_tree_rejection(draft_len, parents, tokens, tl, dl, ua, us)
+    assert n_o.tolist() == [0, 1]
+    dev = lambda a: torch.from_numpy(a).cuda()
+    n_g, path_g, nxt_g = hip_accept_tree(ctx, draft_len, parents, dev(tokens), dev(tl), dev(dl), dev(ua), dev(us))
+    np.testing.assert_array_equal(n_g, n_o)
+    np.testing.assert_array_equal(path_g, path_o)
+    np.testing.assert_array_equal(nxt_g, nxt_o)
 
 
 def test_accept_tree_errors(ctx):
