@@ -82,7 +82,8 @@ def main():
     ap.add_argument("--append", action="store_true",
                     help="the step also scatters the draft tokens' K/V rows into the cache first (spin_append_kv)")
     ap.add_argument("--tree", default="", help="drafts are token trees of this shape (random, star, wide, chain): "
-                                               "spin_verify_attn_tree instead of spin_verify_attn")
+                                               "spin_verify_attn_tree and spin_accept_tree instead of the linear calls "
+                                               "(the acceptance kernels of the tree call are not timed separately)")
     ap.add_argument("--decomp", default="config",
                     help="decomposition of the batch: config (the configuration's own), none, q:<width>, kv:<length>, "
                          "search:<max sub-requests> (the padding-minimising length search of Sec. V-A)")
@@ -140,7 +141,8 @@ def main():
         k_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
         v_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
 
-    masks = si.random_trees(t.draft_len, np.random.default_rng(args.seed), args.tree)[1] if args.tree else None
+    parents, masks = si.random_trees(t.draft_len, np.random.default_rng(args.seed), args.tree) if args.tree else (None, None)
+    path = torch.empty(t.n_rows, dtype=torch.int32, device=dev)
     # micro-batches: contiguous request ranges of about equal K/V volume
     tok = np.cumsum(t.prefix_len.astype(np.int64) + t.draft_len)
     cuts = [0] + [int(np.searchsorted(tok, tok[-1] * (m + 1) / M, side="left")) + 1 for m in range(M - 1)] + [t.n_req]
@@ -157,6 +159,7 @@ def main():
             q=batch.q[r0:r1], out=out[r0:r1], tokens=ab.draft_tokens[r0:r1], target=ab.target_logits[r0 + i0:r1 + i1],
             dlogits=ab.draft_logits[r0:r1], u_acc=ab.u_accept[r0:r1], u_smp=ab.u_sample[i0:i1],
             n_acc=n_acc[i0:i1], nxt=nxt[i0:i1], masks=masks[r0:r1] if args.tree else None,
+            parents=parents[r0:r1] if args.tree else None, path=path[r0:r1],
             k_new=k_new[r0:r1] if args.append else None, v_new=v_new[r0:r1] if args.append else None))
 
     def decomposition(prefix, draft):
@@ -191,8 +194,12 @@ def main():
                                       tree_mask=mb["masks"])
                 if S > 1:
                     attn_done[k].record(mb["stream"])
-                mb["ctx"].accept(spin.ACCEPT_REJECTION, mb["draft"], mb["tokens"], mb["target"], mb["dlogits"],
-                                 mb["u_acc"], mb["u_smp"], mb["n_acc"], mb["nxt"])
+                if args.tree:
+                    mb["ctx"].accept_tree(spin.ACCEPT_REJECTION, mb["draft"], mb["parents"], mb["tokens"], mb["target"],
+                                          mb["dlogits"], mb["u_acc"], mb["u_smp"], mb["n_acc"], mb["path"], mb["nxt"])
+                else:
+                    mb["ctx"].accept(spin.ACCEPT_REJECTION, mb["draft"], mb["tokens"], mb["target"], mb["dlogits"],
+                                     mb["u_acc"], mb["u_smp"], mb["n_acc"], mb["nxt"])
 
     for _ in range(args.warmup):
         step()
