@@ -255,23 +255,32 @@ int spin_reserve(spin_ctx* ctx, int64_t max_req, int64_t max_rows, int64_t max_p
 
 namespace {
 
+// What every call that takes a K/V descriptor demands of it (the attention kernels further restrict head_dim).
+int check_kv_desc(spin_ctx* ctx, const spin_kv_desc* kv) {
+    if (kv->dtype != SPIN_DTYPE_BF16) return fail(ctx, SPIN_EUNSUPPORTED, "only bf16 K/V is supported");
+    if (kv->head_dim < 8 || kv->head_dim % 8) return fail(ctx, SPIN_EUNSUPPORTED, "head_dim must be a multiple of 8");
+    if (kv->page_size < 1 || (kv->page_size & (kv->page_size - 1)))
+        return fail(ctx, SPIN_EUNSUPPORTED, "page_size must be a power of two");
+    if (kv->n_kv_heads < 1) return fail(ctx, SPIN_EINVAL, "n_kv_heads < 1");
+    if (kv->n_pages < 0 || kv->token_stride < kv->head_dim || kv->token_stride % 8 || kv->page_stride % 8 ||
+        kv->head_stride % 8 || kv->page_stride < 0 || kv->head_stride < 0)
+        return fail(ctx, SPIN_EINVAL, "bad K/V strides (must be non-negative multiples of 8 elements)");
+    return SPIN_OK;
+}
+
 // Both attention entry points; tree_mask is null for linear drafts.
 int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* table, const spin_subreq* subs,
                      int32_t n_sub, const uint64_t* tree_mask, const void* q_dev, void* o_dev, int32_t n_q_heads,
                      float softmax_scale, void* hip_stream) {
     if (!ctx) return SPIN_EINVAL;
     if (!kv || !table) return fail(ctx, SPIN_EINVAL, "kv descriptor or request table is null");
-    if (kv->dtype != SPIN_DTYPE_BF16) return fail(ctx, SPIN_EUNSUPPORTED, "only bf16 K/V is supported");
     if (kv->head_dim != 64 && kv->head_dim != 128) return fail(ctx, SPIN_EUNSUPPORTED, "head_dim must be 64 or 128");
-    if (kv->page_size < 1 || (kv->page_size & (kv->page_size - 1)))
-        return fail(ctx, SPIN_EUNSUPPORTED, "page_size must be a power of two");
-    if (kv->n_kv_heads < 1 || n_q_heads < 1 || n_q_heads % kv->n_kv_heads)
+    int rc = check_kv_desc(ctx, kv);
+    if (rc) return rc;
+    if (n_q_heads < 1 || n_q_heads % kv->n_kv_heads)
         return fail(ctx, SPIN_EINVAL, "n_q_heads must be a positive multiple of n_kv_heads");
     const int group = n_q_heads / kv->n_kv_heads;
     if (group > spin::kMaxTileRows) return fail(ctx, SPIN_EUNSUPPORTED, "more than 64 query heads per KV head");
-    if (kv->n_pages < 0 || kv->token_stride < kv->head_dim || kv->token_stride % 8 || kv->page_stride % 8 ||
-        kv->head_stride % 8 || kv->page_stride < 0 || kv->head_stride < 0)
-        return fail(ctx, SPIN_EINVAL, "bad K/V strides (must be non-negative multiples of 8 elements)");
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -289,7 +298,6 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     }
     StagedPlan& sp = ctx->staged;
     std::string err;
-    int rc;
 
     // ---- the same tables as last time?  (compared by content: the caller's arrays may have been rewritten)
     bool hit = false;
@@ -536,15 +544,10 @@ int spin_append_kv(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* 
                    const void* v_new_dev, void* hip_stream) {
     if (!ctx) return SPIN_EINVAL;
     if (!kv || !table) return fail(ctx, SPIN_EINVAL, "kv descriptor or request table is null");
-    if (kv->dtype != SPIN_DTYPE_BF16) return fail(ctx, SPIN_EUNSUPPORTED, "only bf16 K/V is supported");
-    if (kv->head_dim < 8 || kv->head_dim % 8) return fail(ctx, SPIN_EUNSUPPORTED, "head_dim must be a multiple of 8");
-    if (kv->page_size < 1 || (kv->page_size & (kv->page_size - 1)))
-        return fail(ctx, SPIN_EUNSUPPORTED, "page_size must be a power of two");
-    if (kv->n_kv_heads < 1 || kv->n_pages < 0 || kv->token_stride < kv->head_dim || kv->token_stride % 8 ||
-        kv->page_stride % 8 || kv->head_stride % 8 || kv->page_stride < 0 || kv->head_stride < 0)
-        return fail(ctx, SPIN_EINVAL, "bad K/V descriptor");
+    int rc = check_kv_desc(ctx, kv);
+    if (rc) return rc;
     std::string err;
-    int rc = spin::validate_table(table, kv->page_size, kv->n_pages, true, err);
+    rc = spin::validate_table(table, kv->page_size, kv->n_pages, true, err);
     if (rc) return fail(ctx, rc, err);
     if (table->n_req == 0) return SPIN_OK;
     if (!kv->k_pool || !kv->v_pool || !k_new_dev || !v_new_dev) return fail(ctx, SPIN_EINVAL, "null device pointer");
