@@ -843,6 +843,61 @@ def test_accept_tree_errors(ctx):
     assert ei.value.code == spin.ETABLE
 
 
+# ------------------------------------------------------------------------------ all calls in sequence
+@pytest.mark.parametrize("hq,hkv,page", [(4, 4, 16), (8, 2, 4)])
+def test_decode_loop_append_verify_accept(ctx, hq, hkv, page):
+    """Eight speculative steps of a small batch, every call on the GPU shadowed by the oracle: the drafts'
+    K/V are appended, verified and accepted; the prefixes grow by the accepted lengths, so rejected slots are
+    overwritten by the next step's drafts and the tables differ from step to step."""
+    import paper_2503_15921_amd as spin
+    rng = np.random.default_rng(1234 + hq)
+    B, d, vocab, steps, max_draft = 5, 64, 300, 8, 5
+    prefix = rng.integers(0, 40, B).astype(np.int32)
+    # pages for the longest any request can get; the cache starts with random prefixes
+    table0 = si.make_table(prefix + steps * max_draft, np.ones(B, dtype=np.int32), page, rng)
+    cfg = make_cfg("loop", B, hq, hkv, d, page=page)
+    g = torch.Generator(device="cpu").manual_seed(99)
+    k_pool = torch.randn((table0.n_pages, hkv, page, d), generator=g).to(torch.bfloat16).cuda()
+    v_pool = torch.randn((table0.n_pages, hkv, page, d), generator=g).to(torch.bfloat16).cuda()
+    k_ref, v_ref = si.bf16_bits(k_pool).copy(), si.bf16_bits(v_pool).copy()
+    dev = lambda a: torch.from_numpy(a).cuda()
+    scale = 1.0 / math.sqrt(d)
+    for step in range(steps):
+        draft = rng.integers(1, max_draft + 1, B).astype(np.int32)
+        q_off = np.concatenate([[0], np.cumsum(draft)]).astype(np.int32)
+        R = int(q_off[-1])
+        tab = ctx.make_table(prefix, draft, q_off, table0.pt_offset, table0.page_table)
+        # 1. the drafts' K/V enter the cache
+        k_new = torch.randn((R, hkv, d), generator=g).to(torch.bfloat16).cuda()
+        v_new = torch.randn((R, hkv, d), generator=g).to(torch.bfloat16).cuda()
+        ctx.append_kv(tab, k_pool, v_pool, k_new, v_new)
+        orc.append_kv(prefix, draft, q_off, table0.pt_offset, table0.page_table, page, k_ref, v_ref,
+                      si.bf16_bits(k_new), si.bf16_bits(v_new))
+        # 2. attention of the draft rows (same stream, no synchronisation in between)
+        q = torch.randn((R, hq, d), generator=g).to(torch.bfloat16).cuda()
+        out = torch.full_like(q, float("nan"))
+        ctx.verify_attn(tab, k_pool, v_pool, q, out, hq)
+        # 3. acceptance
+        tl = rng.normal(0, 2, (R + B, vocab)).astype(np.float32)
+        own = np.delete(tl, q_off[1:] + np.arange(B), axis=0)
+        dl = (0.9 * own + 0.44 * rng.normal(0, 2, (R, vocab))).astype(np.float32)
+        tok = np.array([rng.choice(vocab, p=orc._softmax64(dl[r])) for r in range(R)], dtype=np.int32)
+        ua, us = rng.random(R), rng.random(B)
+        n_acc = torch.full((B,), -7, dtype=torch.int32, device="cuda"); nxt = torch.full_like(n_acc, -7)
+        ctx.accept(spin.ACCEPT_REJECTION, draft, dev(tok), dev(tl), dev(dl), dev(ua), dev(us), n_acc, nxt)
+        torch.cuda.synchronize()
+        assert np.array_equal(si.bf16_bits(k_pool), k_ref) and np.array_equal(si.bf16_bits(v_pool), v_ref), f"step {step}: cache"
+        want = orc.verify_attention(prefix, draft, q_off, table0.pt_offset, table0.page_table, page, si.bf16_bits(q),
+                                    k_ref, v_ref, hq, hkv, scale)
+        assert_close(out, want, f"step {step}: attention")
+        n_o, t_o, margin = orc.accept_rejection(draft, tok, tl, dl, ua, us)
+        assert margin.min() > 1e-9
+        np.testing.assert_array_equal(n_acc.cpu().numpy(), n_o, err_msg=f"step {step}")
+        np.testing.assert_array_equal(nxt.cpu().numpy(), t_o, err_msg=f"step {step}")
+        prefix = (prefix + n_o).astype(np.int32)          # the accepted drafts stay, the rest is overwritten next time
+    assert (prefix > 0).any()
+
+
 # ------------------------------------------------------------------------------ error paths
 def test_errors_before_launch(ctx):
     import paper_2503_15921_amd as spin
