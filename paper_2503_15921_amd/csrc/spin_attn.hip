@@ -473,7 +473,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 // queue are the same, with the workgroup in the wavefront's place; results are stored as they
 // finish (a workgroup meets few ends of a (request, KV head) per share).
 template <int D, int NW, bool TREE>
-__global__ __launch_bounds__(64 * NW) void verify_attn_group_kernel(AttnParams P) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void verify_attn_group_kernel(AttnParams P) {
     constexpr int DCH = D / 8;
     constexpr int KCALLS = D / 32;
     constexpr int KLOADS = DCH / 2;
