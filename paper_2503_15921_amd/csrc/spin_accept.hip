@@ -32,29 +32,28 @@ __device__ __forceinline__ MaxArg better(MaxArg a, MaxArg b) {
     return a;
 }
 
-// exp(d) in float64 for the row sums, d below about 700: d = (64 e + j) ln2/64 + r with |r| <= ln2/128, so
-// exp(d) = 2^e * 2^(j/64) * exp(r) with a 64-entry table (in LDS) and a degree-5 polynomial for exp(r)
-// (remainder r^6/720 < 4e-17).  About two thirds of the float64 instructions of the general routine.
-// Minus infinity (and anything below -800) gives 0.
+// exp(d) in float64 for the sums and masses, d below about 700: d = (256 e + j) ln2/256 + r with
+// |r| <= ln2/512, so exp(d) = 2^e * 2^(j/256) * exp(r) with a 256-entry table (in LDS) and a cubic for
+// exp(r) (remainder r^4/24 < 1.4e-13 relative: four orders below what the accept decisions need, and
+// about half the float64 instructions of the general routine).  Minus infinity (and anything below
+// -800) gives 0.
 __device__ __forceinline__ double exp_table64(double d, const double* tab) {
     d = fmax(d, -800.0);
-    const double kd = __builtin_rint(d * 92.332482616893656758);            // 64 / ln 2
-    double r = fma(kd, -1.0830424696249145e-02, d);                           // ln2/64, high part
-    r = fma(kd, -3.623510646634843e-19, r);                                  // ln2/64 - high part
+    const double kd = __builtin_rint(d * 369.3299304675746);            // 256 / ln 2
+    double r = fma(kd, -0.0027076061740622863, d);                           // ln2/256, high part
+    r = fma(kd, -9.058776616587108e-20, r);                                  // ln2/256 - high part
     const int k = (int)kd;
-    double p = fma(r, 1.0 / 120.0, 1.0 / 24.0);
-    p = fma(p, r, 1.0 / 6.0);
-    p = fma(p, r, 0.5);
+    double p = fma(r, 1.0 / 6.0, 0.5);
     p = fma(p, r, 1.0);
     p = fma(p, r, 1.0);
-    return ldexp(tab[k & 63] * p, k >> 6);
+    return ldexp(tab[k & 255] * p, k >> 8);
 }
 
 __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(AcceptParams P) {
     __shared__ MaxArg s_ma[kStatThreads / 64];
     __shared__ double s_sum[kStatThreads / 64];
     __shared__ float s_ref[kStatThreads / 64];
-    __shared__ double s_tab[64];
+    __shared__ double s_tab[256];
     const int row = blockIdx.x;
     const int n_target = P.n_rows + P.n_req;
     const float* x = row < n_target ? P.target_logits + (int64_t)row * P.vocab
@@ -97,7 +96,7 @@ __global__ __launch_bounds__(kStatThreads) void row_stats_kernel(AcceptParams P)
     // against a reference found in the row's first elements while the true maximum is tracked beside
     // them, and the sum is moved to the true maximum at the end (float64 has the range for that as
     // long as the two are within a few hundred of each other; otherwise the row is swept twice).
-    if (tid < 64) s_tab[tid] = exp2((double)tid * (1.0 / 64.0));
+    s_tab[tid] = exp2((double)tid * (1.0 / 256.0));
     float ref = -INFINITY;
     if (vec) {
         if (tid < V / 4) {
@@ -314,7 +313,7 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
     __shared__ int s_last[kWaves];
     __shared__ double s_total, s_before;
     __shared__ int s_cross;
-    __shared__ double s_tab[64];                 // 2^(j/64) for exp_table64
+    __shared__ double s_tab[256];                 // 2^(j/256) for exp_table64
     const DrawShared sh = {s_run, s_last, &s_total, &s_before, &s_cross};
     const int req = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -324,7 +323,7 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
     const int n_target = P.n_rows + P.n_req;
     const int V = P.vocab;
 
-    if (wave == 1) s_tab[lane] = exp2((double)lane * (1.0 / 64.0));   // ready at the barrier below
+    if (tid < 256) s_tab[tid] = exp2((double)tid * (1.0 / 256.0));   // ready at the barrier below
     // ---- first-reject scan: wavefront 0 tests 64 draft rows at a time, one per lane
     if (wave == 0) {
         int n = g;
@@ -452,7 +451,7 @@ __global__ __launch_bounds__(kFinishThreads) void accept_tree_reject_kernel(Acce
     __shared__ int s_last[kWaves];
     __shared__ double s_total, s_before;
     __shared__ int s_cross;
-    __shared__ double s_tab[64];
+    __shared__ double s_tab[256];
     __shared__ const float* s_row[kMaxSiblings];     // draft rows of the rejected children of the current node
     __shared__ double s_dmax[kMaxSiblings], s_coef[kMaxSiblings];   // their maxima and s_j / (their sums)
     __shared__ double s_part[kWaves];
@@ -465,7 +464,7 @@ __global__ __launch_bounds__(kFinishThreads) void accept_tree_reject_kernel(Acce
     const int base = r0 + req;                  // target row of the root; node t owns row base + 1 + t
     const int n_target = P.n_rows + P.n_req;
     const int V = P.vocab;
-    if (wave == 1) s_tab[lane] = exp2((double)lane * (1.0 / 64.0));
+    if (tid < 256) s_tab[tid] = exp2((double)tid * (1.0 / 256.0));
     __syncthreads();
 
     int cur = -1, n = 0;
