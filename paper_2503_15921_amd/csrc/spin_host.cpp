@@ -260,7 +260,9 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
         // small chunks that wavefronts take from a queue as they finish (sizes shrink towards the end).
         std::vector<int64_t>& bounds = plan.bounds;
         bounds.clear();
-        const int64_t T_dyn = (W >= kMinDynamicWaves && T / W * bk >= kMinKeysForQueue) ? T * kDynamicPercent / 100 : 0;
+        // (The grouped-query kernel gets no queue: its workgroups end within a few percent of each other
+        // anyway, and the extra cuts cost more in partial results to join than the evening-out saves.)
+        const int64_t T_dyn = (c < 2 && W >= kMinDynamicWaves && T / W * bk >= kMinKeysForQueue) ? T * kDynamicPercent / 100 : 0;
         const int64_t T_static = T - T_dyn;
         for (int64_t w = 1; w <= W; ++w) bounds.push_back(w * T_static / W);
         if (T_dyn == 0 && T / W <= kSnapShareBlocks) {
