@@ -8,6 +8,7 @@ QK^T, mask, online softmax, PV, join) for ONE attention layer, and spin_accept (
 row statistics, first-reject scan, residual / bonus draw).  Prints one JSON line.
 """
 import argparse
+import dataclasses
 import json
 import math
 import os
@@ -77,6 +78,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="13b")
     ap.add_argument("--seed", type=int, default=3)
+    ap.add_argument("--page-size", type=int, default=0, help="tokens per KV page (0 = the configuration's, 16)")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per attention launch (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--append", action="store_true",
@@ -110,6 +112,8 @@ def main():
     import spin_inputs as si
 
     cfg = si.CONFIGS[args.config]
+    if args.page_size:
+        cfg = dataclasses.replace(cfg, page_size=args.page_size)
     dev = "cuda:0"
     if args.calib_copy:
         # known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE: each step reads 1 GiB and writes 1 GiB

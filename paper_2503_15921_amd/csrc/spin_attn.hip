@@ -194,16 +194,16 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
         const int pg = sPT[buf][(key >> pshift) - pg0];
         return pool + (int64_t)pg * P.page_stride + head_off + (int64_t)(key & pmask) * P.token_stride;
     };
-    // With 16-token pages whose rows are contiguous (token_stride == D), a full 32-key block that starts
-    // on a page boundary is exactly two page-head tiles: two wavefront-uniform base addresses plus
-    // constant per-lane offsets, no per-lane address arithmetic.  Anything else takes the general path.
-    const bool tile_layout = pshift == 4 && P.token_stride == D;
+    // With pages of 16 tokens or more whose rows are contiguous (token_stride == D), a full 32-key block
+    // that starts on a multiple of 32 is two runs of 16 contiguous rows (two pages, or two halves of one):
+    // two wavefront-uniform base addresses plus constant per-lane offsets, no per-lane address
+    // arithmetic.  Anything else takes the general path.
+    const bool tile_layout = pshift >= 4 && P.token_stride == D;
     auto page_bases = [&](const uint16_t* pool, int buf, int pg0, int64_t head_off, int kb, const char*& a, const char*& b) {
-        const int pi = (kb >> 4) - pg0;
-        const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][pi]);
-        const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][pi + 1]);
-        a = (const char*)(pool + (int64_t)pga * P.page_stride + head_off);
-        b = (const char*)(pool + (int64_t)pgb * P.page_stride + head_off);
+        const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][(kb >> pshift) - pg0]);
+        const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][((kb + 16) >> pshift) - pg0]);
+        a = (const char*)(pool + (int64_t)pga * P.page_stride + head_off + (int64_t)(kb & pmask) * D);
+        b = (const char*)(pool + (int64_t)pgb * P.page_stride + head_off + (int64_t)((kb + 16) & pmask) * D);
     };
     auto load_k = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
         if (tile_layout && !(kb & 31) && kb + 32 <= k1) {
@@ -548,14 +548,14 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const int pg = sPT[buf][(key >> pshift) - pg0];
         return pool + (int64_t)pg * P.page_stride + head_off + (int64_t)(key & pmask) * P.token_stride;
     };
-    const bool tile_layout = pshift == 4 && P.token_stride == D;   // see the single-wavefront kernel
+    const bool tile_layout = pshift >= 4 && P.token_stride == D;   // see the single-wavefront kernel
     auto load_kv = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
         const int kw = kb + 32 * wave;
         if (tile_layout && !(kb & 31) && kb + BK <= k1) {
-            const int pi = (kw >> 4) - pg0;
-            const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][pi]);
-            const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][pi + 1]);
-            const int64_t oa = (int64_t)pga * P.page_stride + head_off, ob = (int64_t)pgb * P.page_stride + head_off;
+            const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][(kw >> pshift) - pg0]);
+            const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][((kw + 16) >> pshift) - pg0]);
+            const int64_t oa = (int64_t)pga * P.page_stride + head_off + (int64_t)(kw & pmask) * D;
+            const int64_t ob = (int64_t)pgb * P.page_stride + head_off + (int64_t)((kw + 16) & pmask) * D;
             const char *ka = (const char*)(P.k_pool + oa), *kb_ = (const char*)(P.k_pool + ob);
             const char *va = (const char*)(P.v_pool + oa), *vb = (const char*)(P.v_pool + ob);
             constexpr int KPI = 64 / DCH;

@@ -278,7 +278,7 @@ def test_small_pages(ctx):
     assert_close(hip_attention(ctx, b), oracle_attention(b, 0.0), "page size 4")
 
 
-@pytest.mark.parametrize("page", [1, 2, 8, 32, 64])
+@pytest.mark.parametrize("page", [1, 2, 8, 32, 64, 128, 256])
 def test_other_page_sizes(ctx, page):
     cfg = make_cfg(f"page{page}", 5, 4, 2, 128, page=page)
     prefix = np.array([0, 37, 129, 500, 1031]); draft = np.array([2, 7, 1, 16, 4])
