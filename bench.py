@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--config", default="13b")
     ap.add_argument("--seed", type=int, default=3)
     ap.add_argument("--page-size", type=int, default=0, help="tokens per KV page (0 = the configuration's, 16)")
+    ap.add_argument("--kv-layout", default="hnd", choices=["hnd", "nhd"],
+                    help="memory order of a KV page: [head][token][dim] (default) or [token][head][dim]")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per attention launch (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--append", action="store_true",
@@ -126,6 +128,10 @@ def main():
                           "steps": args.warmup + args.steps}))
         return
     batch = si.make_verify_batch(cfg, args.seed, device=dev)
+    if args.kv_layout == "nhd":
+        # same logical [page][head][token][dim] tensors over [page][token][head][dim] memory: the library reads the strides
+        batch.k_pool = batch.k_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        batch.v_pool = batch.v_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
     t = batch.table
     ab = si.make_accept_batch(t.draft_len, cfg.vocab, cfg.logit_sigma, args.seed, device=dev)
     M = max(1, args.microbatches)
@@ -259,7 +265,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.n_req} requests, {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, "
                                f"head_dim {cfg.head_dim}, prefix {cfg.prefix_dist} {cfg.prefix_lo}-{cfg.prefix_hi}, "
-                               f"draft {cfg.draft_dist} {cfg.draft_lo}-{cfg.draft_hi}, page {cfg.page_size}, "
+                               f"draft {cfg.draft_dist} {cfg.draft_lo}-{cfg.draft_hi}, page {cfg.page_size}{' (token-major)' if args.kv_layout == 'nhd' else ''}, "
                                f"vocab {cfg.vocab}; " + ("KV append + " if args.append else "") + (f"{args.tree} draft trees, " if args.tree else "") +
                                "one attention layer + one rejection-sampling accept",
                    "decomposition": args.decomp, "microbatches": len(mbs), "streams": S, "plan_reuse": bool(args.reuse_plan),

@@ -69,9 +69,10 @@ typedef struct spin_req_table {
 
 /* Paged K/V cache.  k_pool / v_pool are device pointers to bf16 elements.  Element (page, kv
  * head, slot, c) sits at  page*page_stride + head*head_stride + slot*token_stride + c  (strides
- * in elements, the head dimension is contiguous, token_stride >= head_dim and a multiple of 8,
- * both pools 16-byte aligned).  The streaming kernels are tuned for
- * [n_pages][n_kv_heads][page_size][head_dim].  page_size must be a power of two. */
+ * in elements, the head dimension is contiguous, token_stride >= head_dim, a multiple of 8 and at most 2^24,
+ * both pools 16-byte aligned).  page_size must be a power of two; from 16 tokens up, head-major
+ * ([n_pages][n_kv_heads][page_size][head_dim]) and token-major ([n_pages][page_size][n_kv_heads][head_dim])
+ * pages stream at full speed, smaller pages take a slower addressing path. */
 typedef struct spin_kv_desc {
     const void* k_pool;
     const void* v_pool;

@@ -194,16 +194,19 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
         const int pg = sPT[buf][(key >> pshift) - pg0];
         return pool + (int64_t)pg * P.page_stride + head_off + (int64_t)(key & pmask) * P.token_stride;
     };
-    // With pages of 16 tokens or more whose rows are contiguous (token_stride == D), a full 32-key block
-    // that starts on a multiple of 32 is two runs of 16 contiguous rows (two pages, or two halves of one):
-    // two wavefront-uniform base addresses plus constant per-lane offsets, no per-lane address
-    // arithmetic.  Anything else takes the general path.
-    const bool tile_layout = pshift >= 4 && P.token_stride == D;
+    // With pages of 16 tokens or more, a full 32-key block that starts on a multiple of 32 is two runs
+    // of 16 rows at the token pitch (two pages, or two halves of one): two wavefront-uniform base
+    // addresses plus per-lane offsets that never change, no per-lane address arithmetic.  Anything
+    // else takes the general path.
+    const bool tile_layout = pshift >= 4;
+    const uint32_t ts2 = (uint32_t)P.token_stride * 2;                                  // token pitch in bytes
+    const uint32_t k_lane_off = (uint32_t)(lane / DCH) * ts2 + (uint32_t)(lane % DCH) * 16;   // K: a load covers 64/DCH rows
+    const uint32_t v_lane_off = (uint32_t)(g * 4) * ts2 + (uint32_t)(m16 % DCH) * 16;         // V: a lane's column chunk, keys 4g..
     auto page_bases = [&](const uint16_t* pool, int buf, int pg0, int64_t head_off, int kb, const char*& a, const char*& b) {
         const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][(kb >> pshift) - pg0]);
         const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][((kb + 16) >> pshift) - pg0]);
-        a = (const char*)(pool + (int64_t)pga * P.page_stride + head_off + (int64_t)(kb & pmask) * D);
-        b = (const char*)(pool + (int64_t)pgb * P.page_stride + head_off + (int64_t)((kb + 16) & pmask) * D);
+        a = (const char*)(pool + (int64_t)pga * P.page_stride + head_off + (int64_t)(kb & pmask) * P.token_stride);
+        b = (const char*)(pool + (int64_t)pgb * P.page_stride + head_off + (int64_t)((kb + 16) & pmask) * P.token_stride);
     };
     auto load_k = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
         if (tile_layout && !(kb & 31) && kb + 32 <= k1) {
@@ -213,7 +216,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 #pragma unroll
             for (int i = 0; i < KLOADS; ++i) {
                 const int key = i * KPI;             // first key of this instruction within the block
-                Kr[i] = stream_load(key < 16 ? a : b, (uint32_t)((key & 15) * D * 2 + lane * 16));
+                Kr[i] = stream_load((key < 16 ? a : b) + (int64_t)(key & 15) * ts2, k_lane_off);
             }
         } else {
 #pragma unroll
@@ -227,9 +230,8 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
         if (tile_layout && !(kb & 31) && kb + 32 <= k1) {
             const char *a, *b;
             page_bases(P.v_pool, buf, pg0, head_off, kb, a, b);
-            const uint32_t lo = (uint32_t)(g * 4 * D * 2 + (m16 % DCH) * 16);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) Vr[j] = stream_load(j < 4 ? a : b, lo + (uint32_t)((j & 3) * D * 2));
+            for (int j = 0; j < 8; ++j) Vr[j] = stream_load((j < 4 ? a : b) + (int64_t)(j & 3) * ts2, v_lane_off);
         } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -548,25 +550,27 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const int pg = sPT[buf][(key >> pshift) - pg0];
         return pool + (int64_t)pg * P.page_stride + head_off + (int64_t)(key & pmask) * P.token_stride;
     };
-    const bool tile_layout = pshift >= 4 && P.token_stride == D;   // see the single-wavefront kernel
+    const bool tile_layout = pshift >= 4;   // see the single-wavefront kernel
+    const uint32_t ts2 = (uint32_t)P.token_stride * 2;
+    const uint32_t k_lane_off = (uint32_t)(lane / DCH) * ts2 + (uint32_t)(lane % DCH) * 16;
+    const uint32_t v_lane_off = (uint32_t)(g * 4) * ts2 + (uint32_t)(m16 % DCH) * 16;
     auto load_kv = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
         const int kw = kb + 32 * wave;
         if (tile_layout && !(kb & 31) && kb + BK <= k1) {
             const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][(kw >> pshift) - pg0]);
             const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][((kw + 16) >> pshift) - pg0]);
-            const int64_t oa = (int64_t)pga * P.page_stride + head_off + (int64_t)(kw & pmask) * D;
-            const int64_t ob = (int64_t)pgb * P.page_stride + head_off + (int64_t)((kw + 16) & pmask) * D;
+            const int64_t oa = (int64_t)pga * P.page_stride + head_off + (int64_t)(kw & pmask) * P.token_stride;
+            const int64_t ob = (int64_t)pgb * P.page_stride + head_off + (int64_t)((kw + 16) & pmask) * P.token_stride;
             const char *ka = (const char*)(P.k_pool + oa), *kb_ = (const char*)(P.k_pool + ob);
             const char *va = (const char*)(P.v_pool + oa), *vb = (const char*)(P.v_pool + ob);
             constexpr int KPI = 64 / DCH;
 #pragma unroll
             for (int i = 0; i < KLOADS; ++i) {
                 const int key = i * KPI;
-                Kr[i] = stream_load(key < 16 ? ka : kb_, (uint32_t)((key & 15) * D * 2 + lane * 16));
+                Kr[i] = stream_load((key < 16 ? ka : kb_) + (int64_t)(key & 15) * ts2, k_lane_off);
             }
-            const uint32_t lo = (uint32_t)(g * 4 * D * 2 + (m16 % DCH) * 16);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) Vr[j] = stream_load(j < 4 ? va : vb, lo + (uint32_t)((j & 3) * D * 2));
+            for (int j = 0; j < 8; ++j) Vr[j] = stream_load((j < 4 ? va : vb) + (int64_t)(j & 3) * ts2, v_lane_off);
         } else {
 #pragma unroll
             for (int i = 0; i < KLOADS; ++i) {

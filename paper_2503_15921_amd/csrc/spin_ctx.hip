@@ -265,6 +265,8 @@ int check_kv_desc(spin_ctx* ctx, const spin_kv_desc* kv) {
     if (kv->n_pages < 0 || kv->token_stride < kv->head_dim || kv->token_stride % 8 || kv->page_stride % 8 ||
         kv->head_stride % 8 || kv->page_stride < 0 || kv->head_stride < 0)
         return fail(ctx, SPIN_EINVAL, "bad K/V strides (must be non-negative multiples of 8 elements)");
+    // the kernels keep per-lane byte offsets of up to 15 token pitches in 32 bits
+    if (kv->token_stride > (1 << 24)) return fail(ctx, SPIN_EUNSUPPORTED, "token_stride above 2^24 elements");
     return SPIN_OK;
 }
 

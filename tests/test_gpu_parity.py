@@ -251,9 +251,11 @@ def test_repeat_runs_are_deterministic(ctx):
         assert torch.equal(hip_attention(ctx, b).view(torch.int16), a.view(torch.int16))
 
 
-def test_other_cache_layout_via_strides(ctx):
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (16, 2, 128), (8, 2, 64), (16, 2, 64)])
+def test_other_cache_layout_via_strides(ctx, hq, hkv, d):
     # pool stored as [page][slot][head][dim] with a padded token pitch: same result through strides
-    cfg = make_cfg("layout", 4, 4, 2, 128)
+    # (groups of 2, 4 and 8 query heads: the single-wavefront and the grouped-query kernel)
+    cfg = make_cfg("layout", 4, hq, hkv, d)
     prefix = np.array([40, 333, 5, 800]); draft = np.array([5, 2, 8, 3])
     b = si.make_verify_batch(cfg, 19, device="cuda", prefix_len=prefix, draft_len=draft)
     want = hip_attention(ctx, b)
@@ -269,6 +271,7 @@ def test_other_cache_layout_via_strides(ctx):
     ctx.verify_attn(tab, kv, vv, b.q, out, cfg.n_q_heads)
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int16), want.view(torch.int16))
+    assert_close(out, oracle_attention(b, 0.0), "token-major cache layout")
 
 
 def test_small_pages(ctx):
