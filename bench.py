@@ -37,7 +37,7 @@ def cpu_baseline(cfg, batch, ab, budget_s=20.0):
     rng = np.random.default_rng(0)
     n_tok = (t.prefix_len.astype(np.int64) + t.draft_len)
     total_cells = float((n_tok * cfg.n_q_heads).sum())
-    kb, vb, qb = si.bf16_bits(batch.k_pool), si.bf16_bits(batch.v_pool), si.bf16_bits(batch.q)
+    kb, vb, qb = si.host_elems(batch.k_pool), si.host_elems(batch.v_pool), si.host_elems(batch.q)
     scale = 1.0 / math.sqrt(cfg.head_dim)
     done_cells, t_attn, n_pairs = 0.0, 0.0, 0
     while t_attn < budget_s * 0.6 and n_pairs < t.n_req * cfg.n_q_heads:
@@ -79,6 +79,7 @@ def main():
     ap.add_argument("--config", default="13b")
     ap.add_argument("--seed", type=int, default=3)
     ap.add_argument("--page-size", type=int, default=0, help="tokens per KV page (0 = the configuration's, 16)")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"], help="element type of Q, K, V and the output")
     ap.add_argument("--kv-layout", default="hnd", choices=["hnd", "nhd"],
                     help="memory order of a KV page: [head][token][dim] (default) or [token][head][dim]")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per attention launch (0 = automatic)")
@@ -127,7 +128,8 @@ def main():
         print(json.dumps({"calib_copy_bytes_read_per_step": 1 << 30, "calib_copy_bytes_written_per_step": 1 << 30,
                           "steps": args.warmup + args.steps}))
         return
-    batch = si.make_verify_batch(cfg, args.seed, device=dev)
+    elem = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+    batch = si.make_verify_batch(cfg, args.seed, device=dev, dtype=elem)
     if args.kv_layout == "nhd":
         # same logical [page][head][token][dim] tensors over [page][token][head][dim] memory: the library reads the strides
         batch.k_pool = batch.k_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
@@ -148,8 +150,8 @@ def main():
     if args.append:
         g = torch.Generator(device="cpu").manual_seed(args.seed)
         shape = (t.n_rows, cfg.n_kv_heads, cfg.head_dim)
-        k_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
-        v_new = torch.randn(shape, generator=g).to(torch.bfloat16).to(dev)
+        k_new = torch.randn(shape, generator=g).to(elem).to(dev)
+        v_new = torch.randn(shape, generator=g).to(elem).to(dev)
 
     parents, masks = si.random_trees(t.draft_len, np.random.default_rng(args.seed), args.tree) if args.tree else (None, None)
     path = torch.empty(t.n_rows, dtype=torch.int32, device=dev)
@@ -262,7 +264,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "host_ms_per_step": host * 1e3 / 10, "steps_with_kernel_timing": timed_steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.n_req} requests, {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, "
                                f"head_dim {cfg.head_dim}, prefix {cfg.prefix_dist} {cfg.prefix_lo}-{cfg.prefix_hi}, "
                                f"draft {cfg.draft_dist} {cfg.draft_lo}-{cfg.draft_hi}, page {cfg.page_size}{' (token-major)' if args.kv_layout == 'nhd' else ''}, "

@@ -46,7 +46,8 @@ extern "C" {
 #define SPIN_EUNSUPPORTED (-4) /* a shape or type this build has no kernel for                  */
 #define SPIN_EHIP (-5)         /* a HIP runtime call failed; text via spin_last_error           */
 
-#define SPIN_DTYPE_BF16 1
+#define SPIN_DTYPE_BF16 1   /* bfloat16 */
+#define SPIN_DTYPE_F16 2    /* IEEE binary16 */
 
 typedef struct spin_ctx spin_ctx;
 
@@ -67,7 +68,7 @@ typedef struct spin_req_table {
     const int32_t* page_table;
 } spin_req_table;
 
-/* Paged K/V cache.  k_pool / v_pool are device pointers to bf16 elements.  Element (page, kv
+/* Paged K/V cache.  k_pool / v_pool are device pointers to 16-bit elements of type `dtype`.  Element (page, kv
  * head, slot, c) sits at  page*page_stride + head*head_stride + slot*token_stride + c  (strides
  * in elements, the head dimension is contiguous, token_stride >= head_dim, a multiple of 8 and at most 2^24,
  * both pools 16-byte aligned).  page_size must be a power of two; from 16 tokens up, head-major
@@ -83,7 +84,7 @@ typedef struct spin_kv_desc {
     int64_t page_stride;
     int64_t head_stride;
     int64_t token_stride;
-    int32_t dtype;             /* SPIN_DTYPE_BF16 */
+    int32_t dtype;             /* SPIN_DTYPE_BF16 or SPIN_DTYPE_F16: the type of K, V, Q and the output */
 } spin_kv_desc;
 
 /* A sub-request: a rectangle of its parent's (draft row x key) score matrix.  It refers to the
@@ -187,9 +188,10 @@ int spin_schedule(const spin_req_table* table, const spin_subreq* subs, int32_t 
 /* ---- the verification step ---------------------------------------------------------------- */
 
 /* Sec. II-A1 Eq. (2) with the normalisation of Sec. V-A Eq. (13).
- *   q_dev  device, bf16 [R][n_q_heads][head_dim], R = q_offset[n_req]   (read)
- *   o_dev  device, bf16 [R][n_q_heads][head_dim]                         (every row written once)
- *          both 16-byte aligned
+ *   q_dev  device, kv->dtype [R][n_q_heads][head_dim], R = q_offset[n_req]   (read)
+ *   o_dev  device, kv->dtype [R][n_q_heads][head_dim]                         (every row written once)
+ *          both 16-byte aligned.  Products accumulate in fp32; the softmax weights are rounded
+ *          to kv->dtype before they multiply V, the result rows once at the end.
  *   subs   host, n_sub sub-requests that tile the batch exactly once, or NULL for none
  *   softmax_scale  multiplies Q.K before exp; <= 0 selects 1/sqrt(head_dim); 1 is the literal
  *                  formula of Eq. (2)
@@ -217,7 +219,7 @@ int spin_verify_attn_tree(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_
                           void* hip_stream);
 
 /* The step just before the attention: put the draft tokens' K and V rows into the paged cache, so
- * that the caller need not run a scatter of its own.  Row r of k_new_dev / v_new_dev (device, bf16
+ * that the caller need not run a scatter of its own.  Row r of k_new_dev / v_new_dev (device, kv->dtype
  * [R][n_kv_heads][head_dim], packed like Q) is draft token t = r - q_offset[i] of its request i and goes
  * to position p_i + t: page page_table[pt_offset[i] + (p_i+t)/page_size], slot (p_i+t) % page_size.
  * kv->k_pool / kv->v_pool are WRITTEN by this call (and only by this call).  Rejected draft tokens

@@ -17,6 +17,7 @@ OK, EINVAL, ETABLE, ENOSPC, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
 DECOMP_NONE, DECOMP_Q_SPLIT, DECOMP_KV_SPLIT, DECOMP_KV_SEARCH = 0, 1, 2, 3
 ACCEPT_GREEDY, ACCEPT_REJECTION = 0, 1
 DTYPE_BF16 = 1
+DTYPE_F16 = 2
 
 SUBREQ_DTYPE = np.dtype([("parent", "<i4"), ("q_begin", "<i4"), ("q_len", "<i4"),
                          ("kv_begin", "<i4"), ("kv_len", "<i4")])
@@ -218,6 +219,15 @@ def schedule(prefix_len, draft_len, subs, page_size: int, group: int, n_kv_heads
     return out[: cnt.value].copy()
 
 
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    if t.dtype == torch.float16:
+        return DTYPE_F16
+    raise TypeError(f"K/V must be torch.bfloat16 or torch.float16, not {t.dtype}")
+
+
 # ----------------------------------------------------------------------------- GPU context
 class SpinContext:
     """Owns a spin_ctx.  `auto_reserve` lets the binding grow the workspace when a call reports
@@ -306,9 +316,10 @@ class SpinContext:
     def verify_attn(self, table: _Table, k_pool, v_pool, q, out, n_q_heads: int, subs=None,
                     softmax_scale: float = 0.0, page_size: Optional[int] = None, stream=None,
                     strides=None, tree_mask=None):
-        """spin_verify_attn, or spin_verify_attn_tree when tree_mask (host uint64 [R]) is given.  k_pool/v_pool: torch bf16 [n_pages][n_kv_heads][page_size][head_dim]
+        """spin_verify_attn, or spin_verify_attn_tree when tree_mask (host uint64 [R]) is given.  k_pool/v_pool: torch bf16 or fp16 [n_pages][n_kv_heads][page_size][head_dim]
         (or any layout with `strides` = (page, head, token) in elements and page_size given);
-        q/out: torch bf16 [R][n_q_heads][head_dim]."""
+        q/out: torch tensors of the same type, [R][n_q_heads][head_dim]."""
+        assert q.dtype == k_pool.dtype == v_pool.dtype == out.dtype
         if strides is None:
             n_pages, n_kv, psz, d = k_pool.shape
             ps, hs, ts, ds = k_pool.stride()
@@ -318,7 +329,7 @@ class SpinContext:
             ps, hs, ts = strides
         if page_size is not None:
             psz = page_size
-        desc = KvDesc(k_pool.data_ptr(), v_pool.data_ptr(), n_pages, psz, n_kv, d, ps, hs, ts, DTYPE_BF16)
+        desc = KvDesc(k_pool.data_ptr(), v_pool.data_ptr(), n_pages, psz, n_kv, d, ps, hs, ts, _dtype_code(k_pool))
         sp, ns, keep = _subs_arg(subs)
         st = self._stream(stream)
         if tree_mask is not None:
@@ -333,11 +344,12 @@ class SpinContext:
                                                        n_q_heads, softmax_scale, st))
 
     def append_kv(self, table: _Table, k_pool, v_pool, k_new, v_new, stream=None):
-        """spin_append_kv: scatter the draft tokens' K/V rows (bf16 [R][n_kv_heads][head_dim]) into the pools."""
+        """spin_append_kv: scatter the draft tokens' K/V rows ([R][n_kv_heads][head_dim], the pools' type) into the pools."""
+        assert k_new.dtype == v_new.dtype == k_pool.dtype == v_pool.dtype
         n_pages, n_kv, psz, d = k_pool.shape
         ps, hs, ts, ds = k_pool.stride()
         assert ds == 1 and tuple(v_pool.stride()) == tuple(k_pool.stride())
-        desc = KvDesc(k_pool.data_ptr(), v_pool.data_ptr(), n_pages, psz, n_kv, d, ps, hs, ts, DTYPE_BF16)
+        desc = KvDesc(k_pool.data_ptr(), v_pool.data_ptr(), n_pages, psz, n_kv, d, ps, hs, ts, _dtype_code(k_pool))
         st = self._stream(stream)
         self._retry(lambda: self._lib.spin_append_kv(self._h, C.byref(desc), C.byref(table.struct),
                                                      C.c_void_p(k_new.data_ptr()), C.c_void_p(v_new.data_ptr()), st))

@@ -45,6 +45,8 @@ namespace spin {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
@@ -53,10 +55,25 @@ constexpr float kSlack = 6.0f;        // log2 of how far a score may exceed the 
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    bf16x2 v = {(__bf16)lo, (__bf16)hi};   // round to nearest even
-    return __builtin_bit_cast(uint32_t, v);
-}
+// The two 16-bit element types of Q, K, V and the output.  The kernels move elements as bit patterns
+// (loads, the LDS re-shaping, the 8x8 transpose of V); only the matrix-core instruction and the
+// rounding of fp32 values (P before P.V, the final rows) depend on the type.
+struct Bf16 {
+    typedef bf16x8 vec8;
+    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) {
+        bf16x2 v = {(__bf16)lo, (__bf16)hi};   // round to nearest even
+        return __builtin_bit_cast(uint32_t, v);
+    }
+};
+struct F16 {
+    typedef f16x8 vec8;
+    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+    static __device__ __forceinline__ uint32_t pack(float lo, float hi) {
+        f16x2 v = {(_Float16)lo, (_Float16)hi};   // round to nearest even
+        return __builtin_bit_cast(uint32_t, v);
+    }
+};
 
 // K/V bytes are used once: a non-temporal load keeps them from displacing anything in the caches
 // and streams measurably faster from HBM on this part.
@@ -68,8 +85,9 @@ __device__ __forceinline__ u32x4 stream_load(const char* base, uint32_t byte_off
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + byte_off));
 }
 
-template <int D, int NT, bool TREE>
+template <int D, int NT, bool TREE, class E>
 __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
+    typedef typename E::vec8 vec8;
     constexpr int DCH = D / 8;      // 16-byte chunks per key row
     constexpr int KCALLS = D / 32;  // MFMA calls (32 head dims each) per 16-key score tile
     constexpr int KLOADS = DCH / 2; // 16-byte loads per lane for 32 keys of K
@@ -170,7 +188,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     };
 
     // query operands of a piece (zeros for rows beyond its draft rows)
-    bf16x8 qf[NT][KCALLS];
+    vec8 qf[NT][KCALLS];
     auto load_q = [&](const Piece& pc) {
         const int kvh = pc.head_flags & kPieceHeadMask;
 #pragma unroll
@@ -182,7 +200,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 #pragma unroll
             for (int c = 0; c < KCALLS; ++c) {
                 u32x4 v = valid ? *(const u32x4*)(qp + c * 32) : u32x4{0, 0, 0, 0};
-                qf[nt][c] = __builtin_bit_cast(bf16x8, v);
+                qf[nt][c] = __builtin_bit_cast(vec8, v);
             }
         }
     };
@@ -340,17 +358,17 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
             for (int c = 0; c < KCALLS; ++c)      // the two tiles alternate, so consecutive MFMAs are independent
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sK[(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
+                    const vec8 a = __builtin_bit_cast(vec8, *(const u32x4*)&sK[(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
-                        S[t][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[nt][c], S[t][nt], 0, 0, 0);
+                        S[t][nt] = E::mfma(a, qf[nt][c], S[t][nt]);
                 }
             // the queries are no longer needed after the last block: fetch the next piece's if they differ
             if (last && new_q) load_q(p1);
 
             // ---- online softmax; lane (row, g) holds keys kb + t*16 + g*4 + r
             const bool full = kb + 32 <= full_end;
-            bf16x8 Pb[NT];
+            vec8 Pb[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
                 float s[8];
@@ -379,8 +397,8 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
                 l_run[nt] = l_run[nt] * alpha + sum;
 #pragma unroll
                 for (int jd = 0; jd < 8; ++jd) O[nt][jd] *= alpha;
-                u32x4 pk = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-                Pb[nt] = __builtin_bit_cast(bf16x8, pk);
+                u32x4 pk = {E::pack(p[0], p[1]), E::pack(p[2], p[3]), E::pack(p[4], p[5]), E::pack(p[6], p[7])};
+                Pb[nt] = __builtin_bit_cast(vec8, pk);
             }
 
             // ---- V: 8x8 transpose of 16-bit values inside each lane, then O^T += V^T P^T
@@ -399,10 +417,10 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
                 if (hh == 1) load_v(s_buf, s_pg0, s_k1, s_head, s_kb);
 #pragma unroll
                 for (int j4 = 0; j4 < 4; ++j4) {
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, Vt[j4]);
+                    const vec8 a = __builtin_bit_cast(vec8, Vt[j4]);
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
-                        O[nt][hh * 4 + j4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, Pb[nt], O[nt][hh * 4 + j4], 0, 0, 0);
+                        O[nt][hh * 4 + j4] = E::mfma(a, Pb[nt], O[nt][hh * 4 + j4]);
                 }
             }
         }
@@ -423,8 +441,8 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
                     const float inv = 1.0f / l;
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        dst[r * 64] = u32x4{pack_bf16(O[nt][0][r] * inv, O[nt][1][r] * inv), pack_bf16(O[nt][2][r] * inv, O[nt][3][r] * inv),
-                                            pack_bf16(O[nt][4][r] * inv, O[nt][5][r] * inv), pack_bf16(O[nt][6][r] * inv, O[nt][7][r] * inv)};
+                        dst[r * 64] = u32x4{E::pack(O[nt][0][r] * inv, O[nt][1][r] * inv), E::pack(O[nt][2][r] * inv, O[nt][3][r] * inv),
+                                            E::pack(O[nt][4][r] * inv, O[nt][5][r] * inv), E::pack(O[nt][6][r] * inv, O[nt][7][r] * inv)};
                 } else {
 #pragma unroll
                     for (int jd = 0; jd < 8; ++jd) dst[jd * 64] = __builtin_bit_cast(u32x4, O[nt][jd]);
@@ -474,8 +492,9 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 // wavefront reads the sub-blocks it needs.  Shares, pieces, the look-ahead across pieces and the
 // queue are the same, with the workgroup in the wavefront's place; results are stored as they
 // finish (a workgroup meets few ends of a (request, KV head) per share).
-template <int D, int NW, bool TREE>
+template <int D, int NW, bool TREE, class E>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void verify_attn_group_kernel(AttnParams P) {
+    typedef typename E::vec8 vec8;
     constexpr int DCH = D / 8;
     constexpr int KCALLS = D / 32;
     constexpr int KLOADS = DCH / 2;
@@ -529,7 +548,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
             for (int i = 0; i < PTR; ++i) sPT[buf][lane + 64 * i] = pr[i];
         }
     };
-    bf16x8 qf[KCALLS];
+    vec8 qf[KCALLS];
     auto load_q = [&](const Piece& pc) {
         const int kvh = pc.head_flags & kPieceHeadMask;
         const int nn = (wave % tiles_eff(pc)) * 16 + m16;
@@ -539,7 +558,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
         for (int c = 0; c < KCALLS; ++c) {
             u32x4 v = valid ? *(const u32x4*)(qp + c * 32) : u32x4{0, 0, 0, 0};
-            qf[c] = __builtin_bit_cast(bf16x8, v);
+            qf[c] = __builtin_bit_cast(vec8, v);
         }
     };
     // this wavefront's 32 keys (kb + 32*wave ...) of the block starting at kb: K as 1 KiB-contiguous
@@ -676,8 +695,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 for (int c = 0; c < KCALLS; ++c)
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
-                        const bf16x8 a = __builtin_bit_cast(bf16x8, *(const u32x4*)&sK[sb][(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
-                        S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[c], S[t], 0, 0, 0);
+                        const vec8 a = __builtin_bit_cast(vec8, *(const u32x4*)&sK[sb][(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
+                        S[t] = E::mfma(a, qf[c], S[t]);
                     }
                 float s[8];
 #pragma unroll
@@ -711,11 +730,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                     sum += p[e];
                 }
                 l_run += sum;
-                const u32x4 pk = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-                const bf16x8 Pb = __builtin_bit_cast(bf16x8, pk);
+                const u32x4 pk = {E::pack(p[0], p[1]), E::pack(p[2], p[3]), E::pack(p[4], p[5]), E::pack(p[6], p[7])};
+                const vec8 Pb = __builtin_bit_cast(vec8, pk);
 #pragma unroll
                 for (int jd = 0; jd < 8; ++jd)
-                    O[jd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, sVt[sb][jd][lane]), Pb, O[jd], 0, 0, 0);
+                    O[jd] = E::mfma(__builtin_bit_cast(vec8, sVt[sb][jd][lane]), Pb, O[jd]);
             }
             // the queries are no longer needed after the last block: fetch the next piece's if they differ
             if (last && new_q) load_q(p1);
@@ -761,8 +780,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                     if (g * 4 < DCH) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            u32x4 w = {pack_bf16(O[0][r] * inv, O[1][r] * inv), pack_bf16(O[2][r] * inv, O[3][r] * inv),
-                                       pack_bf16(O[4][r] * inv, O[5][r] * inv), pack_bf16(O[6][r] * inv, O[7][r] * inv)};
+                            u32x4 w = {E::pack(O[0][r] * inv, O[1][r] * inv), E::pack(O[2][r] * inv, O[3][r] * inv),
+                                       E::pack(O[4][r] * inv, O[5][r] * inv), E::pack(O[6][r] * inv, O[7][r] * inv)};
                             *(u32x4*)(op + r * 8) = w;
                         }
                     }
@@ -807,7 +826,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // written directly have no partial result and are left alone.
 constexpr int kJoinWaves = 4;
 
-template <int D>
+template <int D, class E>
 __global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinParams P) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int req = P.tasks[2 * blockIdx.x], kvh = P.tasks[2 * blockIdx.x + 1];
@@ -849,7 +868,7 @@ __global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinPara
             const float inv = 1.0f / den;
             const int h = kvh * G + hg;
             uint32_t* op = reinterpret_cast<uint32_t*>(P.o + ((int64_t)r * P.n_q_heads + h) * D + chunk * 8 + 2 * jp);
-            *op = pack_bf16(n0 * inv, n1 * inv);
+            *op = E::pack(n0 * inv, n1 * inv);
         }
     }
 }
@@ -879,15 +898,15 @@ hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int D, bool TREE>
+template <int D, bool TREE, class E>
 static const void* attn_kernel_ptr(int cls) {
-    return cls == 0 ? (const void*)verify_attn_kernel<D, 1, TREE>
-         : cls == 1 ? (const void*)verify_attn_kernel<D, 2, TREE> : (const void*)verify_attn_group_kernel<D, 4, TREE>;
+    return cls == 0 ? (const void*)verify_attn_kernel<D, 1, TREE, E>
+         : cls == 1 ? (const void*)verify_attn_kernel<D, 2, TREE, E> : (const void*)verify_attn_group_kernel<D, 4, TREE, E>;
 }
 
 hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
-    // (the tree-mask variants differ by a few registers only and are launched with the same counts)
-    const void* fn = head_dim == 128 ? attn_kernel_ptr<128, false>(cls) : attn_kernel_ptr<64, false>(cls);
+    // (the tree-mask and fp16 variants differ by a few registers at most and are launched with the same counts)
+    const void* fn = head_dim == 128 ? attn_kernel_ptr<128, false, Bf16>(cls) : attn_kernel_ptr<64, false, Bf16>(cls);
     int per_cu = 0, dev = 0;
     hipDeviceProp_t prop;
     hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, cls == 2 ? 256 : 64, 0);
@@ -902,7 +921,7 @@ hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
     return hipSuccess;
 }
 
-template <int D>
+template <int D, class E>
 static hipError_t launch_attn_d(const AttnParams& base, const Piece* const pieces_dev[3],
                                 const int32_t* const wave_begin_dev[3], const int32_t n_waves[3],
                                 const int32_t n_queued[3], int32_t* queues_dev, const JoinParams& jp,
@@ -916,7 +935,7 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         p.n_queued = n_queued[cls];
         dim3 grid((unsigned)n_waves[cls]);
         void* args[] = {&p};
-        const void* fn = p.tree_rows ? attn_kernel_ptr<D, true>(cls) : attn_kernel_ptr<D, false>(cls);
+        const void* fn = p.tree_rows ? attn_kernel_ptr<D, true, E>(cls) : attn_kernel_ptr<D, false, E>(cls);
         hipError_t e = hipLaunchKernel(fn, grid, dim3(cls == 2 ? 256 : 64), args, 0, stream);
         if (e != hipSuccess) return e;
     }
@@ -926,20 +945,22 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
     }
     if (jp.n_tasks > 0) {
         const int pair_groups = (jp.max_pairs + kJoinWaves - 1) / kJoinWaves;
-        hipLaunchKernelGGL((join_partials_kernel<D>), dim3(jp.n_tasks, pair_groups), dim3(64 * kJoinWaves), 0, stream, jp);
+        hipLaunchKernelGGL((join_partials_kernel<D, E>), dim3(jp.n_tasks, pair_groups), dim3(64 * kJoinWaves), 0, stream, jp);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-hipError_t launch_attn(int head_dim, const AttnParams& base, const Piece* const pieces_dev[3],
+hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Piece* const pieces_dev[3],
                        const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
                        int32_t* queues_dev, const JoinParams& jp, hipStream_t stream, hipEvent_t ev_mid) {
     if (head_dim == 128)
-        return launch_attn_d<128>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid);
+        return f16 ? launch_attn_d<128, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid)
+                   : launch_attn_d<128, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid);
     if (head_dim == 64)
-        return launch_attn_d<64>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid);
+        return f16 ? launch_attn_d<64, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid)
+                   : launch_attn_d<64, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid);
     return hipErrorInvalidValue;
 }
 

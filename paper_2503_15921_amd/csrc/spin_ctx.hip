@@ -257,7 +257,7 @@ namespace {
 
 // What every call that takes a K/V descriptor demands of it (the attention kernels further restrict head_dim).
 int check_kv_desc(spin_ctx* ctx, const spin_kv_desc* kv) {
-    if (kv->dtype != SPIN_DTYPE_BF16) return fail(ctx, SPIN_EUNSUPPORTED, "only bf16 K/V is supported");
+    if (kv->dtype != SPIN_DTYPE_BF16 && kv->dtype != SPIN_DTYPE_F16) return fail(ctx, SPIN_EUNSUPPORTED, "K/V must be bf16 or fp16");
     if (kv->head_dim < 8 || kv->head_dim % 8) return fail(ctx, SPIN_EUNSUPPORTED, "head_dim must be a multiple of 8");
     if (kv->page_size < 1 || (kv->page_size & (kv->page_size - 1)))
         return fail(ctx, SPIN_EUNSUPPORTED, "page_size must be a power of two");
@@ -506,7 +506,7 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     jp.max_pairs = sp.max_pairs;
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used, ctx->prof_attn_seen);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    e = spin::launch_attn(kv->head_dim, ap, pieces_dev, waves_dev, sp.n_waves_launch, sp.n_queued,
+    e = spin::launch_attn(kv->head_dim, kv->dtype == SPIN_DTYPE_F16, ap, pieces_dev, waves_dev, sp.n_waves_launch, sp.n_queued,
                           (int32_t*)(blob + sp.off_queues), jp, stream, pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
     if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");

@@ -50,7 +50,7 @@ hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves);
 
 // n_waves[c] wavefronts stream the pieces of class c; ev_mid (may be null) is recorded between the
 // attention kernels and the join kernel.
-hipError_t launch_attn(int head_dim, const AttnParams& base, const Piece* const pieces_dev[3],
+hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Piece* const pieces_dev[3],
                        const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
                        int32_t* queues_dev, const JoinParams& jp, hipStream_t stream, hipEvent_t ev_mid);
 

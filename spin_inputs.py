@@ -152,21 +152,21 @@ def make_table(prefix_len, draft_len, page_size: int, rng: Optional[np.random.Ge
     return RequestTable(prefix_len, draft_len, q_offset, pt_offset, page_table, page_size, pool)
 
 
-def _randn_bf16(shape, gen: torch.Generator, device) -> torch.Tensor:
-    # Drawn in fp32 and rounded to bf16 (round-to-nearest-even) exactly once;
+def _randn_16(shape, gen: torch.Generator, device, dtype=torch.bfloat16) -> torch.Tensor:
+    # Drawn in fp32 and rounded to the 16-bit type (round-to-nearest-even) exactly once;
     # everybody downstream reads these bits.  Done in slabs to bound the fp32 temporary.
-    out = torch.empty(shape, dtype=torch.bfloat16, device=device)
+    out = torch.empty(shape, dtype=dtype, device=device)
     flat = out.view(-1)
     step = 1 << 27
     for s in range(0, flat.numel(), step):
         e = min(flat.numel(), s + step)
-        flat[s:e] = torch.randn(e - s, generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
+        flat[s:e] = torch.randn(e - s, generator=gen, device=device, dtype=torch.float32).to(dtype)
     return out
 
 
 def make_verify_batch(cfg: VerifyConfig, seed: int, device="cpu", prefix_len=None, draft_len=None,
-                      poison_unused: bool = False, shuffle_pages: bool = True) -> VerifyBatch:
-    """One synthetic verification batch.  `poison_unused` writes NaN into every K/V slot no
+                      poison_unused: bool = False, shuffle_pages: bool = True, dtype=torch.bfloat16) -> VerifyBatch:
+    """One synthetic verification batch (Q, K, V standard normal, rounded once to `dtype`: bf16 or fp16).  `poison_unused` writes NaN into every K/V slot no
     request owns (unused pool pages and the tail of each request's last page)."""
     rng = np.random.default_rng(seed)
     if prefix_len is None or draft_len is None:
@@ -177,10 +177,10 @@ def make_verify_batch(cfg: VerifyConfig, seed: int, device="cpu", prefix_len=Non
     gen = torch.Generator(device=device)
     gen.manual_seed(1000003 * seed + 17)
     R = table.n_rows
-    q = _randn_bf16((R, cfg.n_q_heads, cfg.head_dim), gen, device)
+    q = _randn_16((R, cfg.n_q_heads, cfg.head_dim), gen, device, dtype)
     shape = (table.n_pages, cfg.n_kv_heads, cfg.page_size, cfg.head_dim)
-    k_pool = _randn_bf16(shape, gen, device)
-    v_pool = _randn_bf16(shape, gen, device)
+    k_pool = _randn_16(shape, gen, device, dtype)
+    v_pool = _randn_16(shape, gen, device, dtype)
     if poison_unused:
         owned = torch.zeros((table.n_pages, cfg.page_size), dtype=torch.bool)
         n_tok = table.prefix_len.astype(np.int64) + table.draft_len
@@ -263,6 +263,15 @@ def bf16_bits(t: torch.Tensor) -> np.ndarray:
     """The raw 16-bit patterns of a bf16 tensor as a uint16 numpy array (host copy)."""
     assert t.dtype == torch.bfloat16
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def host_elems(t: torch.Tensor) -> np.ndarray:
+    """A 16-bit tensor on the host in the form the oracle reads: bf16 as raw uint16 bit patterns, fp16
+    as a numpy float16 array (both widen to float64 exactly)."""
+    if t.dtype == torch.bfloat16:
+        return bf16_bits(t)
+    assert t.dtype == torch.float16
+    return t.detach().cpu().contiguous().numpy()
 
 
 def algorithmic_kv_bytes(table: RequestTable, n_kv_heads: int, head_dim: int) -> int:

@@ -48,7 +48,7 @@ def oracle_attention(batch, scale, requests=None, heads=None):
     if scale <= 0:
         scale = 1.0 / math.sqrt(cfg.head_dim)
     return orc.verify_attention(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, cfg.page_size,
-                                si.bf16_bits(batch.q), si.bf16_bits(batch.k_pool), si.bf16_bits(batch.v_pool),
+                                si.host_elems(batch.q), si.host_elems(batch.k_pool), si.host_elems(batch.v_pool),
                                 cfg.n_q_heads, cfg.n_kv_heads, scale, requests=requests, heads=heads)
 
 
@@ -365,7 +365,7 @@ def oracle_tree_attention(batch, masks, scale=0.0, requests=None, heads=None):
     if scale <= 0:
         scale = 1.0 / math.sqrt(cfg.head_dim)
     return orc.verify_attention(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, cfg.page_size,
-                                si.bf16_bits(batch.q), si.bf16_bits(batch.k_pool), si.bf16_bits(batch.v_pool),
+                                si.host_elems(batch.q), si.host_elems(batch.k_pool), si.host_elems(batch.v_pool),
                                 cfg.n_q_heads, cfg.n_kv_heads, scale, requests=requests, heads=heads, tree_mask=masks)
 
 
@@ -441,6 +441,83 @@ def test_tree_mask_errors(ctx):
     with pytest.raises(spin.SpinError) as ei:
         hip_tree_attention(ctx, b, np.full(65, 1, dtype=np.uint64))
     assert ei.value.code == spin.ETABLE
+
+
+# ------------------------------------------------------------------------------ fp16 elements
+@pytest.mark.parametrize("hq,hkv,d", [(4, 4, 128), (8, 2, 128), (16, 2, 128), (2, 2, 64), (16, 2, 64)])
+def test_fp16_attention(ctx, hq, hkv, d):
+    """Q, K, V and the output in IEEE half precision: all three kernel widths, whole and cut."""
+    cfg = make_cfg("f16", 6, hq, hkv, d)
+    prefix = np.array([0, 17, 300, 1500, 64, 2049]); draft = np.array([1, 8, 3, 5, 8, 2])
+    b = si.make_verify_batch(cfg, 77, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True,
+                             dtype=torch.float16)
+    want = oracle_attention(b, 0.0)
+    whole = hip_attention(ctx, b)
+    assert whole.dtype == torch.float16
+    assert_close(whole, want, f"fp16 {hq}/{hkv}/{d}")
+    subs = orc.decompose_kv_split(prefix, draft, 100)
+    assert_close(hip_attention(ctx, b, subs=subs, waves=7), want, f"fp16 {hq}/{hkv}/{d}, kv-split, 7 shares")
+    assert_close(hip_attention(ctx, b, subs=orc.decompose_q_split(prefix, draft, 2)), want, f"fp16 {hq}/{hkv}/{d}, q-split")
+
+
+def test_fp16_is_closer_than_bf16(ctx):
+    """The same draws through both element types, each against the oracle on its own rounded inputs: the
+    half-precision path carries three more mantissa bits in P and in the output, so its error is the smaller."""
+    cfg = make_cfg("f16-vs-bf16", 4, 8, 2, 128)
+    prefix = np.array([100, 700, 1500, 33]); draft = np.array([4, 8, 2, 6])
+    b = si.make_verify_batch(cfg, 78, device="cuda", prefix_len=prefix, draft_len=draft)
+    h = si.make_verify_batch(cfg, 78, device="cuda", prefix_len=prefix, draft_len=draft, dtype=torch.float16)
+    _, rms_b = assert_close(hip_attention(ctx, b), oracle_attention(b, 0.0), "bf16")
+    _, rms_h = assert_close(hip_attention(ctx, h), oracle_attention(h, 0.0), "fp16")
+    assert rms_h < 0.5 * rms_b, (rms_h, rms_b)
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (16, 2, 64)])
+def test_fp16_tree_and_append(ctx, hq, hkv, d):
+    cfg = make_cfg("f16-tree", 5, hq, hkv, d)
+    prefix = np.array([0, 15, 333, 1500, 47]); draft = np.array([5, 8, 1, 8, 7])
+    b = si.make_verify_batch(cfg, 79, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True,
+                             dtype=torch.float16)
+    g = torch.Generator(device="cpu").manual_seed(80)
+    shape = (b.table.n_rows, hkv, d)
+    k_new = torch.randn(shape, generator=g).to(torch.float16).cuda()
+    v_new = torch.randn(shape, generator=g).to(torch.float16).cuda()
+    t = b.table
+    want_k, want_v = si.host_elems(b.k_pool).copy(), si.host_elems(b.v_pool).copy()
+    orc.append_kv(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, cfg.page_size, want_k, want_v,
+                  si.host_elems(k_new), si.host_elems(v_new))
+    _, masks = si.random_trees(draft, np.random.default_rng(81), "random")
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    out = torch.full_like(b.q, float("nan"))
+    ctx.append_kv(tab, b.k_pool, b.v_pool, k_new, v_new)
+    ctx.verify_attn(tab, b.k_pool, b.v_pool, b.q, out, hq, tree_mask=masks)
+    torch.cuda.synchronize()
+    assert np.array_equal(si.host_elems(b.k_pool).view(np.uint16), want_k.view(np.uint16))
+    assert np.array_equal(si.host_elems(b.v_pool).view(np.uint16), want_v.view(np.uint16))
+    want = orc.verify_attention(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table, cfg.page_size,
+                                si.host_elems(b.q), want_k, want_v, hq, hkv, 1.0 / math.sqrt(d), tree_mask=masks)
+    assert_close(out, want, "fp16 append + tree attention")
+
+
+def test_fp16_full_size_sampled(ctx):
+    cfg = si.CONFIGS["13b"]
+    b = si.make_verify_batch(cfg, 5, device="cuda", dtype=torch.float16)
+    got = hip_attention(ctx, b)
+    assert not torch.isnan(got.float()).any()
+    n_tok = b.table.prefix_len + b.table.draft_len
+    reqs = sorted({int(np.argmin(n_tok)), int(np.argmax(n_tok)), int(np.argmax(b.table.draft_len)), 7})
+    assert_close(got, oracle_attention(b, 0.0, requests=reqs, heads=[0, 21, 39]), "13b fp16")
+
+
+def test_mixed_element_types_are_refused(ctx):
+    cfg = make_cfg("mixed", 2, 2, 2, 64)
+    b = si.make_verify_batch(cfg, 82, device="cuda", prefix_len=np.array([5, 40]), draft_len=np.array([2, 3]))
+    t = b.table
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    with pytest.raises(AssertionError):
+        ctx.verify_attn(tab, b.k_pool, b.v_pool, b.q.to(torch.float16), torch.empty_like(b.q), 2)
+    with pytest.raises(TypeError):
+        ctx.verify_attn(tab, b.k_pool.float(), b.v_pool.float(), b.q.float(), torch.empty_like(b.q).float(), 2)
 
 
 # ------------------------------------------------------------------------------ KV append
