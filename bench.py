@@ -252,9 +252,12 @@ def main():
     # strips of more than 32 (draft row x query head) rows run on the grouped-query kernel
     group = cfg.n_q_heads // cfg.n_kv_heads
     attn_kernel = "verify_attn_group_kernel" if min(int(t.draft_len.max()), 64 // group) * group > 32 else "verify_attn_kernel"
+    # measured HBM bytes per launch: the PMC summary of this workload as the default flags run it, else none
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
-    if os.path.exists(tpath):
+    as_profiled = (args.seed == 3 and args.decomp == "config" and not args.tree and not args.page_size
+                   and args.kv_layout == "hnd" and args.dtype == "bf16" and M == 1 and not args.waves)
+    if as_profiled and os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
     res = {
