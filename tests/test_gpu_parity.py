@@ -4,6 +4,7 @@ seeded inputs.  Attention: every element within 2e-2 absolute OR 2e-2 relative o
 """
 import dataclasses
 import math
+import os
 
 import numpy as np
 import pytest
@@ -318,6 +319,62 @@ def test_random_batches(ctx, seed):
     what = f"seed {seed}: hkv {hkv} group {group} d {d} page {page} kind {kind} waves {waves} scale {scale}"
     print(what, flush=True)
     assert_close(hip_attention(ctx, b, subs=subs, scale=scale, waves=waves), oracle_attention(b, scale), what)
+
+
+def wide_random_case(ctx, seed):
+    """One random case over every axis at once: shapes, group sizes, page sizes, both element types, head- and
+    token-major pages with padded pitches, decompositions, share counts, scales, linear and tree drafts."""
+    rng = np.random.default_rng(50000 + seed)
+    hkv = int(rng.choice([1, 2, 3, 5, 8]))
+    group = int(rng.choice([1, 1, 2, 3, 4, 5, 8, 16]))
+    d = int(rng.choice([64, 128]))
+    page = int(rng.choice([1, 2, 4, 8, 16, 16, 32, 64, 128]))
+    n_req = int(rng.integers(1, 12))
+    prefix = np.where(rng.random(n_req) < 0.3, rng.integers(0, 40, n_req), rng.integers(0, 3000, n_req))
+    draft = rng.integers(1, max(1, min(16, 64 // group)) + 1, n_req)
+    dtype = torch.float16 if rng.random() < 0.4 else torch.bfloat16
+    cfg = make_cfg("wide", n_req, hkv * group, hkv, d, page=page)
+    b = si.make_verify_batch(cfg, 60000 + seed, device="cuda", prefix_len=prefix, draft_len=draft, poison_unused=True,
+                             dtype=dtype)
+    layout = "head-major"
+    if rng.random() < 0.4:
+        n_pages, _, P, _ = b.k_pool.shape
+        pitch = d + int(rng.choice([0, 0, 8, 64]))
+        k_alt = torch.full((n_pages, P, hkv, pitch), float("nan"), dtype=dtype, device="cuda")
+        v_alt = k_alt.clone()
+        k_alt[..., :d] = b.k_pool.permute(0, 2, 1, 3); v_alt[..., :d] = b.v_pool.permute(0, 2, 1, 3)
+        b.k_pool = k_alt.permute(0, 2, 1, 3)[..., :d]; b.v_pool = v_alt.permute(0, 2, 1, 3)[..., :d]
+        layout = f"token-major, pitch {pitch}"
+    kind = int(rng.integers(4))
+    if kind == 0:
+        subs = None
+    elif kind == 1:
+        subs = orc.decompose_q_split(prefix, draft, int(rng.integers(1, 6)))
+    elif kind == 2:
+        subs = orc.decompose_kv_split(prefix, draft, int(rng.integers(1, 700)))
+    else:
+        subs = np.array([(i,) + r for i in range(n_req) for r in random_rectangles(rng, int(prefix[i]), int(draft[i]))],
+                        dtype=np.int32)
+    waves = int(rng.choice([1, 3, 17, 256, 0, 0]))
+    scale = float(rng.choice([0.0, 0.0, 0.3, 1.0]))
+    tree = rng.random() < 0.3
+    what = (f"seed {seed}: hkv {hkv} group {group} d {d} page {page} {layout} {dtype} kind {kind} waves {waves} "
+            f"scale {scale} tree {tree}")
+    if tree:
+        masks = si.random_trees(draft, rng, str(rng.choice(["random", "star", "wide", "chain"])))[1]
+        assert_close(hip_tree_attention(ctx, b, masks, subs=subs, scale=scale, waves=waves),
+                     oracle_tree_attention(b, masks, scale), what)
+    else:
+        assert_close(hip_attention(ctx, b, subs=subs, scale=scale, waves=waves), oracle_attention(b, scale), what)
+
+
+def test_random_batches_over_all_axes(ctx):
+    """48 cases by default; SPIN_SWEEP_CASES=n runs the first n seeds (5400 have passed)."""
+    n = int(os.environ.get("SPIN_SWEEP_CASES", "48"))
+    for seed in range(n):
+        wide_random_case(ctx, seed)
+        if seed % 100 == 99:
+            print(f"{seed + 1} cases", flush=True)
 
 
 FULL = [("7b", 1), ("skewed", 2), ("13b", 3), ("70b_gqa", 4)]
@@ -877,6 +934,70 @@ def test_accept_tree_rejection(ctx, vocab, shape):
         torch.cuda.synchronize()
         np.testing.assert_array_equal(n_l.cpu().numpy(), n_o)
         np.testing.assert_array_equal(t_l.cpu().numpy(), nxt_o)
+
+
+def wide_accept_case(ctx, seed):
+    """One random acceptance case: vocabulary sizes around the kernels' step sizes, linear drafts or trees of any
+    shape, greedy or rejection sampling, narrow to wide logits.  Returns False when the oracle's decision margin
+    is too small to compare bit for bit."""
+    import paper_2503_15921_amd as spin
+    rng = np.random.default_rng(90000 + seed)
+    vocab = int(rng.choice([1, 2, 3, 5, 17, 64, 255, 256, 257, 1000, 4095, 4096, 4097, 8191, 32000, 50257]))
+    B = int(rng.integers(1, 10))
+    tree = rng.random() < 0.5
+    max_g = 10 if vocab > 8000 else (64 if tree else 40)
+    draft_len = rng.integers(1, max_g + 1, B).astype(np.int32)
+    R = int(draft_len.sum())
+    sigma = float(rng.choice([0.5, 2.0, 6.0]))
+    greedy = rng.random() < 0.4
+    what = f"seed {seed}: vocab {vocab} B {B} R {R} tree {tree} greedy {greedy} sigma {sigma}"
+    dev = lambda a: torch.from_numpy(a).cuda()
+    if not tree:
+        rho = None if rng.random() < 0.3 else float(rng.choice([0.5, 0.9, 0.99]))
+        ab = si.make_accept_batch(draft_len, vocab, sigma, 91000 + seed, device="cuda", rho=rho,
+                                  draft_token_mode="argmax" if greedy else "sample")
+        mode = spin.ACCEPT_GREEDY if greedy else spin.ACCEPT_REJECTION
+        n_g, t_g = hip_accept(ctx, mode, ab)
+        n_o, t_o, margin = oracle_accept(mode, ab)
+        if margin.min() <= 1e-9:
+            return False
+        np.testing.assert_array_equal(n_g, n_o, err_msg=what)
+        np.testing.assert_array_equal(t_g, t_o, err_msg=what)
+        return True
+    parents, _ = si.random_trees(draft_len, rng, str(rng.choice(["random", "wide", "star", "chain"])))
+    tl = rng.normal(0, sigma, (R + B, vocab)).astype(np.float32)
+    dl = np.empty((R, vocab), dtype=np.float32)
+    tokens = np.empty(R, dtype=np.int32)
+    r = 0
+    for i, g in enumerate(draft_len):
+        for t in range(g):
+            prow = tl[r + i + parents[r + t] + 1]
+            dl[r + t] = 0.95 * prow + 0.31 * rng.normal(0, sigma, vocab)
+            if greedy:
+                tokens[r + t] = int(np.argmax(prow)) if rng.random() < 0.6 else int(rng.integers(vocab))
+            else:
+                tokens[r + t] = rng.choice(vocab, p=orc._softmax64(dl[r + t]))
+        r += g
+    if greedy:
+        n_o, path_o, nxt_o, margin = orc.accept_tree_greedy(draft_len, parents, tokens, tl)
+        n_g, path_g, nxt_g = hip_accept_tree(ctx, draft_len, parents, dev(tokens), dev(tl))
+    else:
+        ua, us = rng.random(R), rng.random(B)
+        n_o, path_o, nxt_o, margin = orc.accept_tree_rejection(draft_len, parents, tokens, tl, dl, ua, us)
+        n_g, path_g, nxt_g = hip_accept_tree(ctx, draft_len, parents, dev(tokens), dev(tl), dev(dl), dev(ua), dev(us))
+    if np.min(margin) <= 1e-9:
+        return False
+    np.testing.assert_array_equal(n_g, n_o, err_msg=what)
+    np.testing.assert_array_equal(path_g, path_o, err_msg=what)
+    np.testing.assert_array_equal(nxt_g, nxt_o, err_msg=what)
+    return True
+
+
+def test_accept_over_all_axes(ctx):
+    """100 cases by default; SPIN_SWEEP_CASES=n runs the first n seeds (2000 have passed, one too close to call)."""
+    n = int(os.environ.get("SPIN_SWEEP_CASES", "100"))
+    compared = sum(wide_accept_case(ctx, seed) for seed in range(n))
+    assert compared >= 0.95 * n
 
 
 def test_accept_tree_rejection_many_rejected_siblings(ctx):
