@@ -18,12 +18,12 @@ What it follows
                                  greedy matching, and multi-round rejection sampling over the children.
   * decompose_*              -- Sec. V-A: request decomposition and the choice of the
                                  KV-tensor length L for a fixed width B.
-  * accept_greedy / accept_rejection -- the verification phase of Sec. II-A2 ("tokens
-                                 consistent with the LLM's output are accepted"); the paper
-                                 does not print the rule, so these follow the speculative
+  * accept_greedy / accept_rejection -- the verification phase of Sec. II-A2 (draft tokens that
+                                 agree with the LLM's own output are kept); the paper does
+                                 not print the rule, so these follow the speculative
                                  sampling rule of the works it cites in Sec. I.
 
-Readings taken where the paper is silent or ambiguous (each is listed in the design doc):
+Readings taken where the paper is silent or ambiguous:
   * Eq. (2) has no 1/sqrt(d): `scale` is a parameter (1.0 gives the literal formula).
   * Eq. (2) sums over all n tokens; autoregressive visibility is only in prose.  Here draft row
     t of request i sees keys j <= p_i + t (whole prefix, causal inside the draft block).
