@@ -34,14 +34,13 @@ __device__ __forceinline__ MaxArg better(MaxArg a, MaxArg b) {
 
 // exp(d) in float64 for the sums and masses, d below about 700: d = (256 e + j) ln2/256 + r with
 // |r| <= ln2/512, so exp(d) = 2^e * 2^(j/256) * exp(r) with a 256-entry table (in LDS) and a cubic for
-// exp(r) (remainder r^4/24 < 1.4e-13 relative: four orders below what the accept decisions need, and
-// about half the float64 instructions of the general routine).  Minus infinity (and anything below
+// exp(r) (remainder r^4/24 < 1.4e-13 relative, the rounded ln2/256 adds 2.4e-14: four orders below what
+// the accept decisions need, and about half the float64 instructions of the general routine).  Minus infinity (and anything below
 // -800) gives 0.
 __device__ __forceinline__ double exp_table64(double d, const double* tab) {
     d = fmax(d, -800.0);
     const double kd = __builtin_rint(d * 369.3299304675746);            // 256 / ln 2
-    double r = fma(kd, -0.0027076061740622863, d);                           // ln2/256, high part
-    r = fma(kd, -9.058776616587108e-20, r);                                  // ln2/256 - high part
+    const double r = fma(kd, -0.0027076061740622863, d);                     // ln2/256 rounded: off by 9.1e-20, |kd| < 3e5
     const int k = (int)kd;
     double p = fma(r, 1.0 / 6.0, 0.5);
     p = fma(p, r, 1.0);
