@@ -489,9 +489,9 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 // own 32 keys of it (K and V both as 1 KiB-contiguous loads) and parks them in LDS -- K in MFMA
 // operand shape, V already transposed into MFMA operands (the 8x8 register transpose of the
 // single-wavefront kernel, done once by the loading wavefront) -- and after a barrier every
-// wavefront reads the sub-blocks it needs.  Shares, pieces, the look-ahead across pieces and the
-// queue are the same, with the workgroup in the wavefront's place; results are stored as they
-// finish (a workgroup meets few ends of a (request, KV head) per share).
+// wavefront reads the sub-blocks it needs.  Shares, pieces and the look-ahead across pieces are the
+// same, with the workgroup in the wavefront's place and without the queued tail; results are stored
+// as they finish (a workgroup meets few ends of a (request, KV head) per share).
 template <int D, int NW, bool TREE, class E>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void verify_attn_group_kernel(AttnParams P) {
     typedef typename E::vec8 vec8;
@@ -504,7 +504,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     __shared__ __attribute__((aligned(16))) uint16_t sK[NW][32 * LROW];
     __shared__ u32x4 sVt[NW][8][64];   // V of each sub-block as MFMA operands: [head dim within chunk][lane]
     __shared__ int32_t sPT[3][PTR * 64];
-    __shared__ int32_t s_next;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m16 = lane & 15, g = lane >> 4;
@@ -520,7 +519,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         return t <= 1 ? 1 : (t == 2 || NW == 2 ? 2 : 4);
     };
 
-    for (int share = blockIdx.x;;) {
+    // One share per workgroup: the planner queues no chunks for this kernel (its cuts cost more in partial
+    // results than the evening-out of the ends saves).
+    {
+    const int share = blockIdx.x;
     const int pc_begin = P.wave_begin[share], pc_end = P.wave_begin[share + 1];
     if (pc_begin < pc_end) {
     auto fetch_piece = [&](int r, Piece& pc) {
@@ -807,13 +809,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         fetch_piece(next_piece++, p3);
     }
     }
-    if (P.n_queued == 0) break;
-    __syncthreads();
-    if (threadIdx.x == 0) s_next = atomicAdd(P.queue, 1);
-    __syncthreads();
-    const int next = s_next;
-    if (next >= P.n_queued) break;
-    share = gridDim.x + next;
     }
 }
 
@@ -933,6 +928,7 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         p.wave_begin = wave_begin_dev[cls];
         p.queue = queues_dev + cls;
         p.n_queued = n_queued[cls];
+        if (cls == 2 && p.n_queued != 0) return hipErrorInvalidValue;   // the grouped-query kernel takes no queued chunks
         dim3 grid((unsigned)n_waves[cls]);
         void* args[] = {&p};
         const void* fn = p.tree_rows ? attn_kernel_ptr<D, true, E>(cls) : attn_kernel_ptr<D, false, E>(cls);
