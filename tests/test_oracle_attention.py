@@ -187,6 +187,27 @@ def test_key_shift_invariance():
     np.testing.assert_allclose(moved, base, rtol=1e-11, atol=1e-12)
 
 
+def test_element_types_read_as_values():
+    """The oracle takes bf16 as raw uint16 bit patterns and fp16 as a numpy float16 array.  Dyadic values are
+    exact in both types, so the two forms of the same problem give the same answer to the last bit, and so does the
+    float64 form; half-precision values that bf16 cannot hold (1 + 2^-10) are read exactly too."""
+    rng = np.random.default_rng(12)
+    prefix = np.array([9, 2]); draft = np.array([3, 1])
+    table, q, kp, vp, dk, dv = tiny_problem(12, prefix, draft)
+    qv = rng.integers(-8, 9, size=q.shape).astype(np.float32) / 8
+    kv = rng.integers(-8, 9, size=kp.shape).astype(np.float32) / 8
+    vv = rng.integers(-8, 9, size=vp.shape).astype(np.float32) / 8
+    as_bf16 = run_oracle(table, f32_to_bf16_bits(qv), f32_to_bf16_bits(kv), f32_to_bf16_bits(vv), 2, 2, 0.5)
+    as_f16 = run_oracle(table, qv.astype(np.float16), kv.astype(np.float16), vv.astype(np.float16), 2, 2, 0.5)
+    as_f64 = run_oracle(table, qv.astype(np.float64), kv.astype(np.float64), vv.astype(np.float64), 2, 2, 0.5)
+    np.testing.assert_array_equal(as_bf16, as_f16)
+    np.testing.assert_array_equal(as_bf16, as_f64)
+    fine = np.float16(1.0 + 2.0 ** -10)
+    vv16 = np.full(vp.shape, fine, dtype=np.float16)
+    out = run_oracle(table, qv.astype(np.float16), kv.astype(np.float16), vv16, 2, 2, 0.5)
+    np.testing.assert_allclose(out[~np.isnan(out)], 1.0 + 2.0 ** -10, rtol=1e-15)
+
+
 def test_joint_permutation_of_prefix_pairs():
     prefix = np.array([8]); draft = np.array([2])
     table, q, kp, vp, dk, dv = tiny_problem(11, prefix, draft, shuffle=False)
