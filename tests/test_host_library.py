@@ -156,6 +156,7 @@ def check_schedule(prefix, draft, subs, page, group, n_kv, n_waves):
         else:      # short shares: boundaries within 4 blocks of the end of a (rectangle, head) moved there
             assert static.max() <= static.mean() + 9
         if queued.any():
+            assert cls < 2                      # the grouped-query kernel gets equal shares only
             assert queued[len(static):].all() and n_waves >= 64
             assert per_share[queued].min() >= 1 and per_share[queued].max() * bk <= 1024
             assert static.min() * bk >= 5000 and 0.05 < per_share[queued].sum() / per_share.sum() < 0.15
@@ -228,6 +229,16 @@ def test_scheduler_keeps_short_pairs_whole():
     assert (pcs[pcs[:, 0] == 7][:, 8] & spin.PIECE_DIRECT).sum() == 0
     short = pcs[(pcs[:, 0] != 7) & ((pcs[:, 8] & spin.PIECE_CARRY_OUT) == 0)]
     assert (short[:, 8] & spin.PIECE_DIRECT).mean() > 0.9
+
+
+def test_scheduler_queues_a_tail_for_long_single_wavefront_shares_only():
+    rng = np.random.default_rng(7)
+    prefix = rng.integers(3000, 9000, 24).astype(np.int32)
+    draft = rng.integers(5, 9, 24).astype(np.int32)
+    mha = check_schedule(prefix, draft, None, 16, 1, 8, 128)          # strips of at most 8 rows
+    assert (mha[:, 8] & spin.PIECE_QUEUED).any()
+    gqa = check_schedule(prefix, draft, None, 16, 8, 8, 128)          # strips of up to 64 rows
+    assert (gqa[:, 6] == 2).all() and not (gqa[:, 8] & spin.PIECE_QUEUED).any()
 
 
 def test_scheduler_rejoins_row_bands_sharing_a_prefix():
