@@ -11,6 +11,10 @@
  *                                                                (Sec. II-A1 Eq. (2), Sec. V-A Eq. (13))
  *   spin_accept       greedy-match or rejection-sampling acceptance of the draft tokens
  *                                                                (verification phase, Sec. II-A2)
+ *   spin_append_kv    the draft tokens' K/V rows enter the paged cache just before that pass
+ *                                                                (the KV cache of Sec. II-A1)
+ *   spin_verify_attn_tree, spin_accept_tree   the same two steps for drafts that are token trees
+ *                                                                (the related work named in Sec. I)
  *
  * Conventions
  *   - Plain C, no exceptions cross this boundary.  Every function returns SPIN_OK (0) or a
