@@ -482,27 +482,35 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     }
 }
 
-// Grouped-query variant (instantiated with NW = 4): a workgroup of NW wavefronts shares one K/V
-// stream.  With G query heads per KV head a strip has up to 64 (draft row x query head) rows;
-// wavefront w owns row tile w (16 rows), so the per-block work of all rows runs on NW SIMDs at once
-// while every K/V byte is fetched from HBM once.  A block is 32*NW keys: each wavefront fetches its
-// own 32 keys of it (K and V both as 1 KiB-contiguous loads) and parks them in LDS -- K in MFMA
-// operand shape, V already transposed into MFMA operands (the 8x8 register transpose of the
-// single-wavefront kernel, done once by the loading wavefront) -- and after a barrier every
-// wavefront reads the sub-blocks it needs.  Shares, pieces and the look-ahead across pieces are the
-// same, with the workgroup in the wavefront's place and without the queued tail; results are stored
-// as they finish (a workgroup meets few ends of a (request, KV head) per share).
-template <int D, int NW, bool TREE, class E>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void verify_attn_group_kernel(AttnParams P) {
+// Grouped-query variant: with G query heads per KV head a strip has up to 64 (draft row x query
+// head) rows, four MFMA column tiles, whose arithmetic per key a single wavefront cannot hide behind
+// its own loads.  A workgroup of eight wavefronts (one per CU, two per SIMD) therefore splits the
+// work by kind:
+//   * wavefronts 4..7 stream: each owns 32 keys of every 128-key block, keeps the loads of two
+//     blocks in flight in two register sets (K and V both as 1 KiB-contiguous loads), and parks the
+//     older set in LDS -- K in MFMA operand shape, V already transposed into MFMA operands (the 8x8
+//     register transpose of the single-wavefront kernel, done once here for all readers) -- into
+//     one of two stages, alternating;
+//   * wavefronts 0..3 compute: wavefront t owns row tile t (16 rows) of the strip and works through
+//     the four 32-key sub-blocks of the stage the streamers have just filled.
+// One barrier per block hands a stage over (block i is parked before that barrier and consumed after
+// it, while block i+1 is parked into the other stage), so the streamers run one block ahead in LDS and
+// two more in registers, their load stream never waits for arithmetic, and the stores and query
+// loads of the computing wavefronts never sit between a streamer's load and its wait.  Both kinds
+// walk the same list of pieces of the workgroup's share; every K/V byte is fetched from HBM once.
+constexpr int kGroupWaves = 8;
+
+template <int D, bool TREE, class E>
+__global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void verify_attn_group_kernel(AttnParams P) {
     typedef typename E::vec8 vec8;
     constexpr int DCH = D / 8;
     constexpr int KCALLS = D / 32;
     constexpr int KLOADS = DCH / 2;
     constexpr int LROW = D + 8;
-    constexpr int BK = 32 * NW;     // keys per block
+    constexpr int BK = 128;          // keys per block: 32 per streaming wavefront
     constexpr int PTR = (kMaxPiecePages + 63) / 64;
-    __shared__ __attribute__((aligned(16))) uint16_t sK[NW][32 * LROW];
-    __shared__ u32x4 sVt[NW][8][64];   // V of each sub-block as MFMA operands: [head dim within chunk][lane]
+    __shared__ __attribute__((aligned(16))) uint16_t sK[2][4][32 * LROW];
+    __shared__ u32x4 sVt[2][4][8][64];   // V of each sub-block as MFMA operands: [head dim within chunk][lane]
     __shared__ int32_t sPT[3][PTR * 64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -510,21 +518,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int G = P.group;
     const int pshift = P.page_shift;
     const int pmask = (1 << pshift) - 1;
-    // How the wavefronts divide a piece: a strip with T row tiles (16 rows each) is given T_eff = 1, 2 or
-    // 4 tiles; wavefront w owns tile w % T_eff and, when there are more wavefronts than tiles, every
-    // (NW / T_eff)-th 32-key sub-block of each block -- so narrow strips split the keys instead of
-    // leaving wavefronts idle, and the wavefronts sharing a tile merge their accumulators at the end.
-    auto tiles_eff = [&](const Piece& pc) {
-        const int t = (pc.n_q * G + 15) >> 4;
-        return t <= 1 ? 1 : (t == 2 || NW == 2 ? 2 : 4);
-    };
 
     // One share per workgroup: the planner queues no chunks for this kernel (its cuts cost more in partial
     // results than the evening-out of the ends saves).
-    {
     const int share = blockIdx.x;
     const int pc_begin = P.wave_begin[share], pc_end = P.wave_begin[share + 1];
-    if (pc_begin < pc_end) {
+    if (pc_begin >= pc_end) return;   // (the same for the whole workgroup; shares are never empty)
     auto fetch_piece = [&](int r, Piece& pc) {
         if (pc_begin + r < pc_end) {
             typedef const int32_t __attribute__((address_space(4)))* ConstWords;
@@ -534,113 +533,199 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
             pc = Piece{0, 0, 0, 0, 0, 0, 0, 0};
         }
     };
-    // page ids are handled by wavefront 0 for the whole workgroup
-    auto load_pages = [&](const Piece& pc, int32_t (&pr)[PTR]) {
-        const int pg0 = pc.k0 >> pshift;
-        const int npg = pc.k1 > pc.k0 ? ((pc.k1 - 1) >> pshift) - pg0 + 1 : 0;
+    // Both kinds of wavefront pass the same barriers: three while the streamers start up and one per block.
+
+    if (wave >= 4) {
+        // ================================================================== streaming wavefronts
+        __builtin_amdgcn_s_setprio(2);   // few instructions, all of them on the critical path of the memory stream
+        const int w = wave - 4;          // this wavefront's 32 keys of every block
+        // page ids are fetched by the first streaming wavefront for all four
+        auto load_pages = [&](const Piece& pc, int32_t (&pr)[PTR]) {
+            const int pg0 = pc.k0 >> pshift;
+            const int npg = pc.k1 > pc.k0 ? ((pc.k1 - 1) >> pshift) - pg0 + 1 : 0;
 #pragma unroll
-        for (int i = 0; i < PTR; ++i) {
-            const int idx = lane + 64 * i;
-            pr[i] = (wave == 0 && idx < npg) ? P.page_table[pc.pt_base + pg0 + idx] : 0;
-        }
-    };
-    auto store_pages = [&](int buf, const int32_t (&pr)[PTR]) {
-        if (wave == 0) {
+            for (int i = 0; i < PTR; ++i) {
+                const int idx = lane + 64 * i;
+                pr[i] = (w == 0 && idx < npg) ? P.page_table[pc.pt_base + pg0 + idx] : 0;
+            }
+        };
+        auto store_pages = [&](int buf, const int32_t (&pr)[PTR]) {
+            if (w == 0) {
 #pragma unroll
-            for (int i = 0; i < PTR; ++i) sPT[buf][lane + 64 * i] = pr[i];
+                for (int i = 0; i < PTR; ++i) sPT[buf][lane + 64 * i] = pr[i];
+            }
+        };
+        auto row_ptr = [&](const uint16_t* pool, int buf, int pg0, int k1, int64_t head_off, int key) -> const uint16_t* {
+            key = min(key, k1 - 1);   // past the end: a valid row, masked later
+            const int pg = sPT[buf][(key >> pshift) - pg0];
+            return pool + (int64_t)pg * P.page_stride + head_off + (int64_t)(key & pmask) * P.token_stride;
+        };
+        const bool tile_layout = pshift >= 4;   // see the single-wavefront kernel
+        const uint32_t ts2 = (uint32_t)P.token_stride * 2;
+        const uint32_t k_lane_off = (uint32_t)(lane / DCH) * ts2 + (uint32_t)(lane % DCH) * 16;
+        const uint32_t v_lane_off = (uint32_t)(g * 4) * ts2 + (uint32_t)(m16 % DCH) * 16;
+        // One register set: this wavefront's 32 keys (kb + 32*w ...) of a block, K as 1 KiB-contiguous
+        // loads, V as the same 16-byte column chunk of eight keys per lane (see the kernel above).
+        struct RegSet {
+            u32x4 Kr[KLOADS], Vr[8];
+        };
+        auto load_kv = [&](RegSet& R, int buf, int pg0, int k1, int64_t head_off, int kb) {
+            const int kw = kb + 32 * w;
+            if (tile_layout && !(kb & 31) && kb + BK <= k1) {
+                const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][(kw >> pshift) - pg0]);
+                const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][((kw + 16) >> pshift) - pg0]);
+                const int64_t oa = (int64_t)pga * P.page_stride + head_off + (int64_t)(kw & pmask) * P.token_stride;
+                const int64_t ob = (int64_t)pgb * P.page_stride + head_off + (int64_t)((kw + 16) & pmask) * P.token_stride;
+                const char *ka = (const char*)(P.k_pool + oa), *kb_ = (const char*)(P.k_pool + ob);
+                const char *va = (const char*)(P.v_pool + oa), *vb = (const char*)(P.v_pool + ob);
+                constexpr int KPI = 64 / DCH;
+#pragma unroll
+                for (int i = 0; i < KLOADS; ++i) {
+                    const int key = i * KPI;
+                    R.Kr[i] = stream_load((key < 16 ? ka : kb_) + (int64_t)(key & 15) * ts2, k_lane_off);
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) R.Vr[j] = stream_load((j < 4 ? va : vb) + (int64_t)(j & 3) * ts2, v_lane_off);
+            } else {
+#pragma unroll
+                for (int i = 0; i < KLOADS; ++i) {
+                    const int f = i * 64 + lane;
+                    R.Kr[i] = stream_load(row_ptr(P.k_pool, buf, pg0, k1, head_off, kw + f / DCH) + (f % DCH) * 8);
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int kl = (j >> 2) * 16 + g * 4 + (j & 3);
+                    R.Vr[j] = stream_load(row_ptr(P.v_pool, buf, pg0, k1, head_off, kw + kl) + (m16 % DCH) * 8);
+                }
+            }
+        };
+        auto park = [&](const RegSet& R, int stage) {
+#pragma unroll
+            for (int i = 0; i < KLOADS; ++i) {
+                const int f = i * 64 + lane;
+                *(u32x4*)&sK[stage][w][(f / DCH) * LROW + (f % DCH) * 8] = R.Kr[i];
+            }
+            // V: 8x8 transpose of 16-bit values inside each lane, done once here for all readers
+#pragma unroll
+            for (int jd = 0; jd < 8; ++jd) {
+                const uint32_t sel = (jd & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 vt;
+#pragma unroll
+                for (int kp = 0; kp < 4; ++kp) vt[kp] = __builtin_amdgcn_perm(R.Vr[2 * kp + 1][jd >> 1], R.Vr[2 * kp][jd >> 1], sel);
+                sVt[stage][w][jd][lane] = vt;
+            }
+        };
+
+        // The load cursor: the piece it is in (c0), the three after it, the page-id buffer of c0 and the
+        // next block's first key.  Page ids of the piece three ahead are requested while the last block
+        // of c0 is issued (ahead of that block's K/V loads, so that the K/V loads stay the youngest) and
+        // stored one step later into the buffer c0 has just left.
+        Piece c0, c1, c2, c3;
+        fetch_piece(0, c0);
+        fetch_piece(1, c1);
+        fetch_piece(2, c2);
+        fetch_piece(3, c3);
+        int next_piece = 4;
+        int32_t pr[PTR];
+        load_pages(c0, pr);
+        store_pages(0, pr);
+        load_pages(c1, pr);
+        store_pages(1, pr);
+        load_pages(c2, pr);
+        store_pages(2, pr);
+        bool pr_pending = false;
+        int cb = 0, kb = c0.k0;
+        __syncthreads();                 // barrier 0: the page ids are in place
+        auto issue = [&](RegSet& R) {
+            const bool last = kb + BK >= c0.k1;
+            if (pr_pending) {
+                store_pages(cb == 0 ? 2 : cb - 1, pr);
+                pr_pending = false;
+            }
+            if (last && c3.k1 > c3.k0) {
+                load_pages(c3, pr);
+                pr_pending = true;
+            }
+            load_kv(R, cb, c0.k0 >> pshift, c0.k1, (int64_t)(c0.head_flags & kPieceHeadMask) * P.head_stride, kb);
+            if (!last) {
+                kb += BK;
+            } else if (c1.k1 > c1.k0) {
+                cb = cb == 2 ? 0 : cb + 1;
+                c0 = c1;
+                c1 = c2;
+                c2 = c3;
+                fetch_piece(next_piece++, c3);
+                kb = c0.k0;
+            }   // else: the share is exhausted; the cursor stays, later loads repeat its last block and are never parked
+        };
+        // (a barrier after each of the first two issues as well: a page-id buffer is rewritten one step
+        // after the cursor has left it, and every step must be over in all four wavefronts by then)
+        RegSet A, B;
+        issue(A);
+        __syncthreads();                 // barrier 1
+        issue(B);
+        __syncthreads();                 // barrier 2
+        int n_blocks = 0;                // blocks of the whole share
+        for (int r = 0; pc_begin + r < pc_end; ++r) {
+            Piece t;
+            fetch_piece(r, t);
+            n_blocks += (t.k1 - t.k0 + BK - 1) / BK;
         }
-    };
-    vec8 qf[KCALLS];
-    auto load_q = [&](const Piece& pc) {
+        for (int i = 0; i < n_blocks; i += 2) {
+            park(A, 0);
+            issue(A);
+            __syncthreads();             // barrier i + 3: block i is in stage 0
+            if (i + 1 < n_blocks) {
+                park(B, 1);
+                issue(B);
+                __syncthreads();         // barrier i + 4: block i + 1 is in stage 1
+            }
+        }
+        return;
+    }
+
+    // ====================================================================== computing wavefronts
+    const int tile = wave;               // the row tile (16 rows of the strip) this wavefront owns
+    vec8 qf[KCALLS], qn[KCALLS];
+    uint64_t anc_n = 0;                  // TREE: the next piece's ancestor mask and prefix length
+    int pfx_n = 0;
+    auto load_q = [&](const Piece& pc, vec8 (&q)[KCALLS]) {
         const int kvh = pc.head_flags & kPieceHeadMask;
-        const int nn = (wave % tiles_eff(pc)) * 16 + m16;
+        const int nn = tile * 16 + m16;
         const int tl = nn / G, hg = nn - tl * G;
         const bool valid = tl < pc.n_q;
         const uint16_t* qp = P.q + ((int64_t)(pc.q_row0 + (valid ? tl : 0)) * P.n_q_heads + kvh * G + hg) * D + g * 8;
 #pragma unroll
         for (int c = 0; c < KCALLS; ++c) {
             u32x4 v = valid ? *(const u32x4*)(qp + c * 32) : u32x4{0, 0, 0, 0};
-            qf[c] = __builtin_bit_cast(vec8, v);
+            q[c] = __builtin_bit_cast(vec8, v);
+        }
+        if (TREE) {
+            const u32x4 rec = *(const u32x4*)(P.tree_rows + (int64_t)(pc.q_row0 + (valid ? tl : 0)) * 4);
+            anc_n = (uint64_t)rec[0] | ((uint64_t)rec[1] << 32);
+            pfx_n = (int)rec[2];
         }
     };
-    // this wavefront's 32 keys (kb + 32*wave ...) of the block starting at kb: K as 1 KiB-contiguous
-    // loads, V as the same 16-byte column chunk of eight keys per lane (see the kernel above)
-    u32x4 Kr[KLOADS], Vr[8];
-    auto row_ptr = [&](const uint16_t* pool, int buf, int pg0, int k1, int64_t head_off, int key) -> const uint16_t* {
-        key = min(key, k1 - 1);   // past the end: a valid row, masked later
-        const int pg = sPT[buf][(key >> pshift) - pg0];
-        return pool + (int64_t)pg * P.page_stride + head_off + (int64_t)(key & pmask) * P.token_stride;
-    };
-    const bool tile_layout = pshift >= 4;   // see the single-wavefront kernel
-    const uint32_t ts2 = (uint32_t)P.token_stride * 2;
-    const uint32_t k_lane_off = (uint32_t)(lane / DCH) * ts2 + (uint32_t)(lane % DCH) * 16;
-    const uint32_t v_lane_off = (uint32_t)(g * 4) * ts2 + (uint32_t)(m16 % DCH) * 16;
-    auto load_kv = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
-        const int kw = kb + 32 * wave;
-        if (tile_layout && !(kb & 31) && kb + BK <= k1) {
-            const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][(kw >> pshift) - pg0]);
-            const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][((kw + 16) >> pshift) - pg0]);
-            const int64_t oa = (int64_t)pga * P.page_stride + head_off + (int64_t)(kw & pmask) * P.token_stride;
-            const int64_t ob = (int64_t)pgb * P.page_stride + head_off + (int64_t)((kw + 16) & pmask) * P.token_stride;
-            const char *ka = (const char*)(P.k_pool + oa), *kb_ = (const char*)(P.k_pool + ob);
-            const char *va = (const char*)(P.v_pool + oa), *vb = (const char*)(P.v_pool + ob);
-            constexpr int KPI = 64 / DCH;
-#pragma unroll
-            for (int i = 0; i < KLOADS; ++i) {
-                const int key = i * KPI;
-                Kr[i] = stream_load((key < 16 ? ka : kb_) + (int64_t)(key & 15) * ts2, k_lane_off);
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) Vr[j] = stream_load((j < 4 ? va : vb) + (int64_t)(j & 3) * ts2, v_lane_off);
-        } else {
-#pragma unroll
-            for (int i = 0; i < KLOADS; ++i) {
-                const int f = i * 64 + lane;
-                Kr[i] = stream_load(row_ptr(P.k_pool, buf, pg0, k1, head_off, kw + f / DCH) + (f % DCH) * 8);
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int kl = (j >> 2) * 16 + g * 4 + (j & 3);
-                Vr[j] = stream_load(row_ptr(P.v_pool, buf, pg0, k1, head_off, kw + kl) + (m16 % DCH) * 8);
-            }
-        }
-    };
-
-    Piece cp, p1, p2, p3;
+    Piece cp, p1;
     fetch_piece(0, cp);
     fetch_piece(1, p1);
-    fetch_piece(2, p2);
-    fetch_piece(3, p3);
-    int next_piece = 4;
-    int32_t pr[PTR];
-    load_pages(cp, pr);
-    store_pages(0, pr);
-    load_pages(p1, pr);
-    store_pages(1, pr);
-    load_pages(p2, pr);
-    store_pages(2, pr);
-    bool pr_pending = false;
-    load_q(cp);
-    __syncthreads();
-
+    int next_piece = 2;
+    load_q(cp, qf);
+    uint64_t anc = anc_n;                // TREE: draft keys (bit u = key prefix + u) this lane's row may see
+    int pfx = __builtin_amdgcn_readfirstlane(pfx_n);
+    if (p1.k1 > p1.k0) load_q(p1, qn);   // the queries of a piece are requested one piece ahead
     f32x4 O[8];
     float m_run = kNegBig, l_run = 0.f;
-    int cb = 0;
-    load_kv(cb, cp.k0 >> pshift, cp.k1, (int64_t)(cp.head_flags & kPieceHeadMask) * P.head_stride, cp.k0);
+    int blk = 0;                          // blocks of the share so far: block i sits in stage i & 1
+    __syncthreads();                      // barriers 0, 1, 2: the streamers' start-up
+    __syncthreads();
+    __syncthreads();
 
     while (true) {
-        const int t_eff = tiles_eff(cp);
-        const int ksplit = NW / t_eff, kgroup = wave / t_eff;   // this wavefront takes sub-blocks kgroup, kgroup + ksplit, ...
-        const int nn = (wave % t_eff) * 16 + m16;                // this lane's row of the strip's (draft row x head) rows
+        const bool active = tile * 16 < cp.n_q * G;     // narrower strips leave the upper tiles idle
+        const int nn = tile * 16 + m16;                  // this lane's row of the strip's (draft row x head) rows
         const int tl = nn / G, hg = nn - tl * G;
         const int lim = tl < cp.n_q ? min(cp.k1, cp.causal0 + tl) : cp.k0;
-        uint64_t anc = 0;   // TREE: draft keys (bit u = key prefix + u) this lane's row may see
-        int pfx = 0;        // TREE: the request's prefix length
-        if (TREE) {
-            const u32x4 rec = *(const u32x4*)(P.tree_rows + (int64_t)(cp.q_row0 + (tl < cp.n_q ? tl : 0)) * 4);
-            anc = (uint64_t)rec[0] | ((uint64_t)rec[1] << 32);
-            pfx = __builtin_amdgcn_readfirstlane((int)rec[2]);
-        }
         if (!(cp.head_flags & kPieceCarryIn)) {
             m_run = kNegBig;
             l_run = 0.f;
@@ -649,47 +734,14 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
         const int full_end = TREE ? min(min(cp.k1, cp.causal0), pfx) : min(cp.k1, cp.causal0);
         const bool more = p1.k1 > p1.k0;
-        const bool new_q = more && !(p1.head_flags & kPieceCarryIn);
 
         for (int kb = cp.k0; kb < cp.k1; kb += BK) {
-            const bool last = kb + BK >= cp.k1;
-            const bool hop = last && more;
-            const int s_buf = hop ? (cb == 2 ? 0 : cb + 1) : cb;
-            const int s_pg0 = hop ? (p1.k0 >> pshift) : (cp.k0 >> pshift);
-            const int s_k1 = hop ? p1.k1 : cp.k1;
-            const int64_t s_head = (int64_t)((hop ? p1.head_flags : cp.head_flags) & kPieceHeadMask) * P.head_stride;
-            const int s_kb = hop ? p1.k0 : (last ? kb : kb + BK);
-
-            // ---- everybody has finished with the previous block's tiles: park this block's rows in LDS
-            __syncthreads();
-#pragma unroll
-            for (int i = 0; i < KLOADS; ++i) {
-                const int f = i * 64 + lane;
-                *(u32x4*)&sK[wave][(f / DCH) * LROW + (f % DCH) * 8] = Kr[i];
-            }
-            // V: 8x8 transpose of 16-bit values inside each lane, done once here for all wavefronts
-#pragma unroll
-            for (int jd = 0; jd < 8; ++jd) {
-                const uint32_t sel = (jd & 1) ? 0x07060302u : 0x05040100u;
-                u32x4 vt;
-#pragma unroll
-                for (int kp = 0; kp < 4; ++kp) vt[kp] = __builtin_amdgcn_perm(Vr[2 * kp + 1][jd >> 1], Vr[2 * kp][jd >> 1], sel);
-                sVt[wave][jd][lane] = vt;
-            }
-            if (pr_pending) {
-                store_pages(cb == 0 ? 2 : cb - 1, pr);
-                pr_pending = false;
-            }
-            __syncthreads();
-            if (last && (p3.k1 > p3.k0)) {
-                load_pages(p3, pr);
-                pr_pending = true;
-            }
-            load_kv(s_buf, s_pg0, s_k1, s_head, s_kb);
-
-            // ---- every wavefront works through its sub-blocks for its own 16 rows
+            __syncthreads();              // barrier blk + 3: the streamers have parked this block
+            const int st = blk & 1;
+            ++blk;
+            if (!active) continue;
 #pragma unroll 1
-            for (int sb = kgroup; sb < NW; sb += ksplit) {
+            for (int sb = 0; sb < 4; ++sb) {
                 const int kb2 = kb + 32 * sb;
                 if (kb2 >= cp.k1) break;              // the block's tail beyond the piece holds nothing
                 f32x4 S[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
@@ -697,7 +749,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 for (int c = 0; c < KCALLS; ++c)
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
-                        const vec8 a = __builtin_bit_cast(vec8, *(const u32x4*)&sK[sb][(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
+                        const vec8 a = __builtin_bit_cast(vec8, *(const u32x4*)&sK[st][sb][(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
                         S[t] = E::mfma(a, qf[c], S[t]);
                     }
                 float s[8];
@@ -736,41 +788,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 const vec8 Pb = __builtin_bit_cast(vec8, pk);
 #pragma unroll
                 for (int jd = 0; jd < 8; ++jd)
-                    O[jd] = E::mfma(__builtin_bit_cast(vec8, sVt[sb][jd][lane]), Pb, O[jd]);
+                    O[jd] = E::mfma(__builtin_bit_cast(vec8, sVt[st][sb][jd][lane]), Pb, O[jd]);
             }
-            // the queries are no longer needed after the last block: fetch the next piece's if they differ
-            if (last && new_q) load_q(p1);
         }
 
-        // ---- wavefronts that shared a row tile (each on its own keys) merge into the first of them
-        if (!(cp.head_flags & kPieceCarryOut) && ksplit > 1) {
-            f32x4* const sMergeO = reinterpret_cast<f32x4*>(&sVt[0][0][0]);     // [wave][8][64] overlays the V tiles exactly
-            float* const sMergeML = reinterpret_cast<float*>(&sK[0][0]);        // [wave][2][64] overlays the K tiles
-            __syncthreads();                       // everybody has finished reading the tiles
-            if (kgroup > 0) {
-#pragma unroll
-                for (int jd = 0; jd < 8; ++jd) sMergeO[(wave * 8 + jd) * 64 + lane] = O[jd];
-                sMergeML[(wave * 2 + 0) * 64 + lane] = m_run;
-                sMergeML[(wave * 2 + 1) * 64 + lane] = l_run;
-            }
-            __syncthreads();
-            if (kgroup == 0) {
-                for (int k = 1; k < ksplit; ++k) {
-                    const int pw = wave + k * t_eff;
-                    const float m2 = sMergeML[(pw * 2 + 0) * 64 + lane], l2 = sMergeML[(pw * 2 + 1) * 64 + lane];
-                    const float M = fmaxf(m_run, m2);
-                    const float a = fast_exp2(m_run - M), b = fast_exp2(m2 - M);
-#pragma unroll
-                    for (int jd = 0; jd < 8; ++jd) {
-                        const f32x4 o2 = sMergeO[(pw * 8 + jd) * 64 + lane];
-                        O[jd] = O[jd] * a + o2 * b;
-                    }
-                    l_run = l_run * a + l2 * b;
-                    m_run = M;
-                }
-            }
-        }
-        if (!(cp.head_flags & kPieceCarryOut) && kgroup == 0) {
+        if (!(cp.head_flags & kPieceCarryOut) && active) {
             const int kvh = cp.head_flags & kPieceHeadMask;
             float l = l_run;
             l += __shfl_xor(l, 16);
@@ -802,13 +824,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
             }
         }
         if (!more) break;
-        cb = cb == 2 ? 0 : cb + 1;
         cp = p1;
-        p1 = p2;
-        p2 = p3;
-        fetch_piece(next_piece++, p3);
-    }
-    }
+#pragma unroll
+        for (int c = 0; c < KCALLS; ++c) qf[c] = qn[c];
+        anc = anc_n;
+        pfx = __builtin_amdgcn_readfirstlane(pfx_n);
+        fetch_piece(next_piece++, p1);
+        if (p1.k1 > p1.k0) load_q(p1, qn);
     }
 }
 
@@ -896,7 +918,7 @@ hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
 template <int D, bool TREE, class E>
 static const void* attn_kernel_ptr(int cls) {
     return cls == 0 ? (const void*)verify_attn_kernel<D, 1, TREE, E>
-         : cls == 1 ? (const void*)verify_attn_kernel<D, 2, TREE, E> : (const void*)verify_attn_group_kernel<D, 4, TREE, E>;
+         : cls == 1 ? (const void*)verify_attn_kernel<D, 2, TREE, E> : (const void*)verify_attn_group_kernel<D, TREE, E>;
 }
 
 hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
@@ -904,7 +926,7 @@ hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
     const void* fn = head_dim == 128 ? attn_kernel_ptr<128, false, Bf16>(cls) : attn_kernel_ptr<64, false, Bf16>(cls);
     int per_cu = 0, dev = 0;
     hipDeviceProp_t prop;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, cls == 2 ? 256 : 64, 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, cls == 2 ? 64 * kGroupWaves : 64, 0);
     if (e == hipSuccess) e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e != hipSuccess) return e;
@@ -932,7 +954,7 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         dim3 grid((unsigned)n_waves[cls]);
         void* args[] = {&p};
         const void* fn = p.tree_rows ? attn_kernel_ptr<D, true, E>(cls) : attn_kernel_ptr<D, false, E>(cls);
-        hipError_t e = hipLaunchKernel(fn, grid, dim3(cls == 2 ? 256 : 64), args, 0, stream);
+        hipError_t e = hipLaunchKernel(fn, grid, dim3(cls == 2 ? 64 * kGroupWaves : 64), args, 0, stream);
         if (e != hipSuccess) return e;
     }
     if (ev_mid) {
