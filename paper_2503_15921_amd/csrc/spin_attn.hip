@@ -764,12 +764,14 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
                     }
                 }
                 float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // The exponent reference m_run follows the running maximum lazily: it moves (and the
-                // accumulators are rescaled) only when some row's maximum has grown past it by more than
-                // kSlack, so exp2(score - m_run) stays below 2^kSlack and most blocks skip the rescale.
+                // The exponent reference m_run (one value per row, the same in the row's four lanes) follows
+                // the running maximum lazily: it moves (and the accumulators are rescaled) only when some
+                // score has grown past it by more than kSlack, so exp2(score - m_run) stays below 2^kSlack and
+                // most blocks skip the rescale -- and with it the two cross-lane exchanges that make a row's
+                // maximum out of its lanes' maxima.
                 if (__any(mx * P.scale_log2 > m_run + kSlack)) {
+                    mx = fmaxf(mx, __shfl_xor(mx, 16));
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
                     const float m_new = fmaxf(m_run, mx * P.scale_log2);
                     const float alpha = fast_exp2(m_run - m_new);
                     m_run = m_new;
