@@ -740,58 +740,78 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
             const int st = blk & 1;
             ++blk;
             if (!active) continue;
-#pragma unroll 1
+            // The block as a whole -- scores of all four sub-blocks, one test of the exponent reference, all
+            // exponentials, all of P.V -- in straight-line code, so that the LDS reads, matrix and vector
+            // instructions of different sub-blocks overlap (this wavefront has its SIMD almost to itself
+            // and nothing else would hide their latencies).  Rows of the block beyond the piece's end are
+            // copies of its last key (see the streamers) and fall to the mask like every key beyond `lim`.
+            f32x4 S[4][2];
+#pragma unroll
             for (int sb = 0; sb < 4; ++sb) {
-                const int kb2 = kb + 32 * sb;
-                if (kb2 >= cp.k1) break;              // the block's tail beyond the piece holds nothing
-                f32x4 S[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
+                S[sb][0] = f32x4{0, 0, 0, 0};
+                S[sb][1] = f32x4{0, 0, 0, 0};
 #pragma unroll
                 for (int c = 0; c < KCALLS; ++c)
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
                         const vec8 a = __builtin_bit_cast(vec8, *(const u32x4*)&sK[st][sb][(t * 16 + m16) * LROW + (c * 4 + g) * 8]);
-                        S[t] = E::mfma(a, qf[c], S[t]);
+                        S[sb][t] = E::mfma(a, qf[c], S[sb][t]);
                     }
-                float s[8];
+            }
+            float sc[4][8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) s[e] = S[e >> 2][e & 3];
-                if (kb2 + 32 > full_end) {
+            for (int sb = 0; sb < 4; ++sb)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sc[sb][e] = S[sb][e >> 2][e & 3];
+            if (kb + BK > full_end) {
+#pragma unroll
+                for (int sb = 0; sb < 4; ++sb)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const int key = kb2 + (e >> 2) * 16 + g * 4 + (e & 3);
-                        if (key >= lim) s[e] = -INFINITY;
-                        if (TREE && key >= pfx && !((anc >> ((key - pfx) & 63)) & 1)) s[e] = -INFINITY;
+                        const int key = kb + 32 * sb + (e >> 2) * 16 + g * 4 + (e & 3);
+                        if (key >= lim) sc[sb][e] = -INFINITY;
+                        if (TREE && key >= pfx && !((anc >> ((key - pfx) & 63)) & 1)) sc[sb][e] = -INFINITY;
                     }
-                }
-                float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-                // The exponent reference m_run (one value per row, the same in the row's four lanes) follows
-                // the running maximum lazily: it moves (and the accumulators are rescaled) only when some
-                // score has grown past it by more than kSlack, so exp2(score - m_run) stays below 2^kSlack and
-                // most blocks skip the rescale -- and with it the two cross-lane exchanges that make a row's
-                // maximum out of its lanes' maxima.
-                if (__any(mx * P.scale_log2 > m_run + kSlack)) {
-                    mx = fmaxf(mx, __shfl_xor(mx, 16));
-                    mx = fmaxf(mx, __shfl_xor(mx, 32));
-                    const float m_new = fmaxf(m_run, mx * P.scale_log2);
-                    const float alpha = fast_exp2(m_run - m_new);
-                    m_run = m_new;
-                    l_run *= alpha;
+            }
+            float mx = -INFINITY;
 #pragma unroll
-                    for (int jd = 0; jd < 8; ++jd) O[jd] *= alpha;
-                }
-                float p[8], sum = 0.f;
+            for (int sb = 0; sb < 4; ++sb)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mx = fmaxf(mx, sc[sb][e]);
+            // The exponent reference m_run (one value per row, the same in the row's four lanes) follows
+            // the running maximum lazily: it moves (and the accumulators are rescaled) only when some
+            // score has grown past it by more than kSlack, so exp2(score - m_run) stays below 2^kSlack and
+            // most blocks skip the rescale -- and with it the two cross-lane exchanges that make a row's
+            // maximum out of its lanes' maxima.
+            if (__any(mx * P.scale_log2 > m_run + kSlack)) {
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_run, mx * P.scale_log2);
+                const float alpha = fast_exp2(m_run - m_new);
+                m_run = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int jd = 0; jd < 8; ++jd) O[jd] *= alpha;
+            }
+            vec8 Pb[4];
+            float sum = 0.f;
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) {
+                float p[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    p[e] = fast_exp2(s[e] * P.scale_log2 - m_run);
+                    p[e] = fast_exp2(sc[sb][e] * P.scale_log2 - m_run);
                     sum += p[e];
                 }
-                l_run += sum;
                 const u32x4 pk = {E::pack(p[0], p[1]), E::pack(p[2], p[3]), E::pack(p[4], p[5]), E::pack(p[6], p[7])};
-                const vec8 Pb = __builtin_bit_cast(vec8, pk);
+                Pb[sb] = __builtin_bit_cast(vec8, pk);
+            }
+            l_run += sum;
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb)
 #pragma unroll
                 for (int jd = 0; jd < 8; ++jd)
-                    O[jd] = E::mfma(__builtin_bit_cast(vec8, sVt[st][sb][jd][lane]), Pb, O[jd]);
-            }
+                    O[jd] = E::mfma(__builtin_bit_cast(vec8, sVt[st][sb][jd][lane]), Pb[sb], O[jd]);
         }
 
         if (!(cp.head_flags & kPieceCarryOut) && active) {
