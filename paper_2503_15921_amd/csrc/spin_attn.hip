@@ -814,6 +814,15 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
                     O[jd] = E::mfma(__builtin_bit_cast(vec8, sVt[st][sb][jd][lane]), Pb[sb], O[jd]);
         }
 
+        // The next piece's queries (requested when this piece began) are taken over BEFORE this piece's
+        // rows are stored: loads and stores share one in-order counter, and waiting for the queries after
+        // the stores would mean waiting for the stores.
+        if (more) {
+#pragma unroll
+            for (int c = 0; c < KCALLS; ++c) qf[c] = qn[c];
+            anc = anc_n;
+            pfx = __builtin_amdgcn_readfirstlane(pfx_n);
+        }
         if (!(cp.head_flags & kPieceCarryOut) && active) {
             const int kvh = cp.head_flags & kPieceHeadMask;
             float l = l_run;
@@ -847,10 +856,6 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
         }
         if (!more) break;
         cp = p1;
-#pragma unroll
-        for (int c = 0; c < KCALLS; ++c) qf[c] = qn[c];
-        anc = anc_n;
-        pfx = __builtin_amdgcn_readfirstlane(pfx_n);
         fetch_piece(next_piece++, p1);
         if (p1.k1 > p1.k0) load_q(p1, qn);
     }
