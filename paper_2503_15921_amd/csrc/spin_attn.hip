@@ -32,7 +32,7 @@
 //     the middle of the stream would hold up the loads issued after it.
 //   * Rectangles of up to 16 (draft row x query head) rows use one MFMA column tile per wavefront,
 //     up to 32 rows two (verify_attn_kernel<D, 1 | 2>); wider ones, up to 64 rows, go to
-//     verify_attn_group_kernel, where four wavefronts share one K/V stream through LDS.
+//     verify_attn_group_kernel, where four wavefronts stream K/V into LDS for four that compute.
 //   * TREE = true: drafts are token trees; a draft key is visible to a row only if the row's
 //     ancestor mask says so (checked only in the blocks that reach into the draft region).
 #include <hip/hip_runtime.h>
