@@ -508,6 +508,7 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
     constexpr int KLOADS = DCH / 2;
     constexpr int LROW = D + 8;
     constexpr int BK = 128;          // keys per block: 32 per streaming wavefront
+    static_assert(BK == block_keys(2), "the planner balances shares in blocks of this kernel's size");
     constexpr int PTR = (kMaxPiecePages + 63) / 64;
     __shared__ __attribute__((aligned(16))) uint16_t sK[2][4][32 * LROW];
     __shared__ u32x4 sVt[2][4][8][64];   // V of each sub-block as MFMA operands: [head dim within chunk][lane]
