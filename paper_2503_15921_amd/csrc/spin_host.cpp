@@ -226,7 +226,7 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
         }
     }
     // One launch per call: every strip runs in the kernel instance of the widest strip (a single
-    // wavefront for one or two column tiles, a workgroup of four wavefronts beyond that).
+    // wavefront for one or two column tiles, a workgroup of eight wavefronts beyond that).
     int call_cls = 0;
     for (const Strip& st : plan.strips) call_cls = std::max(call_cls, st.cls);
     const int bk = block_keys(call_cls);

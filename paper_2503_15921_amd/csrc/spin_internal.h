@@ -18,7 +18,7 @@ constexpr int kMaxTileRows = 64;
 // Keys per wavefront and streaming block of the attention kernels.
 constexpr int kBlockKeys = 32;
 // Keys per streaming block of the kernel that serves column-tile class c: classes 0 and 1 (one or two
-// tiles) run on single wavefronts, class 2 (up to four tiles) on workgroups of four.
+// tiles) run on single wavefronts, class 2 (up to four tiles) on workgroups with four streaming wavefronts.
 constexpr int block_keys(int cls) { return cls == 2 ? 4 * kBlockKeys : kBlockKeys; }
 // Page ids one piece may touch (cached in LDS by the attention kernel).
 constexpr int kMaxPiecePages = 136;
