@@ -377,30 +377,44 @@ def test_random_batches_over_all_axes(ctx):
             print(f"{seed + 1} cases", flush=True)
 
 
-FULL = [("7b", 1), ("skewed", 2), ("13b", 3), ("70b_gqa", 4)]
+BENCH_SEED = 3   # the seed bench.py draws every configuration's batch with
 
 
-@pytest.mark.parametrize("name,seed", FULL)
-def test_full_size_configs_sampled(ctx, name, seed):
-    """The benchmark shapes at full size, in the launch configuration the benchmark times; the
-    oracle evaluates a sample of (request, head) pairs: shortest, longest and a few random."""
+def product_subs(cfg, table):
+    """The configuration's own decomposition, made by the product's spin_decompose (and equal to the oracle's)."""
+    import paper_2503_15921_amd as spin
+    if not cfg.q_split_width:
+        return None
+    subs, _ = spin.decompose(table.prefix_len, table.draft_len, spin.DECOMP_Q_SPLIT, q_width=cfg.q_split_width)
+    np.testing.assert_array_equal(subs, orc.decompose_q_split(table.prefix_len, table.draft_len, cfg.q_split_width))
+    return subs
+
+
+@pytest.mark.parametrize("name", si.CONFIG_ORDER)
+def test_full_size_configs_every_element(ctx, name):
+    """The five benchmark batches exactly as bench.py draws and launches them (same seed, the
+    configuration's decomposition made by spin_decompose, automatic wavefront count): EVERY output
+    element against the oracle."""
+    cfg = si.CONFIGS[name]
+    b = si.make_verify_batch(cfg, BENCH_SEED, device="cuda")
+    got = hip_attention(ctx, b, subs=product_subs(cfg, b.table))
+    want = oracle_attention(b, 0.0)
+    assert not np.isnan(want).any()
+    err, rms = assert_close(got, want, name)
+    print(f"{name}: all {want.size} elements, max abs err {err:.2e}, rel rms {rms:.2e}")
+
+
+@pytest.mark.parametrize("name,seed", [("7b", 1), ("skewed", 2), ("70b_gqa", 4)])
+def test_full_size_configs_other_seeds(ctx, name, seed):
+    """Other draws of the benchmark shapes, every element again (the grouped-query batch on a third of its requests)."""
     cfg = si.CONFIGS[name]
     b = si.make_verify_batch(cfg, seed, device="cuda")
-    subs = orc.decompose_q_split(b.table.prefix_len, b.table.draft_len, cfg.q_split_width) \
-        if cfg.q_split_width else None
-    got = hip_attention(ctx, b, subs=subs)
+    got = hip_attention(ctx, b, subs=product_subs(cfg, b.table))
+    reqs = None if name != "70b_gqa" else list(range(0, cfg.n_req, 3))
     assert not torch.isnan(got.float()).any()
-    rng = np.random.default_rng(seed)
-    n_tok = b.table.prefix_len + b.table.draft_len
-    reqs = sorted({int(np.argmin(n_tok)), int(np.argmax(n_tok)), int(np.argmax(b.table.draft_len)),
-                   *rng.choice(cfg.n_req, size=3, replace=False).tolist()})
-    heads = sorted({0, cfg.n_q_heads - 1, int(rng.integers(cfg.n_q_heads))})
-    want = oracle_attention(b, 0.0, requests=reqs, heads=heads)
-    err, rms = assert_close(got, want, name)
-    print(f"{name}: sampled {len(reqs)}x{len(heads)} (request, head) pairs, max abs err {err:.2e}, rel rms {rms:.2e}")
+    assert_close(got, oracle_attention(b, 0.0, requests=reqs), f"{name} seed {seed}")
 
 
-# ------------------------------------------------------------------------------ tree-shaped drafts
 def hip_tree_attention(ctx, batch, masks, subs=None, scale=0.0, waves=None):
     t = batch.table
     tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
@@ -468,15 +482,13 @@ def test_tree_of_64_tokens(ctx):
     assert_close(hip_tree_attention(ctx, b, masks), oracle_tree_attention(b, masks), "64-token trees")
 
 
-def test_tree_full_size_sampled(ctx):
+def test_tree_full_size_every_element(ctx):
     cfg = si.CONFIGS["13b"]
-    b = si.make_verify_batch(cfg, 5, device="cuda")
-    rng = np.random.default_rng(65)
-    _, masks = si.random_trees(b.table.draft_len, rng)
+    b = si.make_verify_batch(cfg, BENCH_SEED, device="cuda")
+    _, masks = si.random_trees(b.table.draft_len, np.random.default_rng(BENCH_SEED))   # bench.py --tree random
     got = hip_tree_attention(ctx, b, masks)
-    assert not torch.isnan(got.float()).any()
-    reqs = sorted({int(np.argmax(b.table.draft_len)), *rng.choice(cfg.n_req, size=3, replace=False).tolist()})
-    want = oracle_tree_attention(b, masks, requests=reqs, heads=[0, cfg.n_q_heads - 1])
+    want = oracle_tree_attention(b, masks)
+    assert not np.isnan(want).any()
     assert_close(got, want, "13b with trees")
 
 
@@ -556,14 +568,13 @@ def test_fp16_tree_and_append(ctx, hq, hkv, d):
     assert_close(out, want, "fp16 append + tree attention")
 
 
-def test_fp16_full_size_sampled(ctx):
+def test_fp16_full_size_every_element(ctx):
     cfg = si.CONFIGS["13b"]
-    b = si.make_verify_batch(cfg, 5, device="cuda", dtype=torch.float16)
+    b = si.make_verify_batch(cfg, BENCH_SEED, device="cuda", dtype=torch.float16)
     got = hip_attention(ctx, b)
-    assert not torch.isnan(got.float()).any()
-    n_tok = b.table.prefix_len + b.table.draft_len
-    reqs = sorted({int(np.argmin(n_tok)), int(np.argmax(n_tok)), int(np.argmax(b.table.draft_len)), 7})
-    assert_close(got, oracle_attention(b, 0.0, requests=reqs, heads=[0, 21, 39]), "13b fp16")
+    want = oracle_attention(b, 0.0)
+    assert not np.isnan(want).any()
+    assert_close(got, want, "13b fp16")
 
 
 def test_mixed_element_types_are_refused(ctx):
@@ -693,8 +704,10 @@ def test_accept_tiny(ctx, seed, rho):
     check_accept(ctx, spin.ACCEPT_GREEDY, ab, f"tiny greedy seed {seed} rho {rho}")
 
 
-@pytest.mark.parametrize("name,seed", [("7b", 1), ("skewed", 2), ("13b", 3), ("70b_gqa", 4)])
+@pytest.mark.parametrize("name,seed", [(n, BENCH_SEED) for n in si.CONFIG_ORDER] + [("7b", 1), ("skewed", 2), ("70b_gqa", 4)])
 def test_accept_full_vocab(ctx, name, seed):
+    """Acceptance over the benchmark batches (BENCH_SEED, rho None is exactly what bench.py times) and other
+    draws: every request's accepted length and next token against the oracle, bit for bit."""
     import paper_2503_15921_amd as spin
     cfg = si.CONFIGS[name]
     draft_len = si.draw_lengths(cfg, np.random.default_rng(seed))[1]
@@ -812,10 +825,23 @@ def test_accept_extreme_uniforms(ctx):
     n_o, t_o, margin = oracle_accept(spin.ACCEPT_REJECTION, ab)
     np.testing.assert_array_equal(n_g, n_o)
     # request 1's draw sits at the very end of the CDF, where the two summation orders may pick different
-    # ids among the last few with mass: compare the others bit for bit, and request 1 for validity
+    # ids among the last few with mass: compare the others bit for bit, and request 1 for validity --
+    # the id must carry mass, and the mass after it must be no more than rounding of the total
     keep = np.array([0, 2, 3])
     np.testing.assert_array_equal(t_g[keep], t_o[keep])
-    assert 0 <= t_g[1] < 5000
+    n = int(n_o[1])
+    tl = ab.target_logits.cpu().numpy().astype(np.float64)
+    dl = ab.draft_logits.cpu().numpy().astype(np.float64)
+
+    def softmax(x):
+        e = np.exp(x - x.max())
+        return e / e.sum()
+    p = softmax(tl[4 + 1 + n])                       # request 1 owns target rows 5..9, draft rows 4..7
+    mass = np.maximum(p - softmax(dl[4 + n]), 0.0) if n < 4 else p
+    k = int(t_g[1])
+    assert 0 <= k < 5000 and mass[k] > 0, "the id drawn at the end of the CDF has no mass"
+    assert mass[k + 1:].sum() <= 1e-12 * mass.sum(), "the id drawn with u' = 1 - 2^-53 is not at the end of the CDF"
+    assert mass[int(t_o[1]) + 1:].sum() <= 1e-12 * mass.sum()
 
 
 @pytest.mark.parametrize("vocab", [6000, 5001])
@@ -1251,6 +1277,63 @@ def test_two_contexts_on_two_streams(ctx):
             assert torch.equal(got.view(torch.int16), want.view(torch.int16))
     finally:
         other.close()
+
+
+@pytest.mark.parametrize("M", [2, 4])
+def test_microbatches_on_two_streams_against_oracle(ctx, M):
+    """The one-GPU shadow of the speculation/verification pipeline of Sec. V-B, as bench.py --microbatches
+    issues it: the batch is cut into M micro-batches, two contexts on two streams, attention kernels chained
+    by events so that the acceptance of micro-batch m runs beside the attention of m+1.  Every micro-batch's
+    attention rows (tolerance) and accepted lengths / next tokens (bit for bit) against the oracle."""
+    import paper_2503_15921_amd as spin
+    cfg = si.CONFIGS["7b"]
+    b = si.make_verify_batch(cfg, BENCH_SEED, device="cuda")
+    t = b.table
+    ab = si.make_accept_batch(t.draft_len, cfg.vocab, cfg.logit_sigma, BENCH_SEED, device="cuda", rho=0.9)
+    tok = np.cumsum(t.prefix_len.astype(np.int64) + t.draft_len)
+    cuts = sorted({0, t.n_req, *[min(t.n_req, int(np.searchsorted(tok, tok[-1] * (m + 1) / M)) + 1) for m in range(M - 1)]})
+    assert len(cuts) == M + 1
+    other = spin.SpinContext(0)
+    try:
+        ctxs = [ctx, other]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        out = torch.full_like(b.q, float("nan"))
+        n_acc = torch.full((t.n_req,), -7, dtype=torch.int32, device="cuda")
+        nxt = torch.full((t.n_req,), -7, dtype=torch.int32, device="cuda")
+        mbs = []
+        for k, (i0, i1) in enumerate(zip(cuts[:-1], cuts[1:])):
+            r0, r1 = int(t.q_offset[i0]), int(t.q_offset[i1])
+            p0, p1 = int(t.pt_offset[i0]), int(t.pt_offset[i1])
+            c = ctxs[k % 2]
+            mbs.append(dict(ctx=c, stream=streams[k % 2], draft=t.draft_len[i0:i1],
+                            tab=c.make_table(t.prefix_len[i0:i1], t.draft_len[i0:i1], t.q_offset[i0:i1 + 1] - r0,
+                                             t.pt_offset[i0:i1 + 1] - p0, t.page_table[p0:p1]),
+                            q=b.q[r0:r1], out=out[r0:r1], tokens=ab.draft_tokens[r0:r1],
+                            target=ab.target_logits[r0 + i0:r1 + i1], dlogits=ab.draft_logits[r0:r1],
+                            u_acc=ab.u_accept[r0:r1], u_smp=ab.u_sample[i0:i1], n_acc=n_acc[i0:i1], nxt=nxt[i0:i1]))
+        attn_done = [torch.cuda.Event() for _ in mbs]
+        torch.cuda.synchronize()
+        for rep in range(3):            # several steps back to back: staging buffers and workspaces are reused
+            for k, mb in enumerate(mbs):
+                with torch.cuda.stream(mb["stream"]):
+                    if k > 0 or rep > 0:
+                        mb["stream"].wait_event(attn_done[k - 1])
+                    mb["ctx"].verify_attn(mb["tab"], b.k_pool, b.v_pool, mb["q"], mb["out"], cfg.n_q_heads, stream=mb["stream"])
+                    attn_done[k].record(mb["stream"])
+                    mb["ctx"].accept(spin.ACCEPT_REJECTION, mb["draft"], mb["tokens"], mb["target"], mb["dlogits"],
+                                     mb["u_acc"], mb["u_smp"], mb["n_acc"], mb["nxt"], stream=mb["stream"])
+        torch.cuda.synchronize()
+    finally:
+        other.close()
+    want = oracle_attention(b, 0.0)
+    for k, (i0, i1) in enumerate(zip(cuts[:-1], cuts[1:])):
+        r0, r1 = int(t.q_offset[i0]), int(t.q_offset[i1])
+        assert_close(out[r0:r1], want[r0:r1], f"micro-batch {k} of {M}")
+    n_o, t_o, margin = oracle_accept(spin.ACCEPT_REJECTION, ab)
+    assert margin.min() > 1e-9
+    np.testing.assert_array_equal(n_acc.cpu().numpy(), n_o)
+    np.testing.assert_array_equal(nxt.cpu().numpy(), t_o)
+    assert len(set(n_o.tolist())) >= 3
 
 
 def test_profile_sampling(ctx):
