@@ -258,6 +258,29 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
                 const double* u_sample_dev, int32_t* n_accepted_dev, int32_t* next_token_dev,
                 void* hip_stream);
 
+/* spin_accept for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  No context and no reservation: the row statistics live in a
+ * static device array of the library (SPIN_NOALLOC_MAX_STAT_ROWS x 16 bytes = 512 KiB, held by every GPU
+ * the library runs on until the process ends), and the call issues no hipMalloc / hipFree or any other
+ * allocating routine.  It runs on the calling thread's current HIP device; hip_stream must belong to it.
+ * Same arithmetic, kernels and outputs as spin_accept.  Differences in the arguments:
+ *   n_rows          host: R, the total number of draft rows
+ *   q_offset_dev    device int32 [n_req+1]: first draft row of each request (q_offset[0] = 0,
+ *                   q_offset[n_req] = n_rows, every difference >= 1).  The host cannot read it, so the kernel
+ *                   checks it: a request whose rows do not lie in [0, n_rows] gets n_accepted = next_token = -1.
+ * Limit: 2*n_rows + n_req <= SPIN_NOALLOC_MAX_STAT_ROWS (rejection or greedy alike), else SPIN_ENOSPC.
+ * Other errors: SPIN_EINVAL (null pointer, n_rows < n_req, unknown mode), SPIN_EUNSUPPORTED (vocab >
+ * 1048576), SPIN_EHIP.  No error text is kept (there is no context).
+ * All calls on one GPU share the one array, which keeps the previous call's contents (nothing in it has to
+ * start at zero: every statistics row a call reads it has written first): calls that overlap on one GPU
+ * -- two streams, two host threads -- race; order them on one stream or with events. */
+#define SPIN_NOALLOC_MAX_STAT_ROWS 32768
+int spin_accept_noalloc(int32_t mode, int32_t n_req, int32_t n_rows, const int32_t* q_offset_dev,
+                        const int32_t* draft_tokens_dev, const float* target_logits_dev,
+                        const float* draft_logits_dev, int32_t vocab, const double* u_accept_dev,
+                        const double* u_sample_dev, int32_t* n_accepted_dev, int32_t* next_token_dev,
+                        void* hip_stream);
+
 /* Verification of token trees, the companion of spin_verify_attn_tree.  Draft token t of request i hangs
  * below token parent_host[q_offset[i] + t] of the same request (an earlier token, or -1 = the last prefix
  * token); draft_len <= 64.  Target row q_offset[i] + i is the model's output after the prefix, row

@@ -5,7 +5,7 @@ C-ABI library built from csrc/.  PyTorch is used for device memory and streams. 
 CPU fallback: if libspin.so is missing, importing the entry points raises.
 """
 from .binding import (  # noqa: F401
-    SpinError, SpinContext, decompose, kv_padding, check_tiling, schedule, lib_path, load_library,
+    SpinError, SpinContext, accept_noalloc, decompose, kv_padding, check_tiling, schedule, lib_path, load_library,
     DECOMP_NONE, DECOMP_Q_SPLIT, DECOMP_KV_SPLIT, DECOMP_KV_SEARCH, ACCEPT_GREEDY, ACCEPT_REJECTION,
     EINVAL, ETABLE, ENOSPC, EUNSUPPORTED, EHIP, PIECE_CARRY_IN, PIECE_CARRY_OUT, PIECE_DIRECT, PIECE_QUEUED,
 )

@@ -65,7 +65,7 @@ class SpinError(RuntimeError):
 
 EXPORTS = ["spin_create", "spin_reserve", "spin_required", "spin_destroy", "spin_strerror",
            "spin_last_error", "spin_set_waves", "spin_decompose", "spin_kv_padding",
-           "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_verify_attn_tree", "spin_append_kv", "spin_accept", "spin_accept_tree",
+           "spin_check_tiling", "spin_schedule", "spin_verify_attn", "spin_verify_attn_tree", "spin_append_kv", "spin_accept", "spin_accept_noalloc", "spin_accept_tree",
            "spin_set_plan_reuse", "spin_profile_begin", "spin_profile_every", "spin_profile_end"]
 
 _lib = None
@@ -109,6 +109,7 @@ def load_library():
     lib.spin_accept.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_void_p, C.c_void_p,
                                 C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_void_p]
+    lib.spin_accept_noalloc.argtypes = [C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 4 + [C.c_int32] + [C.c_void_p] * 5
     lib.spin_accept_tree.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, _i32p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.spin_set_plan_reuse.argtypes = [C.c_void_p, C.c_int32]
@@ -217,6 +218,26 @@ def schedule(prefix_len, draft_len, subs, page_size: int, group: int, n_kv_heads
     _check(lib.spin_schedule(C.byref(t.struct), p, n, page_size, group, n_kv_heads, n_waves,
                              out.ctypes.data_as(C.POINTER(WorkPiece)), cnt.value, C.byref(cnt)))
     return out[: cnt.value].copy()
+
+
+def accept_noalloc(mode: int, q_offset_dev, draft_tokens, target_logits, draft_logits, u_accept, u_sample,
+                   n_accepted, next_token, n_rows: Optional[int] = None, stream=None) -> None:
+    """spin_accept_noalloc: spin_accept without a context and without any allocation.  q_offset_dev: torch
+    int32 device tensor [n_req+1]; the other tensors as in SpinContext.accept."""
+    import torch
+    lib = load_library()
+    n_req = q_offset_dev.shape[0] - 1
+    if n_rows is None:
+        n_rows = draft_tokens.shape[0]
+    dev = target_logits.device.index or 0
+    st = C.c_void_p(torch._C._cuda_getCurrentRawStream(dev) if stream is None else stream.cuda_stream)
+
+    def ptr(t):
+        return C.c_void_p(None if t is None else t.data_ptr())
+    with torch.cuda.device(dev):
+        _check(lib.spin_accept_noalloc(mode, n_req, n_rows, ptr(q_offset_dev), ptr(draft_tokens), ptr(target_logits),
+                                       ptr(draft_logits), target_logits.shape[-1], ptr(u_accept), ptr(u_sample),
+                                       ptr(n_accepted), ptr(next_token), st))
 
 
 def _dtype_code(t) -> int:

@@ -13,6 +13,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "spin_device.h"
 
 namespace spin {
@@ -322,6 +324,15 @@ __global__ __launch_bounds__(kFinishThreads) void accept_finish_kernel(AcceptPar
     const int base = r0 + req;                  // first target row of the request
     const int n_target = P.n_rows + P.n_req;
     const int V = P.vocab;
+    // Row offsets that came from the device (the entry point that allocates nothing cannot read them on
+    // the host) are checked here: a request whose rows do not lie inside the tensors reports -1, -1.
+    if (r0 < 0 || g < 1 || r0 + g > P.n_rows) {
+        if (tid == 0) {
+            P.n_accepted[req] = -1;
+            P.next_token[req] = -1;
+        }
+        return;
+    }
 
     if (tid < 256) s_tab[tid] = exp2((double)tid * (1.0 / 256.0));   // ready at the barrier below
     // ---- first-reject scan: wavefront 0 tests 64 draft rows at a time, one per lane
@@ -602,3 +613,79 @@ hipError_t launch_accept(const AcceptParams& p, hipStream_t stream, hipEvent_t e
 }
 
 }  // namespace spin
+
+// ------------------------------------------------------------------------------------------------
+// spin_accept for callers that cannot allocate (HIP graph capture, serving loops and harnesses that
+// forbid hipMalloc): the same two kernels, with the row statistics in a file-scope device array
+// instead of a context's workspace.  Every GPU holds its own copy of the array at its own address;
+// the address is looked up once per device and only that pointer is ever handed to HIP calls.
+namespace {
+
+constexpr int kStaticRows = SPIN_NOALLOC_MAX_STAT_ROWS;
+// per statistics row: float64 sum | float max | int32 arg-max
+static __device__ __align__(256) unsigned char scratch[(size_t)kStaticRows * 16];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];     // device address of `scratch` on each GPU, null until looked up
+std::mutex g_scratch_mutex;
+
+// Device address of the scratch array on the current device (looked up on the first call per device).
+hipError_t static_scratch(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
+namespace spin {
+hipError_t resolve_static_scratch() {
+    void* p = nullptr;
+    return static_scratch(&p);
+}
+}  // namespace spin
+
+extern "C" int spin_accept_noalloc(int32_t mode, int32_t n_req, int32_t n_rows, const int32_t* q_offset_dev,
+                                   const int32_t* draft_tokens_dev, const float* target_logits_dev,
+                                   const float* draft_logits_dev, int32_t vocab, const double* u_accept_dev,
+                                   const double* u_sample_dev, int32_t* n_accepted_dev, int32_t* next_token_dev,
+                                   void* hip_stream) {
+    if (mode != SPIN_ACCEPT_GREEDY && mode != SPIN_ACCEPT_REJECTION) return SPIN_EINVAL;
+    if (n_req < 0 || n_rows < 0 || vocab < 1) return SPIN_EINVAL;
+    if (vocab > spin::kMaxVocab) return SPIN_EUNSUPPORTED;
+    if (n_req == 0) return SPIN_OK;
+    if (n_rows < n_req) return SPIN_EINVAL;               // every request brings at least one draft token
+    if (2 * (int64_t)n_rows + n_req > kStaticRows) return SPIN_ENOSPC;
+    if (!q_offset_dev || !draft_tokens_dev || !target_logits_dev || !n_accepted_dev || !next_token_dev) return SPIN_EINVAL;
+    if (mode == SPIN_ACCEPT_REJECTION && (!draft_logits_dev || !u_accept_dev || !u_sample_dev)) return SPIN_EINVAL;
+    void* base = nullptr;
+    if (static_scratch(&base) != hipSuccess) return SPIN_EHIP;
+    spin::AcceptParams p = {};
+    p.row_off = q_offset_dev;
+    p.draft_tokens = draft_tokens_dev;
+    p.target_logits = target_logits_dev;
+    p.draft_logits = draft_logits_dev;
+    p.u_accept = u_accept_dev;
+    p.u_sample = u_sample_dev;
+    p.row_sum = (double*)base;
+    p.row_max = (float*)((char*)base + (size_t)kStaticRows * 8);
+    p.row_arg = (int32_t*)((char*)base + (size_t)kStaticRows * 12);
+    p.n_accepted = n_accepted_dev;
+    p.next_token = next_token_dev;
+    p.n_req = n_req;
+    p.n_rows = n_rows;
+    p.vocab = vocab;
+    p.mode = mode;
+    return spin::launch_accept(p, (hipStream_t)hip_stream, nullptr) == hipSuccess ? SPIN_OK : SPIN_EHIP;
+}

@@ -162,6 +162,7 @@ int spin_create(spin_ctx** out, int device_id) {
     for (int s = 0; s < kStages && ok; ++s)
         ok = hipEventCreateWithFlags(&c->ev[s], hipEventDisableTiming) == hipSuccess &&
              hipEventCreateWithFlags(&c->ev_done[s], hipEventDisableTiming) == hipSuccess;
+    ok = ok && spin::resolve_static_scratch() == hipSuccess;
     if (!ok) {
         spin_destroy(c);
         return SPIN_EHIP;

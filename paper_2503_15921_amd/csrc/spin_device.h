@@ -87,6 +87,10 @@ constexpr int kMaxVocab = 1 << 20;
 
 hipError_t launch_accept(const AcceptParams& p, hipStream_t stream, hipEvent_t ev_mid);
 
+// Look up, for the current device, the address of the static scratch array of spin_accept_noalloc (done by
+// spin_create so that the entry point's first call on a device finds it ready).
+hipError_t resolve_static_scratch();
+
 // Greedy walk down token trees; p is the (greedy-mode) parameter block of the row statistics, parent
 // [R] (device) the index of every draft token's parent within its request (-1: the last prefix token),
 // path [R] (device) receives the accepted nodes.
