@@ -12,6 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspin.so")
+PROBE_LIB = os.path.join(HERE, "libspin_probe.so")   # streaming-read probe of bench.py --calib-stream; not part of the product
 SOURCES = ["spin_host.cpp", "spin_ctx.hip", "spin_attn.hip", "spin_accept.hip"]
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions from scalar float code
@@ -45,6 +46,15 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    cmd = [hipcc, *HIP_FLAGS, "-shared", "-x", "hip", os.path.join(CSRC, "stream_probe.hip"), "-o", PROBE_LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    lines = [l for l in out.stdout.splitlines() if "is not a recognized feature for this target" not in l]
+    if lines and (verbose or out.returncode != 0):
+        print("\n".join(lines), flush=True)
+    if out.returncode != 0:
+        raise RuntimeError("hipcc failed")
     return LIB
 
 

@@ -57,6 +57,9 @@ struct spin_ctx {
     float* d_row_max = nullptr;    // acceptance row statistics
     double* d_row_sum = nullptr;
     int32_t* d_row_arg = nullptr;
+    int32_t* d_arrive = nullptr;   // per-request arrival counters of the acceptance kernels: zero between launches
+    double* d_draw_runs = nullptr; // run masses and last ids of the next-token draw
+    int32_t* d_draw_last = nullptr;
     // pinned staging ring
     char* h_stage[kStages] = {nullptr, nullptr, nullptr, nullptr};
     hipEvent_t ev[kStages] = {nullptr, nullptr, nullptr, nullptr};
@@ -112,11 +115,17 @@ void free_workspace(spin_ctx* c) {
     if (c->d_row_max) (void)hipFree(c->d_row_max);
     if (c->d_row_sum) (void)hipFree(c->d_row_sum);
     if (c->d_row_arg) (void)hipFree(c->d_row_arg);
+    if (c->d_arrive) (void)hipFree(c->d_arrive);
+    if (c->d_draw_runs) (void)hipFree(c->d_draw_runs);
+    if (c->d_draw_last) (void)hipFree(c->d_draw_last);
     for (int s = 0; s < kStages; ++s)
         if (c->h_stage[s]) (void)hipHostFree(c->h_stage[s]);
     c->d_part_o = c->d_part_ml = c->d_row_max = nullptr;
     c->d_row_sum = nullptr;
     c->d_row_arg = nullptr;
+    c->d_arrive = nullptr;
+    c->d_draw_runs = nullptr;
+    c->d_draw_last = nullptr;
     for (int s = 0; s < kStages; ++s) c->h_stage[s] = c->d_blob[s] = nullptr;
 }
 
@@ -241,6 +250,12 @@ int spin_reserve(spin_ctx* ctx, int64_t max_req, int64_t max_rows, int64_t max_p
     SPIN_TRY(hipMalloc((void**)&ctx->d_row_max, (size_t)stat_rows * 4));
     SPIN_TRY(hipMalloc((void**)&ctx->d_row_sum, (size_t)stat_rows * 8));
     SPIN_TRY(hipMalloc((void**)&ctx->d_row_arg, (size_t)stat_rows * 4));
+    SPIN_TRY(hipMalloc((void**)&ctx->d_arrive, (size_t)(max_req + 1) * 4));
+    SPIN_TRY(hipMemset(ctx->d_arrive, 0, (size_t)(max_req + 1) * 4));
+    size_t last_bytes = 0;
+    const size_t runs_bytes = spin::accept_draw_scratch_bytes(max_req + 1, &last_bytes);
+    SPIN_TRY(hipMalloc((void**)&ctx->d_draw_runs, runs_bytes));
+    SPIN_TRY(hipMalloc((void**)&ctx->d_draw_last, last_bytes));
     for (int s = 0; s < kStages; ++s) SPIN_TRY(hipHostMalloc((void**)&ctx->h_stage[s], blob, hipHostMallocMapped | hipHostMallocPortable));
 #undef SPIN_TRY
     ctx->blob_bytes = blob;
@@ -365,9 +380,11 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
         rc = next_stage(ctx, &h);
         if (rc) return rc;
         size_t off = 0;
+        bool overflow = false;   // a table that would not fit is not copied; checked after the last one
         auto put = [&](const void* src, size_t bytes) {
             const size_t at = off;
-            if (bytes) memcpy(h + off, src, bytes);
+            if (off + bytes > ctx->blob_bytes) overflow = true;
+            else if (bytes) memcpy(h + off, src, bytes);
             off = align16(off + bytes);
             return at;
         };
@@ -387,6 +404,7 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
         sp.off_tasks = put(plan.tasks.data(), plan.tasks.size() * 4);
         sp.off_pt = put(table->page_table, n_pages_used * 4);
         sp.off_tree = off;
+        if (overflow) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
         if (tree_mask) {
             if (off + (size_t)n_rows * 16 > ctx->blob_bytes) return fail(ctx, SPIN_ENOSPC, "internal: staging buffer too small");
             uint32_t* rec = (uint32_t*)(h + off);
@@ -619,10 +637,12 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     if (!draft_len_host) return fail(ctx, SPIN_EINVAL, "draft_len is null");
     ctx->row_off_host.resize(n_req + 1);
     int64_t rows = 0;
+    int32_t max_draft = 1;
     for (int32_t i = 0; i < n_req; ++i) {
         if (draft_len_host[i] < 1) return fail(ctx, SPIN_EINVAL, "draft_len < 1");
         ctx->row_off_host[i] = (int32_t)rows;
         rows += draft_len_host[i];
+        max_draft = std::max(max_draft, draft_len_host[i]);
         if (rows > INT32_MAX / 2) return fail(ctx, SPIN_EINVAL, "too many draft rows");
     }
     ctx->row_off_host[n_req] = (int32_t)rows;
@@ -663,6 +683,9 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     p.row_max = ctx->d_row_max;
     p.row_sum = ctx->d_row_sum;
     p.row_arg = ctx->d_row_arg;
+    p.arrive = ctx->d_arrive;
+    p.draw_runs = ctx->d_draw_runs;
+    p.draw_last = ctx->d_draw_last;
     p.n_accepted = n_accepted_dev;
     p.next_token = next_token_dev;
     p.n_req = n_req;
@@ -671,7 +694,7 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     p.mode = mode;
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_accept, ctx->prof_accept_used, ctx->prof_accept_seen);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    e = spin::launch_accept(p, stream, pe ? pe[1] : nullptr);
+    e = spin::launch_accept(p, max_draft, ctx->row_off_host.data(), stream, pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "acceptance launch");
     if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     e = hipEventRecord(ctx->ev[slot], stream);

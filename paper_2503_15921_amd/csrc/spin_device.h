@@ -76,16 +76,28 @@ struct AcceptParams {
     float* row_max;                // [2R+n_req] target rows first, then draft rows
     double* row_sum;
     int32_t* row_arg;
+    int32_t* arrive;               // [n_req] arrival counters (zero between launches), or null: the plain two-launch form
+    double* draw_runs;             // [n_req][512] run masses of the next-token draw, or null
+    int32_t* draw_last;            // [n_req][8] last id with mass of every part of the vocabulary
     int32_t* n_accepted;
     int32_t* next_token;
     int32_t n_req, n_rows, vocab, mode;
 };
 
-// ev_mid (may be null) is recorded between the two kernels.
+// ev_mid (may be null) is recorded after the first kernel.
 // Largest vocabulary the next-token search handles (its per-run sums live in LDS).
 constexpr int kMaxVocab = 1 << 20;
 
-hipError_t launch_accept(const AcceptParams& p, hipStream_t stream, hipEvent_t ev_mid);
+// Small vocabularies (with arrival counters p.arrive and the longest draft of the batch, max_draft >= 1): one
+// launch.  Otherwise the row statistics, then -- rejection mode with counters and the run table p.draw_runs --
+// the next-token draw spread over eight workgroups per request, else one workgroup per request.
+// row_off_host (may be null): the offsets p.row_off points at, as the host holds them; small batches pass
+// them to the kernel by value.
+hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* row_off_host, hipStream_t stream,
+                         hipEvent_t ev_mid);
+
+// Bytes of p.draw_runs (returned) and p.draw_last for batches of up to n_req requests.
+size_t accept_draw_scratch_bytes(int64_t n_req, size_t* last_bytes);
 
 // Look up, for the current device, the address of the static scratch array of spin_accept_noalloc (done by
 // spin_create so that the entry point's first call on a device finds it ready).

@@ -2,6 +2,8 @@
 // the tiling check and the work scheduler.  Integers only.
 #include <algorithm>
 #include <cstring>
+#include <iterator>
+#include <map>
 #include <string>
 #include <vector>
 
@@ -85,25 +87,52 @@ int check_tiling(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub
         if (subs[a].parent != subs[b].parent) return subs[a].parent < subs[b].parent;
         return a < b;
     });
+    // Per request: the pieces' visible cells must add up to the request's, and no two pieces may share a
+    // visible cell; with equal areas that makes the cover exact.  Overlaps are found by a sweep over the
+    // draft rows (n log n in the pieces of a request): every piece is first cut back to the rows and keys
+    // where it has visible cells at all -- keys below its last row's causal edge, rows from the first one
+    // that sees its first key -- after which two pieces share a visible cell exactly when their row ranges
+    // and their key ranges both intersect.  The pieces alive at a row are kept ordered by first key; they
+    // are pairwise disjoint, so a piece that enters need only be compared with its two neighbours.
+    struct Event {
+        int32_t row, enter, k0, k1;   // leave events (enter = 0) sort before enter events of the same row
+    };
+    std::vector<Event> events;
+    std::map<int32_t, int32_t> alive;  // first key -> end key
     int32_t pos = 0;
     for (int32_t i = 0; i < t->n_req; ++i) {
         int64_t p = t->prefix_len[i], g = t->draft_len[i];
         int64_t want = g * p + g * (g + 1) / 2;   // sum over rows of (p + t + 1)
         int64_t got = 0;
-        int32_t first = pos;
-        while (pos < n_sub && subs[idx[pos]].parent == i) got += visible_cells(subs[idx[pos++]], p);
-        // No two pieces may share a visible cell; with equal areas this makes the cover exact.
-        for (int32_t a = first; a < pos; ++a)
-            for (int32_t b = a + 1; b < pos; ++b) {
-                const spin_subreq &x = subs[idx[a]], &y = subs[idx[b]];
-                int64_t r0 = std::max(x.q_begin, y.q_begin);
-                int64_t r1 = std::min((int64_t)x.q_begin + x.q_len, (int64_t)y.q_begin + y.q_len);
-                int64_t k0 = std::max(x.kv_begin, y.kv_begin);
-                int64_t k1 = std::min((int64_t)x.kv_begin + x.kv_len, (int64_t)y.kv_begin + y.kv_len);
-                if (r0 < r1 && k0 < k1 && k0 < p + r1) {
-                    err = fmt("request %lld: sub-requests overlap", i); return SPIN_ETABLE;
-                }
+        events.clear();
+        alive.clear();
+        for (; pos < n_sub && subs[idx[pos]].parent == i; ++pos) {
+            const spin_subreq& s = subs[idx[pos]];
+            got += visible_cells(s, p);
+            const int64_t q_end = (int64_t)s.q_begin + s.q_len;
+            const int64_t k_end = std::min<int64_t>((int64_t)s.kv_begin + s.kv_len, p + q_end);
+            const int64_t q_first = std::max<int64_t>(s.q_begin, (int64_t)s.kv_begin - p);
+            if (k_end <= s.kv_begin || q_first >= q_end) continue;   // nothing visible in it
+            events.push_back({(int32_t)q_first, 1, s.kv_begin, (int32_t)k_end});
+            events.push_back({(int32_t)q_end, 0, s.kv_begin, (int32_t)k_end});
+        }
+        std::sort(events.begin(), events.end(), [](const Event& a, const Event& b) {
+            if (a.row != b.row) return a.row < b.row;
+            return a.enter < b.enter;
+        });
+        for (const Event& e : events) {
+            if (!e.enter) {
+                alive.erase(e.k0);
+                continue;
             }
+            auto next = alive.lower_bound(e.k0);
+            bool clash = next != alive.end() && next->first < e.k1;
+            if (!clash && next != alive.begin()) clash = std::prev(next)->second > e.k0;
+            if (clash) {
+                err = fmt("request %lld: sub-requests overlap", i); return SPIN_ETABLE;
+            }
+            alive.emplace(e.k0, e.k1);
+        }
         if (got != want) {
             err = fmt("request %lld: sub-requests cover %lld cells, not all of them", i, got);
             return SPIN_ETABLE;

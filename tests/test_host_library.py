@@ -121,6 +121,53 @@ def test_check_tiling_accepts_exact_and_rejects_broken():
     assert spin.check_tiling([p], [g], subs) == 0
 
 
+def test_check_tiling_against_a_cell_bitmap():
+    """Random sets of rectangles on small requests -- exact tilings with one rectangle moved, grown, shrunk or
+    doubled, and rectangles drawn at random -- judged by the library and by counting how often every visible
+    cell is covered."""
+    rng = np.random.default_rng(17)
+    n_ok = n_bad = 0
+    for case in range(600):
+        p, g = int(rng.integers(0, 12)), int(rng.integers(1, 7))
+        if case % 3 == 0:
+            rects = [tuple(int(x) for x in (rng.integers(0, g), 1, rng.integers(0, p + g), 1)) for _ in range(int(rng.integers(1, 6)))]
+            rects = [(qb, int(rng.integers(1, g - qb + 1)), kb, int(rng.integers(1, p + g - kb + 1))) for qb, _, kb, _ in rects]
+        else:
+            rects = list(random_rectangles(rng, p, g))
+            k = int(rng.integers(len(rects)))
+            qb, ql, kb, kl = rects[k]
+            what = int(rng.integers(5))
+            if what == 0 and kb + kl < p + g:
+                kl += 1
+            elif what == 1 and kl > 1:
+                kl -= 1
+            elif what == 2 and qb + ql < g:
+                ql += 1
+            elif what == 3 and kb > 0:
+                kb -= 1
+                kl += 1
+            rects[k] = (qb, ql, kb, kl)      # (what == 4 or an impossible move: left exact)
+        cover = np.zeros((g, p + g), dtype=np.int64)
+        for qb, ql, kb, kl in rects:
+            cover[qb:qb + ql, kb:kb + kl] += 1
+        exact = all((cover[t, :p + t + 1] == 1).all() for t in range(g))
+        subs = np.array([(0,) + tuple(r) for r in rects], dtype=np.int32)
+        assert (spin.check_tiling([p], [g], subs) == 0) == exact, (p, g, rects)
+        n_ok += exact
+        n_bad += not exact
+    assert n_ok > 50 and n_bad > 50
+
+
+def test_check_tiling_of_many_pieces_is_fast():
+    # a KV-split with a short length on long requests: ~10^5 pieces per request
+    import time
+    prefix = np.array([200000, 150000]); draft = np.array([4, 8])
+    subs = orc.decompose_kv_split(prefix, draft, 2)
+    t0 = time.perf_counter()
+    assert spin.check_tiling(prefix, draft, subs) == 0
+    assert time.perf_counter() - t0 < 2.0
+
+
 def blocks_of(piece, bk=32):
     return -(-int(piece[4]) // bk)
 
