@@ -687,7 +687,7 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
 
     // ====================================================================== computing wavefronts
     const int tile = wave;               // the row tile (16 rows of the strip) this wavefront owns
-    vec8 qf[KCALLS], qn[KCALLS];
+    vec8 qf[KCALLS];
     uint64_t anc_n = 0;                  // TREE: the next piece's ancestor mask and prefix length
     int pfx_n = 0;
     auto load_q = [&](const Piece& pc, vec8 (&q)[KCALLS]) {
@@ -712,9 +712,12 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
     fetch_piece(1, p1);
     int next_piece = 2;
     load_q(cp, qf);
+    // (reading the query registers here puts the wait for them in front of the loop: inside it no wait for a
+    // memory operation may follow a store, see below)
+#pragma unroll
+    for (int c = 0; c < KCALLS; ++c) asm volatile("" : "+v"(qf[c]));
     uint64_t anc = anc_n;                // TREE: draft keys (bit u = key prefix + u) this lane's row may see
     int pfx = __builtin_amdgcn_readfirstlane(pfx_n);
-    if (p1.k1 > p1.k0) load_q(p1, qn);   // the queries of a piece are requested one piece ahead
     f32x4 O[8];
     float m_run = kNegBig, l_run = 0.f;
     int blk = 0;                          // blocks of the share so far: block i sits in stage i & 1
@@ -736,11 +739,7 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
         const int full_end = TREE ? min(min(cp.k1, cp.causal0), pfx) : min(cp.k1, cp.causal0);
         const bool more = p1.k1 > p1.k0;
 
-        for (int kb = cp.k0; kb < cp.k1; kb += BK) {
-            __syncthreads();              // barrier blk + 3: the streamers have parked this block
-            const int st = blk & 1;
-            ++blk;
-            if (!active) continue;
+        auto block = [&](int kb, int st, bool last) {
             // The block as a whole -- scores of all four sub-blocks, one test of the exponent reference, all
             // exponentials, all of P.V -- in straight-line code, so that the LDS reads, matrix and vector
             // instructions of different sub-blocks overlap (this wavefront has its SIMD almost to itself
@@ -759,6 +758,9 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
                         S[sb][t] = E::mfma(a, qf[c], S[sb][t]);
                     }
             }
+            // The queries are no longer needed after the piece's last block: the next piece's are requested
+            // here, straight into the same registers, so that they arrive behind the rest of this block.
+            if (last) load_q(p1, qf);
             float sc[4][8];
 #pragma unroll
             for (int sb = 0; sb < 4; ++sb)
@@ -813,17 +815,31 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
 #pragma unroll
                 for (int jd = 0; jd < 8; ++jd)
                     O[jd] = E::mfma(__builtin_bit_cast(vec8, sVt[st][sb][jd][lane]), Pb[sb], O[jd]);
+        };
+        // All blocks but the last in a loop that holds no memory load, then the last one, which requests the
+        // next piece's queries: kept apart so that the wait for those queries is not carried into the loop
+        // (where, placed in front of the first use of the queries, it would follow the stores below).
+        int kb = cp.k0;
+        for (; kb + BK < cp.k1; kb += BK) {
+            __syncthreads();              // barrier blk + 3: the streamers have parked this block
+            if (active) block(kb, blk & 1, false);
+            ++blk;
         }
+        __syncthreads();
+        if (active) block(kb, blk & 1, true);
+        ++blk;
 
-        // The next piece's queries (requested when this piece began) are taken over BEFORE this piece's
-        // rows are stored: loads and stores share one in-order counter, and waiting for the queries after
-        // the stores would mean waiting for the stores.
-        if (more) {
+        // The next piece's queries must have ARRIVED before this piece's rows are stored: loads and stores
+        // share one in-order counter, so any wait for a load that comes after the stores is a wait for the
+        // stores -- several microseconds under a saturated read stream, more than the one block of slack this
+        // wavefront has before the streamers stall at the next barrier.  The empty statement below reads the
+        // query registers, which puts the wait for them here; after the stores this wavefront waits for no
+        // memory operation until the end of the next piece.
+        if (!active) load_q(p1, qf);
 #pragma unroll
-            for (int c = 0; c < KCALLS; ++c) qf[c] = qn[c];
-            anc = anc_n;
-            pfx = __builtin_amdgcn_readfirstlane(pfx_n);
-        }
+        for (int c = 0; c < KCALLS; ++c) asm volatile("" : "+v"(qf[c]));
+        anc = anc_n;
+        pfx = __builtin_amdgcn_readfirstlane(pfx_n);
         if (!(cp.head_flags & kPieceCarryOut) && active) {
             const int kvh = cp.head_flags & kPieceHeadMask;
             float l = l_run;
@@ -858,7 +874,6 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
         if (!more) break;
         cp = p1;
         fetch_piece(next_piece++, p1);
-        if (p1.k1 > p1.k0) load_q(p1, qn);
     }
 }
 

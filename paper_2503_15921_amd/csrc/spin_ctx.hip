@@ -503,6 +503,7 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.page_shift = pshift;
     ap.tree_rows = tree_mask ? (const uint32_t*)(blob + sp.off_tree) : nullptr;
     ap.scale_log2 = scale * 1.4426950408889634f;
+
     const spin::Piece* pieces_dev[3];
     const int32_t* waves_dev[3];
     for (int c = 0; c < 3; ++c) {
