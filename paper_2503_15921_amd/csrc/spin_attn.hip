@@ -38,6 +38,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include "spin_device.h"
 
@@ -85,8 +86,27 @@ __device__ __forceinline__ u32x4 stream_load(const char* base, uint32_t byte_off
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + byte_off));
 }
 
+// Where the tables of a small call sit: in the argument segment, behind the parameter block of type Params.
+template <class Params>
+__device__ __forceinline__ const char* inline_tables_base() {
+    return (const char*)__builtin_amdgcn_kernarg_segment_ptr() + ((sizeof(Params) + 15) & ~(size_t)15);
+}
+template <class T>
+__device__ __forceinline__ void rebase(const T*& p, const char* base) {
+    p = (const T*)(base + (uintptr_t)p);
+}
+
+template <bool TREE>
+__device__ __forceinline__ void use_inline_tables(AttnParams& P) {
+    const char* base = inline_tables_base<AttnParams>();
+    rebase(P.pieces, base);
+    rebase(P.wave_begin, base);
+    rebase(P.page_table, base);
+    if (TREE) rebase(P.tree_rows, base);
+}
+
 template <int D, int NT, bool TREE, class E>
-__global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
+__device__ __forceinline__ void verify_attn_body(const AttnParams& P) {
     typedef typename E::vec8 vec8;
     constexpr int DCH = D / 8;      // 16-byte chunks per key row
     constexpr int KCALLS = D / 32;  // MFMA calls (32 head dims each) per 16-key score tile
@@ -482,6 +502,17 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
     }
 }
 
+template <int D, int NT, bool TREE, class E>
+__global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
+    verify_attn_body<D, NT, TREE, E>(P);
+}
+// the same with the tables of the call in the kernel arguments (small calls)
+template <int D, int NT, bool TREE, class E>
+__global__ __launch_bounds__(64) void verify_attn_small_kernel(AttnParams P, InlineTables) {
+    use_inline_tables<TREE>(P);
+    verify_attn_body<D, NT, TREE, E>(P);
+}
+
 // Grouped-query variant: with G query heads per KV head a strip has up to 64 (draft row x query
 // head) rows, four MFMA column tiles, whose arithmetic per key a single wavefront cannot hide behind
 // its own loads.  A workgroup of eight wavefronts (one per CU, two per SIMD) therefore splits the
@@ -501,7 +532,7 @@ __global__ __launch_bounds__(64) void verify_attn_kernel(AttnParams P) {
 constexpr int kGroupWaves = 8;
 
 template <int D, bool TREE, class E>
-__global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void verify_attn_group_kernel(AttnParams P) {
+__device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
     typedef typename E::vec8 vec8;
     constexpr int DCH = D / 8;
     constexpr int KCALLS = D / 32;
@@ -877,6 +908,16 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
     }
 }
 
+template <int D, bool TREE, class E>
+__global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void verify_attn_group_kernel(AttnParams P) {
+    verify_attn_group_body<D, TREE, E>(P);
+}
+template <int D, bool TREE, class E>
+__global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void verify_attn_group_small_kernel(AttnParams P, InlineTables) {
+    use_inline_tables<TREE>(P);
+    verify_attn_group_body<D, TREE, E>(P);
+}
+
 // Join the partial results of one (request, KV head): Eq. (13) -- one denominator over all tokens
 // of the original request.  With piece s holding (m_s, l_s, N_s) where l_s = sum of exp2(score -
 // m_s) and N_s the matching weighted value sum:  O = sum_s 2^(m_s-M) N_s / sum_s 2^(m_s-M) l_s.
@@ -887,7 +928,7 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
 constexpr int kJoinWaves = 4;
 
 template <int D, class E>
-__global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinParams P) {
+__device__ __forceinline__ void join_partials_body(const JoinParams& P) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int req = P.tasks[2 * blockIdx.x], kvh = P.tasks[2 * blockIdx.x + 1];
     const int G = P.group;
@@ -933,6 +974,21 @@ __global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinPara
     }
 }
 
+template <int D, class E>
+__global__ __launch_bounds__(64 * kJoinWaves) void join_partials_kernel(JoinParams P) {
+    join_partials_body<D, E>(P);
+}
+template <int D, class E>
+__global__ __launch_bounds__(64 * kJoinWaves) void join_partials_small_kernel(JoinParams P, InlineTables) {
+    const char* base = inline_tables_base<JoinParams>();
+    rebase(P.pieces, base);
+    rebase(P.ppos, base);
+    rebase(P.strip_begin, base);
+    rebase(P.q_offset, base);
+    rebase(P.tasks, base);
+    join_partials_body<D, E>(P);
+}
+
 // Scatter the draft tokens' K and V rows into their page slots: one workgroup per packed row, 16
 // bytes per lane and step, over all KV heads of K and then of V.
 __global__ __launch_bounds__(256) void append_kv_kernel(AppendParams P) {
@@ -959,7 +1015,10 @@ hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
 }
 
 template <int D, bool TREE, class E>
-static const void* attn_kernel_ptr(int cls) {
+static const void* attn_kernel_ptr(int cls, bool small = false) {
+    if (small)
+        return cls == 0 ? (const void*)verify_attn_small_kernel<D, 1, TREE, E>
+             : cls == 1 ? (const void*)verify_attn_small_kernel<D, 2, TREE, E> : (const void*)verify_attn_group_small_kernel<D, TREE, E>;
     return cls == 0 ? (const void*)verify_attn_kernel<D, 1, TREE, E>
          : cls == 1 ? (const void*)verify_attn_kernel<D, 2, TREE, E> : (const void*)verify_attn_group_kernel<D, TREE, E>;
 }
@@ -985,7 +1044,7 @@ template <int D, class E>
 static hipError_t launch_attn_d(const AttnParams& base, const Piece* const pieces_dev[3],
                                 const int32_t* const wave_begin_dev[3], const int32_t n_waves[3],
                                 const int32_t n_queued[3], int32_t* queues_dev, const JoinParams& jp,
-                                hipStream_t stream, hipEvent_t ev_mid) {
+                                const InlineTables* tables, hipStream_t stream, hipEvent_t ev_mid) {
     for (int cls = 0; cls < 3; ++cls) {
         if (n_waves[cls] <= 0) continue;
         AttnParams p = base;
@@ -994,9 +1053,11 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         p.queue = queues_dev + cls;
         p.n_queued = n_queued[cls];
         if (cls == 2 && p.n_queued != 0) return hipErrorInvalidValue;   // the grouped-query kernel takes no queued chunks
+        if (p.inline_tables && p.n_queued != 0) return hipErrorInvalidValue;   // the chunk queue needs device memory
         dim3 grid((unsigned)n_waves[cls]);
-        void* args[] = {&p};
-        const void* fn = p.tree_rows ? attn_kernel_ptr<D, true, E>(cls) : attn_kernel_ptr<D, false, E>(cls);
+        void* args[] = {&p, (void*)tables};
+        const bool small = p.inline_tables != 0;
+        const void* fn = p.tree_rows ? attn_kernel_ptr<D, true, E>(cls, small) : attn_kernel_ptr<D, false, E>(cls, small);   // (an offset when inline, never zero)
         hipError_t e = hipLaunchKernel(fn, grid, dim3(cls == 2 ? 64 * kGroupWaves : 64), args, 0, stream);
         if (e != hipSuccess) return e;
     }
@@ -1006,7 +1067,8 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
     }
     if (jp.n_tasks > 0) {
         const int pair_groups = (jp.max_pairs + kJoinWaves - 1) / kJoinWaves;
-        hipLaunchKernelGGL((join_partials_kernel<D, E>), dim3(jp.n_tasks, pair_groups), dim3(64 * kJoinWaves), 0, stream, jp);
+        if (jp.inline_tables) hipLaunchKernelGGL((join_partials_small_kernel<D, E>), dim3(jp.n_tasks, pair_groups), dim3(64 * kJoinWaves), 0, stream, jp, *tables);
+        else hipLaunchKernelGGL((join_partials_kernel<D, E>), dim3(jp.n_tasks, pair_groups), dim3(64 * kJoinWaves), 0, stream, jp);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -1015,13 +1077,23 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
 
 hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Piece* const pieces_dev[3],
                        const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
-                       int32_t* queues_dev, const JoinParams& jp, hipStream_t stream, hipEvent_t ev_mid) {
+                       int32_t* queues_dev, const JoinParams& jp, const void* inline_tables, size_t inline_bytes,
+                       hipStream_t stream, hipEvent_t ev_mid) {
+    InlineTables storage;
+    const InlineTables* tables = nullptr;
+    if (inline_tables) {
+        if (inline_bytes > kInlineTableBytes || !base.inline_tables) return hipErrorInvalidValue;
+        memcpy(storage.bytes, inline_tables, inline_bytes);
+        tables = &storage;
+    } else if (base.inline_tables || jp.inline_tables) {
+        return hipErrorInvalidValue;
+    }
     if (head_dim == 128)
-        return f16 ? launch_attn_d<128, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid)
-                   : launch_attn_d<128, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid);
+        return f16 ? launch_attn_d<128, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, ev_mid)
+                   : launch_attn_d<128, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, ev_mid);
     if (head_dim == 64)
-        return f16 ? launch_attn_d<64, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid)
-                   : launch_attn_d<64, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, stream, ev_mid);
+        return f16 ? launch_attn_d<64, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, ev_mid)
+                   : launch_attn_d<64, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, ev_mid);
     return hipErrorInvalidValue;
 }
 

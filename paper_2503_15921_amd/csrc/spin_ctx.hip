@@ -23,7 +23,8 @@ inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 struct StagedPlan {
     bool valid = false;
     int slot = -1;                  // ring slot holding the tables; kept out of the rotation while valid
-    bool in_place = false;          // read by the kernels from the pinned buffer, not copied
+    bool in_place = false;          // small tables: passed to the kernels in their arguments, not copied to the device
+    size_t bytes = 0;               // size of the staged tables
     // key
     int32_t page_size = 0, n_kv_heads = 0, head_dim = 0, n_pages = 0, n_q_heads = 0, n_sub = -1;
     int32_t waves[3] = {0, 0, 0};
@@ -129,7 +130,7 @@ void free_workspace(spin_ctx* c) {
     for (int s = 0; s < kStages; ++s) c->h_stage[s] = c->d_blob[s] = nullptr;
 }
 
-constexpr size_t kInPlaceBytes = 4096;   // tables up to this size are read by the kernels where the host wrote them
+constexpr size_t kInPlaceBytes = spin::kInlineTableBytes;   // tables up to this size travel in the kernel arguments
 constexpr int kMaxWaves = 16384;   // wavefronts per launch the staging buffers are sized for
 
 // pieces | per-class wavefront ranges | (strip, head) piece ranges | strip ranges | row offsets | tasks | page table
@@ -425,10 +426,11 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
         // Upload on the context's own stream so that it runs beside the kernels of earlier calls; the
         // caller's stream only waits for it.  d_blob[slot] is free once the kernels of the call that
         // last used it are done.
-        // Small tables (a few requests) are not copied at all: the kernels read them from the pinned,
-        // device-mapped staging buffer, which saves the host four runtime calls and the stream a
-        // dependency on another stream -- what counts when the whole step takes tens of microseconds.
+        // Small tables (a few requests) are not copied at all: they go into the kernels' arguments, which
+        // saves the host four runtime calls, the stream a dependency on another stream and the kernels
+        // their first round trips to memory -- what counts when the whole step takes tens of microseconds.
         sp.slot = ctx->stage;
+        sp.bytes = off;
         sp.in_place = off <= kInPlaceBytes && sp.n_queued[0] + sp.n_queued[1] + sp.n_queued[2] == 0;
         if (!sp.in_place) {
             if (ctx->done_pending[sp.slot]) {
@@ -469,13 +471,9 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
 
     // ---- launch
     const int slot = sp.slot;
-    char* blob = ctx->d_blob[slot];
-    if (sp.in_place) {
-        void* mapped = nullptr;
-        e = hipHostGetDevicePointer(&mapped, ctx->h_stage[slot], 0);
-        if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
-        blob = (char*)mapped;
-    } else {
+    // (with inline tables the table pointers below are offsets into the kernels' inline-table argument)
+    const uintptr_t blob = sp.in_place ? 0 : (uintptr_t)ctx->d_blob[slot];
+    if (!sp.in_place) {
         e = hipStreamWaitEvent(stream, ctx->ev[slot], 0);   // the upload (long done on a hit)
         if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
     }
@@ -503,6 +501,7 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     ap.page_shift = pshift;
     ap.tree_rows = tree_mask ? (const uint32_t*)(blob + sp.off_tree) : nullptr;
     ap.scale_log2 = scale * 1.4426950408889634f;
+    ap.inline_tables = sp.in_place ? 1 : 0;
 
     const spin::Piece* pieces_dev[3];
     const int32_t* waves_dev[3];
@@ -524,18 +523,15 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     jp.group = group;
     jp.n_tasks = sp.n_tasks;
     jp.max_pairs = sp.max_pairs;
+    jp.inline_tables = sp.in_place ? 1 : 0;
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used, ctx->prof_attn_seen);
     if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     e = spin::launch_attn(kv->head_dim, kv->dtype == SPIN_DTYPE_F16, ap, pieces_dev, waves_dev, sp.n_waves_launch, sp.n_queued,
-                          (int32_t*)(blob + sp.off_queues), jp, stream, pe ? pe[1] : nullptr);
+                          (int32_t*)(blob + sp.off_queues), jp, sp.in_place ? ctx->h_stage[slot] : nullptr, sp.bytes, stream,
+                          pe ? pe[1] : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
     if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    if (sp.in_place) {
-        // the staging buffer is free again once the kernels that read it are done
-        e = hipEventRecord(ctx->ev[slot], stream);
-        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-        ctx->ev_pending[slot] = true;
-    } else {
+    if (!sp.in_place) {   // (tables passed in the arguments were copied at the launch: their staging buffer is free at once)
         e = hipEventRecord(ctx->ev_done[slot], stream);
         if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
         ctx->done_pending[slot] = true;

@@ -14,45 +14,57 @@ namespace spin {
 // the head dim; head dim 64 uses the first 8 chunks.
 constexpr int kPartRow = 128;
 
+// Tables of a small call (a handful of requests) travel in the kernel arguments instead of device memory:
+// the pointer fields marked (*) then hold byte offsets into this block, which follows the parameter block in
+// the argument segment, and the kernels turn them into addresses there.
+constexpr size_t kInlineTableBytes = 3840;
+struct alignas(16) InlineTables {
+    char bytes[kInlineTableBytes];
+};
+
 struct AttnParams {
     const uint16_t* k_pool;
     const uint16_t* v_pool;
     const uint16_t* q;
-    const Piece* pieces;         // pieces of one column-tile class, in streaming order
-    const int32_t* wave_begin;   // [n_shares + 1] pieces of each share: gridDim.x per-wavefront shares, then queued chunks
+    const Piece* pieces;         // (*) pieces of one column-tile class, in streaming order
+    const int32_t* wave_begin;   // (*) [n_shares + 1] pieces of each share: gridDim.x per-wavefront shares, then queued chunks
     int32_t* queue;              // next queued chunk to hand out (zero at launch)
     int32_t n_queued;
-    const int32_t* page_table;
+    const int32_t* page_table;   // (*)
     float* part_o;               // [slots][kPartRow]
     float* part_ml;              // [slots][2]: running max (log2 domain), sum
     uint16_t* o;                 // final rows of pieces flagged direct
-    const uint32_t* tree_rows;   // tree-shaped drafts only, else null: [R][4] = ancestor mask (low, high), prefix length, 0
+    const uint32_t* tree_rows;   // (*) tree-shaped drafts only, else null: [R][4] = ancestor mask (low, high), prefix length, 0
     int64_t page_stride, head_stride, token_stride;   // elements
     int32_t n_q_heads, n_kv_heads, group, page_shift;
     float scale_log2;            // softmax scale * log2(e)
+    int32_t inline_tables;       // the (*) fields are offsets into the InlineTables argument
 };
 
 struct JoinParams {
-    const Piece* pieces;         // all classes
-    const int32_t* ppos;         // [n_strips * n_kv_heads][2] first piece and count of each (strip, KV head)
-    const int32_t* strip_begin;  // [n_req + 1]
-    const int32_t* q_offset;     // [n_req + 1]
-    const int32_t* tasks;        // [n_tasks][2] (request, KV head)
+    const Piece* pieces;         // (*) all classes
+    const int32_t* ppos;         // (*) [n_strips * n_kv_heads][2] first piece and count of each (strip, KV head)
+    const int32_t* strip_begin;  // (*) [n_req + 1]
+    const int32_t* q_offset;     // (*) [n_req + 1]
+    const int32_t* tasks;        // (*) [n_tasks][2] (request, KV head)
     const float* part_o;
     const float* part_ml;
     uint16_t* o;
     int32_t n_q_heads, n_kv_heads, group, n_tasks;
     int32_t max_pairs;           // largest (draft rows x group) of any request
+    int32_t inline_tables;       // the (*) fields are offsets into the InlineTables argument
 };
 
 // Wavefronts of the attention kernel of class `cls` (0, 1, 2) and head dim that fit on the device at once.
 hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves);
 
 // n_waves[c] wavefronts stream the pieces of class c; ev_mid (may be null) is recorded between the
-// attention kernels and the join kernel.
+// attention kernels and the join kernel.  inline_tables (may be null): the tables themselves, at most
+// kInlineTableBytes of them, to be passed in the kernel arguments (base.inline_tables / jp.inline_tables set).
 hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Piece* const pieces_dev[3],
                        const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
-                       int32_t* queues_dev, const JoinParams& jp, hipStream_t stream, hipEvent_t ev_mid);
+                       int32_t* queues_dev, const JoinParams& jp, const void* inline_tables, size_t inline_bytes,
+                       hipStream_t stream, hipEvent_t ev_mid);
 
 struct AppendParams {
     const int64_t* dst_slot;   // [R] page * page_size + slot of every packed row
