@@ -117,8 +117,10 @@ __device__ __forceinline__ void verify_attn_body(const AttnParams& P) {
     __shared__ int32_t sPT[3][PTR * 64];   // page ids of the current piece and the two after it
     // Finished rows wait here until the share ends (or the space runs out) and leave together: a store
     // into global memory in the middle of the stream would hold up every load issued after it.
-    // Units of 4 KiB per column tile: final rows take one ([4][64] x 16 bytes), partial rows two
-    // ([8][64] x 16 bytes).
+    // Units of 4 KiB per column tile: final rows take one ([4][64] x 16 bytes); partial rows wait as the raw
+    // fp32 accumulators, two units ([8][64] x 16 bytes), and are turned into what the join kernel reads -- the
+    // row normalised by its own sum, IEEE half precision whatever the element type, next to its (maximum,
+    // sum) pair -- when they leave, after the wavefront's stream has ended.
     static_assert(NT <= 2, "result staging is laid out for at most two column tiles");
     constexpr int kStageUnits = 6, kStageEntries = 6;
     __shared__ u32x4 sStage[kStageUnits * 256];
@@ -155,18 +157,23 @@ __device__ __forceinline__ void verify_attn_body(const AttnParams& P) {
                     }
                     unit += 1;
                 } else {
-                    // partial rows, stored as [jd][16] so that each lane writes 16 contiguous bytes;
-                    // the join kernel undoes the permutation
                     if (tl < n_q) {
                         const int64_t slot = (int64_t)out_base + nn;
-                        float* po = P.part_o + slot * kPartRow;
+                        const float m = sStageML[e][nn * 2], l = sStageML[e][nn * 2 + 1];
+                        const float inv = l > 0.f ? 1.0f / l : 0.f;      // (a row that saw no key: all zero, weight zero)
                         if (g * 4 < DCH) {
+                            f32x4 o[8];
 #pragma unroll
-                            for (int jd = 0; jd < 8; ++jd) *(u32x4*)(po + jd * 16 + g * 4) = src[jd * 64];
+                            for (int jd = 0; jd < 8; ++jd) o[jd] = __builtin_bit_cast(f32x4, src[jd * 64]);
+                            uint16_t* op = P.part_o + slot * kPartRow + g * 32;
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                *(u32x4*)(op + r * 8) = u32x4{F16::pack(o[0][r] * inv, o[1][r] * inv), F16::pack(o[2][r] * inv, o[3][r] * inv),
+                                                              F16::pack(o[4][r] * inv, o[5][r] * inv), F16::pack(o[6][r] * inv, o[7][r] * inv)};
                         }
                         if (g == 0) {
-                            P.part_ml[slot * 2] = sStageML[e][nn * 2];
-                            P.part_ml[slot * 2 + 1] = sStageML[e][nn * 2 + 1];
+                            P.part_ml[slot * 2] = m;
+                            P.part_ml[slot * 2 + 1] = l;
                         }
                     }
                     unit += 2;
@@ -877,8 +884,8 @@ __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
             l += __shfl_xor(l, 16);
             l += __shfl_xor(l, 32);
             if (tl < cp.n_q) {
+                const float inv = l > 0.f ? 1.0f / l : 0.f;      // (a partial row that saw no key: all zero, weight zero)
                 if (cp.head_flags & kPieceDirect) {
-                    const float inv = 1.0f / l;
                     uint16_t* op = P.o + ((int64_t)(cp.q_row0 + tl) * P.n_q_heads + kvh * G + hg) * D + g * 32;
                     if (g * 4 < DCH) {
 #pragma unroll
@@ -889,11 +896,16 @@ __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
                         }
                     }
                 } else {
+                    // a partial row: normalised by its own sum, as half precision, next to (maximum, sum)
                     const int64_t slot = (int64_t)cp.out_base + nn;
-                    float* po = P.part_o + slot * kPartRow;
+                    uint16_t* po = P.part_o + slot * kPartRow + g * 32;
                     if (g * 4 < DCH) {
 #pragma unroll
-                        for (int jd = 0; jd < 8; ++jd) *(f32x4*)(po + jd * 16 + g * 4) = O[jd];
+                        for (int r = 0; r < 4; ++r) {
+                            u32x4 w = {F16::pack(O[0][r] * inv, O[1][r] * inv), F16::pack(O[2][r] * inv, O[3][r] * inv),
+                                       F16::pack(O[4][r] * inv, O[5][r] * inv), F16::pack(O[6][r] * inv, O[7][r] * inv)};
+                            *(u32x4*)(po + r * 8) = w;
+                        }
                     }
                     if (g == 0) {
                         P.part_ml[slot * 2] = m_run;
@@ -919,12 +931,11 @@ __global__ __launch_bounds__(64 * kGroupWaves) __attribute__((amdgpu_waves_per_e
 }
 
 // Join the partial results of one (request, KV head): Eq. (13) -- one denominator over all tokens
-// of the original request.  With piece s holding (m_s, l_s, N_s) where l_s = sum of exp2(score -
-// m_s) and N_s the matching weighted value sum:  O = sum_s 2^(m_s-M) N_s / sum_s 2^(m_s-M) l_s.
-// One wavefront per (task, draft row, query head of the group).
-// Lane (chunk, jp) owns head dims chunk*8 + 2*jp and +1, which the attention kernel left at
-// partial elements (2*jp)*16 + chunk and (2*jp+1)*16 + chunk.  Rows whose pieces were all
-// written directly have no partial result and are left alone.
+// of the original request.  Piece s left (m_s, l_s, O_s): l_s = sum of exp2(score - m_s) over its keys and
+// O_s its own normalised output (half precision):  O = sum_s w_s O_s / sum_s w_s,  w_s = 2^(m_s-M) l_s.
+// One wavefront per (task, draft row, query head of the group); lane (chunk, jp) owns head dims
+// chunk*8 + 2*jp and +1.  Rows whose pieces were all written directly have no partial result and are
+// left alone.
 constexpr int kJoinWaves = 4;
 
 template <int D, class E>
@@ -935,7 +946,7 @@ __device__ __forceinline__ void join_partials_body(const JoinParams& P) {
     const int row0 = P.q_offset[req], n_rows = P.q_offset[req + 1] - row0;
     const int sb = P.strip_begin[req], se = P.strip_begin[req + 1];
     const int chunk = lane & 15, jp = lane >> 4;
-    const int e0 = (2 * jp) * 16 + chunk;
+    const int e0 = chunk * 8 + 2 * jp;
     const bool active = chunk * 8 < D;
 
     {
@@ -955,12 +966,12 @@ __device__ __forceinline__ void join_partials_body(const JoinParams& P) {
                 if (pc.head_flags & (kPieceCarryOut | kPieceDirect)) continue;
                 const int64_t slot = (int64_t)pc.out_base + tl * G + hg;
                 const float m = P.part_ml[slot * 2], l = P.part_ml[slot * 2 + 1];
-                const float o0 = P.part_o[slot * kPartRow + e0], o1 = P.part_o[slot * kPartRow + e0 + 16];
+                const f16x2 o = __builtin_bit_cast(f16x2, *(const uint32_t*)(P.part_o + slot * kPartRow + e0));
                 const float Mn = fmaxf(M, m);
-                const float a = fast_exp2(M - Mn), b = fast_exp2(m - Mn);
-                den = den * a + l * b;
-                n0 = n0 * a + o0 * b;
-                n1 = n1 * a + o1 * b;
+                const float a = fast_exp2(M - Mn), b = fast_exp2(m - Mn) * l;
+                den = den * a + b;
+                n0 = n0 * a + (float)o[0] * b;
+                n1 = n1 * a + (float)o[1] * b;
                 M = Mn;
                 any = true;
             }

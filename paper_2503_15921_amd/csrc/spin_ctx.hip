@@ -53,7 +53,7 @@ struct spin_ctx {
     hipStream_t copy_stream = nullptr;   // table uploads run here, beside the previous call's kernels
     hipEvent_t ev_done[kStages] = {nullptr, nullptr, nullptr, nullptr};   // kernels reading d_blob[s] have finished
     bool done_pending[kStages] = {false, false, false, false};
-    float* d_part_o = nullptr;
+    uint16_t* d_part_o = nullptr;
     float* d_part_ml = nullptr;
     float* d_row_max = nullptr;    // acceptance row statistics
     double* d_row_sum = nullptr;
@@ -121,7 +121,8 @@ void free_workspace(spin_ctx* c) {
     if (c->d_draw_last) (void)hipFree(c->d_draw_last);
     for (int s = 0; s < kStages; ++s)
         if (c->h_stage[s]) (void)hipHostFree(c->h_stage[s]);
-    c->d_part_o = c->d_part_ml = c->d_row_max = nullptr;
+    c->d_part_o = nullptr;
+    c->d_part_ml = c->d_row_max = nullptr;
     c->d_row_sum = nullptr;
     c->d_row_arg = nullptr;
     c->d_arrive = nullptr;
@@ -246,7 +247,7 @@ int spin_reserve(spin_ctx* ctx, int64_t max_req, int64_t max_rows, int64_t max_p
         }                                                \
     } while (0)
     for (int s = 0; s < kStages; ++s) SPIN_TRY(hipMalloc((void**)&ctx->d_blob[s], blob));
-    SPIN_TRY(hipMalloc((void**)&ctx->d_part_o, std::max<size_t>(16, (size_t)max_part_slots * spin::kPartRow * 4)));
+    SPIN_TRY(hipMalloc((void**)&ctx->d_part_o, std::max<size_t>(16, (size_t)max_part_slots * spin::kPartRow * 2)));
     SPIN_TRY(hipMalloc((void**)&ctx->d_part_ml, std::max<size_t>(16, (size_t)max_part_slots * 2 * 4)));
     SPIN_TRY(hipMalloc((void**)&ctx->d_row_max, (size_t)stat_rows * 4));
     SPIN_TRY(hipMalloc((void**)&ctx->d_row_sum, (size_t)stat_rows * 8));

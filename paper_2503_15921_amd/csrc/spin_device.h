@@ -10,8 +10,7 @@
 
 namespace spin {
 
-// Floats per partial output row: 8 (head dim within a 16-byte chunk) x 16 (chunk), whatever
-// the head dim; head dim 64 uses the first 8 chunks.
+// Elements (IEEE half precision) per partial output row, whatever the head dim; head dim 64 uses the first 64.
 constexpr int kPartRow = 128;
 
 // Tables of a small call (a handful of requests) travel in the kernel arguments instead of device memory:
@@ -31,7 +30,7 @@ struct AttnParams {
     int32_t* queue;              // next queued chunk to hand out (zero at launch)
     int32_t n_queued;
     const int32_t* page_table;   // (*)
-    float* part_o;               // [slots][kPartRow]
+    uint16_t* part_o;            // [slots][kPartRow] partial rows, each normalised by its own sum, half precision
     float* part_ml;              // [slots][2]: running max (log2 domain), sum
     uint16_t* o;                 // final rows of pieces flagged direct
     const uint32_t* tree_rows;   // (*) tree-shaped drafts only, else null: [R][4] = ancestor mask (low, high), prefix length, 0
@@ -47,7 +46,7 @@ struct JoinParams {
     const int32_t* strip_begin;  // (*) [n_req + 1]
     const int32_t* q_offset;     // (*) [n_req + 1]
     const int32_t* tasks;        // (*) [n_tasks][2] (request, KV head)
-    const float* part_o;
+    const uint16_t* part_o;
     const float* part_ml;
     uint16_t* o;
     int32_t n_q_heads, n_kv_heads, group, n_tasks;
