@@ -537,6 +537,13 @@ __global__ __launch_bounds__(64) void verify_attn_small_kernel(AttnParams P, Inl
 // loads of the computing wavefronts never sit between a streamer's load and its wait.  Both kinds
 // walk the same list of pieces of the workgroup's share; every K/V byte is fetched from HBM once.
 constexpr int kGroupWaves = 8;
+#if defined(SPIN_X_ST_NT)
+#define SPIN_ROW_STORE(p, w) asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(w) : "memory")
+#elif defined(SPIN_X_ST_PLAIN)
+#define SPIN_ROW_STORE(p, w) (*(u32x4*)(p) = (w))
+#else
+#define SPIN_ROW_STORE(p, w) asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(w) : "memory")
+#endif
 
 template <int D, bool TREE, class E>
 __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
@@ -551,6 +558,7 @@ __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
     __shared__ __attribute__((aligned(16))) uint16_t sK[2][4][32 * LROW];
     __shared__ u32x4 sVt[2][4][8][64];   // V of each sub-block as MFMA operands: [head dim within chunk][lane]
     __shared__ int32_t sPT[3][PTR * 64];
+    __shared__ u32x4 sOut[4][16 * 17];   // per computing wavefront: its 16 result rows (16 pieces of 16 bytes + 1 of padding each)
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m16 = lane & 15, g = lane >> 4;
@@ -883,35 +891,38 @@ __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
             float l = l_run;
             l += __shfl_xor(l, 16);
             l += __shfl_xor(l, 32);
-            if (tl < cp.n_q) {
-                const float inv = l > 0.f ? 1.0f / l : 0.f;      // (a partial row that saw no key: all zero, weight zero)
-                if (cp.head_flags & kPieceDirect) {
-                    uint16_t* op = P.o + ((int64_t)(cp.q_row0 + tl) * P.n_q_heads + kvh * G + hg) * D + g * 32;
-                    if (g * 4 < DCH) {
+            // Rows leave through a wavefront-private LDS tile, so that every store instruction writes whole rows
+            // (lane (row, g) parks its four 16-byte pieces of row `row`; lane L of instruction k then takes piece
+            // L % 16 of row 4 k + L / 16), and as write-through stores: a result row is written once and never read
+            // here, and lines that sit in the cache waiting to be written back cost the read stream several times
+            // what lines written through at once do.  A partial row is the row normalised by its own sum, as half
+            // precision, next to its (maximum, sum) pair.
+            const bool direct = cp.head_flags & kPieceDirect;
+            const float inv = l > 0.f ? 1.0f / l : 0.f;          // (a partial row that saw no key: all zero, weight zero)
+            u32x4* tilebuf = sOut[tile];
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            u32x4 w = {E::pack(O[0][r] * inv, O[1][r] * inv), E::pack(O[2][r] * inv, O[3][r] * inv),
-                                       E::pack(O[4][r] * inv, O[5][r] * inv), E::pack(O[6][r] * inv, O[7][r] * inv)};
-                            *(u32x4*)(op + r * 8) = w;
-                        }
-                    }
-                } else {
-                    // a partial row: normalised by its own sum, as half precision, next to (maximum, sum)
-                    const int64_t slot = (int64_t)cp.out_base + nn;
-                    uint16_t* po = P.part_o + slot * kPartRow + g * 32;
-                    if (g * 4 < DCH) {
+            for (int r = 0; r < 4; ++r) {
+                const u32x4 w = direct ? u32x4{E::pack(O[0][r] * inv, O[1][r] * inv), E::pack(O[2][r] * inv, O[3][r] * inv),
+                                               E::pack(O[4][r] * inv, O[5][r] * inv), E::pack(O[6][r] * inv, O[7][r] * inv)}
+                                       : u32x4{F16::pack(O[0][r] * inv, O[1][r] * inv), F16::pack(O[2][r] * inv, O[3][r] * inv),
+                                               F16::pack(O[4][r] * inv, O[5][r] * inv), F16::pack(O[6][r] * inv, O[7][r] * inv)};
+                tilebuf[m16 * 17 + g * 4 + r] = w;
+            }
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            u32x4 w = {F16::pack(O[0][r] * inv, O[1][r] * inv), F16::pack(O[2][r] * inv, O[3][r] * inv),
-                                       F16::pack(O[4][r] * inv, O[5][r] * inv), F16::pack(O[6][r] * inv, O[7][r] * inv)};
-                            *(u32x4*)(po + r * 8) = w;
-                        }
-                    }
-                    if (g == 0) {
-                        P.part_ml[slot * 2] = m_run;
-                        P.part_ml[slot * 2 + 1] = l;
-                    }
+            for (int k = 0; k < 4; ++k) {
+                const int row = k * 4 + g, nr = tile * 16 + row;
+                const int tr = nr / G, hr = nr - tr * G;
+                const u32x4 w = tilebuf[row * 17 + m16];
+                if (tr < cp.n_q && m16 < DCH) {
+                    uint16_t* op = direct ? P.o + ((int64_t)(cp.q_row0 + tr) * P.n_q_heads + kvh * G + hr) * D + m16 * 8
+                                          : P.part_o + ((int64_t)cp.out_base + nr) * kPartRow + m16 * 8;
+                    SPIN_ROW_STORE(op, w);
                 }
+            }
+            if (!direct && tl < cp.n_q && g == 0) {
+                const int64_t slot = (int64_t)cp.out_base + nn;
+                P.part_ml[slot * 2] = m_run;
+                P.part_ml[slot * 2 + 1] = l;
             }
         }
         if (!more) break;
