@@ -11,6 +11,7 @@ configurations each after a warm-up of its own (`per_config`), and the CPU oracl
 """
 import argparse
 import dataclasses
+import gc
 import json
 import math
 import os
@@ -143,6 +144,32 @@ def calib_stream(args):
                 out["results"].append({"order": order, "wavefronts": n_waves, "blocks_per_wavefront": per_wave,
                                        "nontemporal": bool(nt), "ms_median": med, "ms_min": min(times),
                                        "gbs_median": n_bytes / med / 1e6, "gbs_best": n_bytes / min(times) / 1e6})
+    # What result rows written during the stream cost it: 1024 readers over the shuffled table, and beside them 256
+    # writer wavefronts that spread 18.9 MB (the final rows of the 70b_gqa batch) over the stream's duration.
+    lib.spin_probe_read_beside_writers.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_uint64,
+                                                   C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.spin_probe_read_beside_writers.restype = C.c_int
+    tab = tables["shuffled"].to(dev)
+    wbuf = torch.zeros((64 << 20) // 4, dtype=torch.int32, device=dev)
+    out["writes_during_stream"] = []
+    for name, writers, chunks, pause, mode in (("no writers", 0, 0, 0, 0), ("plain stores", 256, 18, 16, 0),
+                                               ("non-temporal stores", 256, 18, 16, 1), ("write-through stores", 256, 18, 16, 2),
+                                               ("plain stores to one cached chunk per writer", 256, 18, 16, 3)):
+        def launch():
+            rc = lib.spin_probe_read_beside_writers(buf.data_ptr(), tab.data_ptr(), 1024, n_blocks // 1024, wbuf.data_ptr(),
+                                                    wbuf.numel() * 4, writers, chunks, pause, mode, sink.data_ptr(), stream)
+            if rc:
+                raise RuntimeError(f"probe launch failed: hipError {rc}")
+        for _ in range(args.warmup):
+            launch()
+        times = []
+        for _ in range(args.steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); launch(); e1.record()
+            e1.synchronize()
+            times.append(e0.elapsed_time(e1))
+        out["writes_during_stream"].append({"writers": name, "mb_written": writers * chunks * 4096 / 1e6,
+                                            "ms_median": statistics.median(times), "ms_min": min(times)})
     print(json.dumps(out))
 
 
@@ -150,7 +177,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="13b")
     ap.add_argument("--seed", type=int, default=3)
     ap.add_argument("--page-size", type=int, default=0, help="tokens per KV page (0 = the configuration's, 16)")
@@ -307,12 +334,17 @@ def main():
         for _ in range(1 + repeats):
             for c in ctxs:
                 c.profile_begin(args.steps * len(mbs), every=args.profile_every)
+            # (the interpreter's cyclic garbage collector stays out of the timed region, as in `timeit`: a full collection
+            # over the tables and tensors this script holds takes 40 ms, more than sixty steps)
+            gc.collect()
+            gc.disable()
             t0 = time.perf_counter()
             for _ in range(args.steps):
                 step()
             torch.cuda.synchronize()
             wall = time.perf_counter() - t0
-            ms = {"attn": 0.0, "join": 0.0, "row_stats": 0.0, "finish": 0.0}
+            gc.enable()
+            ms = {"attn": 0.0, "join": 0.0, "accept_stats": 0.0, "accept_draw": 0.0}
             calls = [0, 0]
             for c in ctxs:
                 m1, c1 = c.profile_end()
@@ -323,7 +355,7 @@ def main():
             n_a, n_c = max(calls[0] / len(mbs), 1), max(calls[1] / len(mbs), 1)
             regions.append({"ms_per_step": wall * 1e3 / args.steps, "timed_steps": calls[0] // len(mbs),
                             "kernel_ms": {"attn": ms["attn"] / n_a, "join": ms["join"] / n_a,
-                                          "row_stats": ms["row_stats"] / n_c, "finish": ms["finish"] / n_c}})
+                                          "accept_stats": ms["accept_stats"] / n_c, "accept_draw": ms["accept_draw"] / n_c}})
         # the host's share of a step (decomposition, scheduling, staging, launches), measured apart from the timed
         # regions with an idle GPU in front of every step so that no call waits for a staging buffer
         host = 0.0
@@ -348,7 +380,7 @@ def main():
     def spread(regions):
         steps = [r["ms_per_step"] for r in regions]
         attn = [r["kernel_ms"]["attn"] for r in regions]
-        return {"regions": len(regions), "steps_per_region": args.steps,
+        return {"regions": len(regions), "steps_per_region": args.steps, "ms_per_step_by_region": [round(x, 5) for x in steps],
                 "ms_per_step_min": min(steps), "ms_per_step_median": statistics.median(steps), "ms_per_step_max": max(steps),
                 "attn_kernel_ms_min": min(attn), "attn_kernel_ms_median": statistics.median(attn), "attn_kernel_ms_max": max(attn)}
 
@@ -391,6 +423,9 @@ def main():
                    "seed": args.seed, "draft_rows": t.n_rows, "kv_tokens": t.kv_tokens(),
                    "kv_gb_per_step": kv_bytes / 1e9, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS},
         "kernel_ms": r0["kernel_ms"],
+        "kernel_ms_keys": "attn / join: attention and partial-join kernels; accept_stats: first acceptance kernel (row "
+                          "statistics; the whole acceptance when the call is small enough for one kernel); accept_draw: "
+                          "second acceptance kernel (accept scan + next-token draw)",
         "spread": spread(head["regions"]),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
@@ -405,7 +440,7 @@ def main():
                 continue
             r = run_config(si.CONFIGS[name], args.repeats)
             sp = spread(r["regions"])
-            km = {k: statistics.median(x["kernel_ms"][k] for x in r["regions"]) for k in ("attn", "join", "row_stats", "finish")}
+            km = {k: statistics.median(x["kernel_ms"][k] for x in r["regions"]) for k in ("attn", "join", "accept_stats", "accept_draw")}
             gbs = r["kv_bytes"] / (km["attn"] * 1e-3) / 1e9 if km["attn"] > 0 else 0.0
             per[name] = {"ms_per_step": sp["ms_per_step_median"], "ms_per_step_min": sp["ms_per_step_min"],
                          "tokens_per_s": r["table"].n_rows / (sp["ms_per_step_median"] * 1e-3),

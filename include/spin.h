@@ -324,9 +324,10 @@ int spin_set_plan_reuse(spin_ctx* ctx, int32_t enable);
  * (nothing is synchronised until spin_profile_end).  spin_profile_begin arms up to max_calls
  * calls of spin_verify_attn and as many of spin_accept; further calls run untimed.
  * spin_profile_end waits for the recorded events and returns the summed durations in
- * milliseconds: ms[0] attention kernels, ms[1] partial-join kernel, ms[2] logits row-statistics
- * kernel, ms[3] acceptance scan / next-token kernel; calls[0] / calls[1] = timed calls of
- * spin_verify_attn / spin_accept.  It disarms the context. */
+ * milliseconds: ms[0] attention kernels, ms[1] partial-join kernel, ms[2] the first kernel of
+ * spin_accept (the logits row statistics; for a call small enough to run as one kernel, the whole
+ * acceptance), ms[3] its second kernel (acceptance scan and next-token draw; zero when there is
+ * none); calls[0] / calls[1] = timed calls of spin_verify_attn / spin_accept.  It disarms the context. */
 int spin_profile_begin(spin_ctx* ctx, int32_t max_calls);
 /* While armed, time only every n-th call of each kind (n >= 1, default 1; the first call after
  * spin_profile_begin is timed).  Each timed call puts three event records on its stream, a few

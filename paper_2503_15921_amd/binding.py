@@ -309,11 +309,11 @@ class SpinContext:
         _check(self._lib.spin_profile_begin(self._h, max_calls), self._h)
 
     def profile_end(self):
-        """Returns ({'attn','join','row_stats','finish'} -> summed ms, (attn calls, accept calls))."""
+        """Returns ({'attn','join','accept_stats','accept_draw'} -> summed ms, (attn calls, accept calls))."""
         ms = (C.c_double * 4)()
         calls = (C.c_int32 * 2)()
         _check(self._lib.spin_profile_end(self._h, ms, calls), self._h)
-        return dict(attn=ms[0], join=ms[1], row_stats=ms[2], finish=ms[3]), (calls[0], calls[1])
+        return dict(attn=ms[0], join=ms[1], accept_stats=ms[2], accept_draw=ms[3]), (calls[0], calls[1])
 
     def _retry(self, call):
         rc = call()

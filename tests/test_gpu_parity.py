@@ -1343,7 +1343,7 @@ def test_profile_sampling(ctx):
         hip_attention(ctx, b)
     ms, calls = ctx.profile_end()
     assert calls[0] == 3 and calls[1] == 0          # calls 0, 3 and 6 of the seven were timed
-    assert ms["attn"] > 0 and ms["row_stats"] == 0
+    assert ms["attn"] > 0 and ms["accept_stats"] == 0
     ctx.profile_begin(2)                            # every call, but only two slots
     for _ in range(4):
         hip_attention(ctx, b)
