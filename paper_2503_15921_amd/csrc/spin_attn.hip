@@ -541,8 +541,11 @@ constexpr int kGroupWaves = 8;
 // and as write-through stores: lines that wait in the cache to be written back -- and rows written in pieces by
 // several instructions -- cost a saturated read stream several times what whole lines written through at once do
 // (measured: 18.9 MB of rows during a 4 GiB stream cost 92 us as plain stores, 22 us written through).
+// (The two idle cycles behind the store: a vector instruction must not overwrite the data registers of a store
+// of more than 8 bytes in the two cycles after it, and the compiler, which leaves such gaps behind its own
+// stores, does not look inside an asm statement.)
 __device__ __forceinline__ void store_row_piece(void* p, u32x4 w) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(w) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(w) : "memory");
 }
 
 template <int D, bool TREE, class E>
