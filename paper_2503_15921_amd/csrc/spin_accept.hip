@@ -14,6 +14,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <algorithm>
+#include <atomic>
 #include <mutex>
 
 #include "spin_device.h"
@@ -603,7 +605,8 @@ __global__ __launch_bounds__(kStatThreads) void accept_small_kernel(AcceptParams
 }
 
 // Second launch (rejection mode, after row_stats_kernel): the next token of every request.  The vocabulary
-// is cut into kDrawChunks parts; workgroup (part, request) runs the request's first-reject scan (every part
+// is cut into P.draw_parts <= kDrawChunks parts (as many as keep all workgroups of the launch resident at
+// once); workgroup (part, request) runs the request's first-reject scan (every part
 // for itself: a few rows, and cheaper than one more launch or a wait), sums the masses of its part's blocks
 // of 256 ids into the request's run table, counts itself in on the request's arrival counter, and the
 // workgroup that arrives last scans the table and looks inside the block that holds u' * Z.  The counter
@@ -632,7 +635,8 @@ __global__ __launch_bounds__(kStatThreads) void accept_draw_kernel(AcceptParams 
     const int n = s_n;
     const int V = P.vocab;
     const int nb = (V + 255) >> 8;
-    const int nbp = (nb + kDrawChunks - 1) / kDrawChunks;       // blocks per part
+    const int parts = P.draw_parts;
+    const int nbp = (nb + parts - 1) / parts;                   // blocks per part
     const int nbw = (nbp + 3) / 4;                              // blocks per wavefront
     ResidualSrc src = residual_src(P, req, r0, g, n, s_tab);
     double* const runs = P.draw_runs + (int64_t)req * kDrawBlocks;
@@ -652,11 +656,11 @@ __global__ __launch_bounds__(kStatThreads) void accept_draw_kernel(AcceptParams 
         for (int w = 1; w < kStatThreads / 64; ++w) last = max(last, sh.last[w]);
         __hip_atomic_store(lasts + part, last, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (!arrive_last(P.arrive + req, kDrawChunks, &s_is_last)) return;
+    if (!arrive_last(P.arrive + req, parts, &s_is_last)) return;
     for (int k = tid; k < nb; k += kStatThreads) sh.run[k] = __hip_atomic_load(runs + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid < kDrawChunks) sh.last[tid] = __hip_atomic_load(lasts + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid < parts) sh.last[tid] = __hip_atomic_load(lasts + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    if (cdf_search(src, V, P.u_sample[req], &P.next_token[req], sh, nb, kDrawChunks, [&](int run, int& b0, int& c) {
+    if (cdf_search(src, V, P.u_sample[req], &P.next_token[req], sh, nb, parts, [&](int run, int& b0, int& c) {
             b0 = run;
             c = 1;
         }))
@@ -882,9 +886,23 @@ hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* ro
         if (e != hipSuccess) return e;
     }
     if (counters && p.mode == SPIN_ACCEPT_REJECTION && p.vocab <= kDrawBlocks * 256 && p.draw_runs && p.draw_last) {
-        const dim3 dgrid(kDrawChunks, p.n_req);
-        if (inl) hipLaunchKernelGGL(accept_draw_kernel<true>, dgrid, block, 0, stream, p, io);
-        else hipLaunchKernelGGL(accept_draw_kernel<false>, dgrid, block, 0, stream, p, io);
+        // as many parts per request as keep every workgroup of the launch resident at once: a second round of
+        // workgroups would double the length of what is a chain of dependent memory round trips
+        static std::atomic<int> resident{0};
+        int res = resident.load();
+        if (res == 0) {
+            int per_cu = 0, dev = 0, cus = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_draw_kernel<true>, kStatThreads, 0) != hipSuccess ||
+                hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+                return hipErrorUnknown;
+            res = std::max(1, per_cu * cus);
+            resident.store(res);
+        }
+        AcceptParams pd = p;
+        pd.draw_parts = std::max(1, std::min(kDrawChunks, res / p.n_req));
+        const dim3 dgrid(pd.draw_parts, p.n_req);
+        if (inl) hipLaunchKernelGGL(accept_draw_kernel<true>, dgrid, block, 0, stream, pd, io);
+        else hipLaunchKernelGGL(accept_draw_kernel<false>, dgrid, block, 0, stream, pd, io);
     } else {
         hipLaunchKernelGGL(accept_finish_kernel, dim3(p.n_req), dim3(kFinishThreads), 0, stream, p);
     }

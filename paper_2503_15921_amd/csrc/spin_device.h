@@ -93,6 +93,7 @@ struct AcceptParams {
     int32_t* n_accepted;
     int32_t* next_token;
     int32_t n_req, n_rows, vocab, mode;
+    int32_t draw_parts;            // parts the vocabulary is cut into by the next-token draw (set by launch_accept)
 };
 
 // ev_mid (may be null) is recorded after the first kernel.

@@ -723,6 +723,18 @@ def test_accept_full_vocab(ctx, name, seed):
     assert len(seen) >= 3, "the correlated draw should spread accepted lengths"
 
 
+@pytest.mark.parametrize("n_req", [150, 260, 330, 450, 700, 1400])
+def test_accept_many_requests(ctx, n_req):
+    """Batches of many requests: the next-token draw cuts the vocabulary into fewer parts per request the more
+    requests there are (8 down to 1), so that every workgroup of its launch stays resident."""
+    import paper_2503_15921_amd as spin
+    rng = np.random.default_rng(n_req)
+    draft_len = rng.integers(1, 4, n_req).astype(np.int32)
+    for rho in (None, 0.9):
+        ab = si.make_accept_batch(draft_len, 9001, 3.0, n_req, device="cuda", rho=rho)
+        check_accept(ctx, spin.ACCEPT_REJECTION, ab, f"{n_req} requests rho {rho}")
+
+
 def test_accept_many_random_small_batches(ctx):
     """150 random small problems (vocabularies 2-700, drafts 1-9, correlation anywhere from none to near
     identity, both modes).  A case whose decisions sit within 1e-9 of a threshold is skipped, not failed."""
@@ -1022,7 +1034,11 @@ def wide_accept_case(ctx, seed):
 def test_accept_over_all_axes(ctx):
     """100 cases by default; SPIN_SWEEP_CASES=n runs the first n seeds (20000 have passed)."""
     n = int(os.environ.get("SPIN_SWEEP_CASES", "100"))
-    compared = sum(wide_accept_case(ctx, seed) for seed in range(n))
+    compared = 0
+    for seed in range(n):
+        compared += wide_accept_case(ctx, seed)
+        if seed % 500 == 499:
+            print(f"{seed + 1} cases", flush=True)
     assert compared >= 0.95 * n
 
 

@@ -28,6 +28,23 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(EXPORTS)
 
 
+def test_stream_probe_refuses_what_would_not_fit():
+    # the measuring kernels of bench.py --calib-stream check their sizes on the host before anything is launched
+    import ctypes as C
+    from paper_2503_15921_amd.build import PROBE_LIB
+    lib = C.CDLL(PROBE_LIB)
+    lib.spin_probe_read_beside_writers.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_uint64,
+                                                   C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.spin_probe_read_blocks.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    invalid = 1   # hipErrorInvalidValue
+    fake = 4096   # stands for a device address; never dereferenced by a refused call
+    assert lib.spin_probe_read_beside_writers(fake, fake, 1024, 1024, fake, 256 * 18 * 4096 - 1, 256, 18, 16, 0, fake, None) == invalid
+    assert lib.spin_probe_read_beside_writers(fake, fake, 1024, 1024, fake, 1 << 30, 256, 18, 16, 4, fake, None) == invalid
+    assert lib.spin_probe_read_beside_writers(fake, fake, 1024, 1022, fake, 1 << 30, 256, 18, 16, 0, fake, None) == invalid
+    assert lib.spin_probe_read_beside_writers(None, fake, 1024, 1024, fake, 1 << 30, 256, 18, 16, 0, fake, None) == invalid
+    assert lib.spin_probe_read_blocks(None, fake, 1024, 1024, 1, fake, None) != 0
+
+
 def test_strerror():
     lib = spin.load_library()
     assert lib.spin_strerror(0) == b"ok"
