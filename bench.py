@@ -246,6 +246,12 @@ def main():
             batch.k_pool = batch.k_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
             batch.v_pool = batch.v_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
         t = batch.table
+        # Batches whose K/V is smaller than the chip's last-level cache would be flattered by it: every step reads another
+        # copy of the pools, enough copies that 2 GB pass between two uses of the same bytes (one copy for 13b and 70b_gqa).
+        kv_once = si.algorithmic_kv_bytes(t, cfg.n_kv_heads, cfg.head_dim)
+        n_copies = max(1, min(16, -(-(2 << 30) // max(kv_once, 1))))
+        pools = [(batch.k_pool, batch.v_pool)] + [(batch.k_pool.clone(), batch.v_pool.clone()) for _ in range(n_copies - 1)]
+        step_no = [0]
         ab = si.make_accept_batch(t.draft_len, cfg.vocab, cfg.logit_sigma, args.seed, device=dev)
         M = max(1, args.microbatches)
         S = 1 if M == 1 else max(1, min(args.streams, M))
@@ -305,6 +311,8 @@ def main():
         attn_done = [torch.cuda.Event() for _ in mbs]
 
         def step():
+            k_pool, v_pool = pools[step_no[0] % n_copies]
+            step_no[0] += 1
             for k, mb in enumerate(mbs):
                 subs = decomposition(mb["prefix"], mb["draft"])
                 with torch.cuda.stream(mb["stream"]):
@@ -313,8 +321,8 @@ def main():
                         # micro-batch runs beside the attention of the next
                         mb["stream"].wait_event(attn_done[k - 1])
                     if args.append:
-                        mb["ctx"].append_kv(mb["tab"], batch.k_pool, batch.v_pool, mb["k_new"], mb["v_new"])
-                    mb["ctx"].verify_attn(mb["tab"], batch.k_pool, batch.v_pool, mb["q"], mb["out"], cfg.n_q_heads, subs=subs,
+                        mb["ctx"].append_kv(mb["tab"], k_pool, v_pool, mb["k_new"], mb["v_new"])
+                    mb["ctx"].verify_attn(mb["tab"], k_pool, v_pool, mb["q"], mb["out"], cfg.n_q_heads, subs=subs,
                                           tree_mask=mb["masks"])
                     if S > 1:
                         attn_done[k].record(mb["stream"])
@@ -372,7 +380,7 @@ def main():
         group = cfg.n_q_heads // cfg.n_kv_heads
         attn_kernel = "verify_attn_group_kernel" if min(int(t.draft_len.max()), 64 // group) * group > 32 else "verify_attn_kernel"
         res = dict(cfg=cfg, table=t, regions=regions, host_ms=host * 1e3 / 10, kv_bytes=kv_bytes, attn_kernel=attn_kernel,
-                   n_mbs=len(mbs), n_streams=S)
+                   n_mbs=len(mbs), n_streams=S, kv_pool_copies=n_copies)
         if keep_inputs:
             res["batch"], res["ab"] = batch, ab
         return res
@@ -421,7 +429,7 @@ def main():
                    "decomposition": args.decomp, "microbatches": head["n_mbs"], "streams": head["n_streams"],
                    "plan_reuse": bool(args.reuse_plan),
                    "seed": args.seed, "draft_rows": t.n_rows, "kv_tokens": t.kv_tokens(),
-                   "kv_gb_per_step": kv_bytes / 1e9, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS},
+                   "kv_gb_per_step": kv_bytes / 1e9, "kv_pool_copies": head["kv_pool_copies"], "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS},
         "kernel_ms": r0["kernel_ms"],
         "kernel_ms_keys": "attn / join: attention and partial-join kernels; accept_stats: first acceptance kernel (row "
                           "statistics; the whole acceptance when the call is small enough for one kernel); accept_draw: "
@@ -447,7 +455,7 @@ def main():
                          "attn_kernel": r["attn_kernel"], "attn_kernel_ms": km["attn"], "attn_kernel_ms_min": sp["attn_kernel_ms_min"],
                          "achieved_gbs": gbs, "frac": gbs / HBM_PEAK_GBS, "kernel_ms": km, "host_ms_per_step": r["host_ms"],
                          "draft_rows": r["table"].n_rows, "kv_gb_per_step": r["kv_bytes"] / 1e9,
-                         "regions": sp["regions"], "steps_per_region": args.steps, "warmup": args.warmup}
+                         "kv_pool_copies": r["kv_pool_copies"], "regions": sp["regions"], "steps_per_region": args.steps, "warmup": args.warmup}
         res["per_config"] = per
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, head["batch"], head["ab"])
