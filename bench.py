@@ -40,7 +40,7 @@ def cpu_model():
 
 def _oracle_leg(cfg, batch, ab, budget_s):
     """Time the oracle on a bounded sample of the batch; returns (verified draft tokens/s for the whole batch
-    by linear scaling, description of the sample, CPU seconds used per wall second)."""
+    by linear scaling, description of the sample, CPU seconds used per wall second, K/V GB/s of its attention)."""
     import numpy as np
     import spin_inputs as si
     from oracle import spin_oracle as orc
@@ -78,7 +78,8 @@ def _oracle_leg(cfg, batch, ab, budget_s):
     sample = (f"attention: {n_pairs} random (request, head) pairs = {done_cells / total_cells:.3%} of the batch's "
               f"key-head rows in {t_attn:.1f} s; acceptance: first {nreq} of {t.n_req} requests in {t_acc:.2f} s; "
               f"both scaled linearly to the whole batch")
-    return t.n_rows / (attn_full + acc_full), sample, busy
+    kv_gbs = si.algorithmic_kv_bytes(t, cfg.n_kv_heads, cfg.head_dim) / attn_full / 1e9
+    return t.n_rows / (attn_full + acc_full), sample, busy, kv_gbs
 
 
 def cpu_baseline(cfg, batch, ab, budget_s=10.0):
@@ -89,17 +90,18 @@ def cpu_baseline(cfg, batch, ab, budget_s=10.0):
         pool = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threadpool_limits, pool = None, 1
-    v_all, sample, busy_all = _oracle_leg(cfg, batch, ab, budget_s)
+    v_all, sample, busy_all, gbs_all = _oracle_leg(cfg, batch, ab, budget_s)
     res = {"value": v_all, "unit": "verified draft tokens/s", "cores": max(1, int(math.ceil(busy_all - 0.05))),
-           "kind": "oracle", "sample": sample,
+           "kind": "oracle", "sample": sample, "attention_kv_gbs": gbs_all,
            "nproc": os.cpu_count(), "cpus_allowed": len(os.sched_getaffinity(0)), "cpu_model": cpu_model(),
            "blas_threads_available": int(pool), "cpu_seconds_per_wall_second": round(busy_all, 2),
            "note": "cores = CPU seconds the oracle used per wall second, rounded up: its loops over requests and heads "
                    "are Python, only the small matrix products inside may use the BLAS pool"}
     if threadpool_limits is not None:
         with threadpool_limits(limits=1):
-            v_one, sample_one, busy_one = _oracle_leg(cfg, batch, ab, budget_s)
+            v_one, sample_one, busy_one, gbs_one = _oracle_leg(cfg, batch, ab, budget_s)
         res["one_thread"] = {"value": v_one, "unit": "verified draft tokens/s", "cores": 1, "sample": sample_one,
+                             "attention_kv_gbs": gbs_one,
                              "cpu_seconds_per_wall_second": round(busy_one, 2)}
     return res
 
