@@ -239,7 +239,7 @@ def main():
         return
     elem = torch.bfloat16 if args.dtype == "bf16" else torch.float16
 
-    def run_config(cfg, repeats, keep_inputs=False, rho=None):
+    def run_config(cfg, repeats, keep_inputs=False, rho=None, decomp=None):
         """Warm up, then time 1 + repeats regions of args.steps steps of `cfg`'s batch.  Returns a dict of figures
         (region 0 is the one a headline is taken from) and, on request, the inputs for the CPU baseline."""
         batch = si.make_verify_batch(cfg, args.seed, device=dev, dtype=elem)
@@ -295,7 +295,7 @@ def main():
                 k_new=k_new[r0:r1] if args.append else None, v_new=v_new[r0:r1] if args.append else None))
 
         def decomposition(prefix, draft):
-            d = args.decomp
+            d = decomp or args.decomp
             if d == "config":
                 d = f"q:{cfg.q_split_width}" if cfg.q_split_width else "none"
             if d == "none":
@@ -458,10 +458,11 @@ def main():
     if not args.no_per_config and args.config == "13b":
         # the other four configurations, each after a warm-up of its own, figures = medians over the timed regions
         per = {}
-        for name in si.CONFIG_ORDER:
+        # (skewed a second time, cut the paper's way: along the keys into rows of length L = 512, Sec. V-A)
+        for name in list(si.CONFIG_ORDER) + ["skewed, KV-split L=512"]:
             if name == cfg.name:
                 continue
-            r = run_config(si.CONFIGS[name], args.repeats)
+            r = run_config(si.CONFIGS[name.split(",")[0]], args.repeats, decomp="kv:512" if "," in name else None)
             sp = spread(r["regions"])
             km = {k: statistics.median(x["kernel_ms"][k] for x in r["regions"]) for k in ("attn", "join", "accept_stats", "accept_draw")}
             gbs = r["kv_bytes"] / (km["attn"] * 1e-3) / 1e9 if km["attn"] > 0 else 0.0
