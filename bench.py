@@ -205,7 +205,7 @@ def main():
     ap.add_argument("--reuse-plan", action="store_true",
                     help="let the library launch from the tables of the previous step (what the other layers of "
                          "one step do); off by default: every timed step plans and uploads afresh")
-    ap.add_argument("--profile-every", type=int, default=4,
+    ap.add_argument("--profile-every", type=int, default=10,
                     help="the library's HIP events time every n-th step of the timed region")
     ap.add_argument("--calib-copy", action="store_true",
                     help="instead of the step, run a plain 1 GiB device copy per step (counter calibration)")
@@ -338,8 +338,9 @@ def main():
         for _ in range(args.warmup):
             step()
         torch.cuda.synchronize()
-        # The library's events time every fourth step of a timed region: three event records per timed call
-        # cost about 27 us of stream time per step, which would otherwise be 4 % of the figure being measured.
+        # The library's events time every tenth step of a timed region: three event records per timed call
+        # cost about 27 us of stream time per step, which would otherwise be 4 % of the figure being measured
+        # (0.4 % this way; the kernel averages do not depend on the sampling).
         regions = []
         for _ in range(1 + repeats):
             for c in ctxs:
