@@ -320,19 +320,21 @@ int spin_set_plan_reuse(spin_ctx* ctx, int32_t enable);
 
 /* ---- measurement aid ------------------------------------------------------------------------ */
 
-/* Time the kernels of the next calls with HIP events recorded on the stream each call is given
- * (nothing is synchronised until spin_profile_end).  spin_profile_begin arms up to max_calls
- * calls of spin_verify_attn and as many of spin_accept; further calls run untimed.
+/* Time the kernels of the next calls with HIP events handed to the kernel launches themselves: an event
+ * pair receives the start and end time stamps of the kernel's own dispatch record, so nothing extra
+ * is put on the stream and a timed call runs like an untimed one (nothing is synchronised until
+ * spin_profile_end).  spin_profile_begin arms up to max_calls calls of spin_verify_attn and as many of
+ * spin_accept; further calls run untimed.
  * spin_profile_end waits for the recorded events and returns the summed durations in
- * milliseconds: ms[0] attention kernels, ms[1] partial-join kernel, ms[2] the first kernel of
- * spin_accept (the logits row statistics; for a call small enough to run as one kernel, the whole
- * acceptance), ms[3] its second kernel (acceptance scan and next-token draw; zero when there is
- * none); calls[0] / calls[1] = timed calls of spin_verify_attn / spin_accept.  It disarms the context. */
+ * milliseconds: ms[0] attention kernels, ms[1] partial-join kernel (zero for a call that has no partial
+ * results to join), ms[2] the first kernel of spin_accept (the logits row statistics; for a call small
+ * enough to run as one kernel, the whole acceptance), ms[3] its second kernel (acceptance scan and
+ * next-token draw; zero when there is none); calls[0] / calls[1] = timed calls of spin_verify_attn /
+ * spin_accept.  It disarms the context. */
 int spin_profile_begin(spin_ctx* ctx, int32_t max_calls);
 /* While armed, time only every n-th call of each kind (n >= 1, default 1; the first call after
- * spin_profile_begin is timed).  Each timed call puts three event records on its stream, a few
- * microseconds of stream time each: sampling keeps a timed run close to an untimed one.  The
- * setting stays until changed.  max_calls of spin_profile_begin counts timed calls. */
+ * spin_profile_begin is timed).  The setting stays until changed.  max_calls of spin_profile_begin
+ * counts timed calls. */
 int spin_profile_every(spin_ctx* ctx, int32_t n);
 int spin_profile_end(spin_ctx* ctx, double ms[4], int32_t calls[2]);
 

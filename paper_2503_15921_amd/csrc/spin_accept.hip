@@ -859,8 +859,11 @@ hipError_t launch_accept_tree(const AcceptParams& p, const int32_t* parent, int3
 // Vocabularies up to this size are handled in one launch.
 constexpr int kSmallVocab = 8192;
 
-hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* row_off_host, hipStream_t stream, hipEvent_t ev_mid) {
+hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* row_off_host, hipStream_t stream, LaunchTiming* timing) {
+    if (timing) timing->second = false;
     if (p.n_req <= 0) return hipSuccess;
+    hipEvent_t t0 = timing ? timing->ev[0] : nullptr, t1 = timing ? timing->ev[1] : nullptr;
+    hipEvent_t t2 = timing ? timing->ev[2] : nullptr, t3 = timing ? timing->ev[3] : nullptr;
     const bool counters = p.arrive && p.n_req <= 65535;
     const bool inl = row_off_host && p.n_req <= kInlineReqs;
     InlineOffsets io;
@@ -871,20 +874,14 @@ hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* ro
     if (counters && max_draft >= 1 && p.vocab <= kSmallVocab) {
         const int slots = p.mode == SPIN_ACCEPT_GREEDY ? max_draft + 1 : 2 * max_draft + 1;
         const dim3 grid(slots, p.n_req);
-        if (inl) hipLaunchKernelGGL(accept_small_kernel<true>, grid, block, 0, stream, p, io);
-        else hipLaunchKernelGGL(accept_small_kernel<false>, grid, block, 0, stream, p, io);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        return ev_mid ? hipEventRecord(ev_mid, stream) : hipSuccess;
+        if (inl) hipExtLaunchKernelGGL(accept_small_kernel<true>, grid, block, 0, stream, t0, t1, 0, p, io);
+        else hipExtLaunchKernelGGL(accept_small_kernel<false>, grid, block, 0, stream, t0, t1, 0, p, io);
+        return hipGetLastError();
     }
     const int n_stat_rows = p.mode == SPIN_ACCEPT_GREEDY ? p.n_rows + p.n_req : 2 * p.n_rows + p.n_req;
-    hipLaunchKernelGGL(row_stats_kernel, dim3(n_stat_rows), block, 0, stream, p);
+    hipExtLaunchKernelGGL(row_stats_kernel, dim3(n_stat_rows), block, 0, stream, t0, t1, 0, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (ev_mid) {
-        e = hipEventRecord(ev_mid, stream);
-        if (e != hipSuccess) return e;
-    }
     if (counters && p.mode == SPIN_ACCEPT_REJECTION && p.vocab <= kDrawBlocks * 256 && p.draw_runs && p.draw_last) {
         // as many parts per request as keep every workgroup of the launch resident at once: a second round of
         // workgroups would double the length of what is a chain of dependent memory round trips
@@ -901,12 +898,14 @@ hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* ro
         AcceptParams pd = p;
         pd.draw_parts = std::max(1, std::min(kDrawChunks, res / p.n_req));
         const dim3 dgrid(pd.draw_parts, p.n_req);
-        if (inl) hipLaunchKernelGGL(accept_draw_kernel<true>, dgrid, block, 0, stream, pd, io);
-        else hipLaunchKernelGGL(accept_draw_kernel<false>, dgrid, block, 0, stream, pd, io);
+        if (inl) hipExtLaunchKernelGGL(accept_draw_kernel<true>, dgrid, block, 0, stream, t2, t3, 0, pd, io);
+        else hipExtLaunchKernelGGL(accept_draw_kernel<false>, dgrid, block, 0, stream, t2, t3, 0, pd, io);
     } else {
-        hipLaunchKernelGGL(accept_finish_kernel, dim3(p.n_req), dim3(kFinishThreads), 0, stream, p);
+        hipExtLaunchKernelGGL(accept_finish_kernel, dim3(p.n_req), dim3(kFinishThreads), 0, stream, t2, t3, 0, p);
     }
-    return hipGetLastError();
+    e = hipGetLastError();
+    if (e == hipSuccess && timing) timing->second = true;
+    return e;
 }
 
 size_t accept_draw_scratch_bytes(int64_t n_req, size_t* last_bytes) {

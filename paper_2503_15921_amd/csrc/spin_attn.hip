@@ -1067,7 +1067,14 @@ template <int D, class E>
 static hipError_t launch_attn_d(const AttnParams& base, const Piece* const pieces_dev[3],
                                 const int32_t* const wave_begin_dev[3], const int32_t n_waves[3],
                                 const int32_t n_queued[3], int32_t* queues_dev, const JoinParams& jp,
-                                const InlineTables* tables, hipStream_t stream, hipEvent_t ev_mid) {
+                                const InlineTables* tables, hipStream_t stream, LaunchTiming* timing) {
+    int first_cls = -1, last_cls = -1;   // (one class per call in practice; with several, the time spans them all)
+    for (int cls = 0; cls < 3; ++cls)
+        if (n_waves[cls] > 0) {
+            if (first_cls < 0) first_cls = cls;
+            last_cls = cls;
+        }
+    if (timing) timing->second = false;
     for (int cls = 0; cls < 3; ++cls) {
         if (n_waves[cls] <= 0) continue;
         AttnParams p = base;
@@ -1081,19 +1088,20 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         void* args[] = {&p, (void*)tables};
         const bool small = p.inline_tables != 0;
         const void* fn = p.tree_rows ? attn_kernel_ptr<D, true, E>(cls, small) : attn_kernel_ptr<D, false, E>(cls, small);   // (an offset when inline, never zero)
-        hipError_t e = hipLaunchKernel(fn, grid, dim3(cls == 2 ? 64 * kGroupWaves : 64), args, 0, stream);
-        if (e != hipSuccess) return e;
-    }
-    if (ev_mid) {
-        hipError_t e = hipEventRecord(ev_mid, stream);
+        hipError_t e = hipExtLaunchKernel(fn, grid, dim3(cls == 2 ? 64 * kGroupWaves : 64), args, 0, stream,
+                                          timing && cls == first_cls ? timing->ev[0] : nullptr,
+                                          timing && cls == last_cls ? timing->ev[1] : nullptr, 0);
         if (e != hipSuccess) return e;
     }
     if (jp.n_tasks > 0) {
         const int pair_groups = (jp.max_pairs + kJoinWaves - 1) / kJoinWaves;
-        if (jp.inline_tables) hipLaunchKernelGGL((join_partials_small_kernel<D, E>), dim3(jp.n_tasks, pair_groups), dim3(64 * kJoinWaves), 0, stream, jp, *tables);
-        else hipLaunchKernelGGL((join_partials_kernel<D, E>), dim3(jp.n_tasks, pair_groups), dim3(64 * kJoinWaves), 0, stream, jp);
+        const dim3 grid(jp.n_tasks, pair_groups), block(64 * kJoinWaves);
+        hipEvent_t e0 = timing ? timing->ev[2] : nullptr, e1 = timing ? timing->ev[3] : nullptr;
+        if (jp.inline_tables) hipExtLaunchKernelGGL((join_partials_small_kernel<D, E>), grid, block, 0, stream, e0, e1, 0, jp, *tables);
+        else hipExtLaunchKernelGGL((join_partials_kernel<D, E>), grid, block, 0, stream, e0, e1, 0, jp);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
+        if (timing) timing->second = true;
     }
     return hipSuccess;
 }
@@ -1101,7 +1109,7 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
 hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Piece* const pieces_dev[3],
                        const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
                        int32_t* queues_dev, const JoinParams& jp, const void* inline_tables, size_t inline_bytes,
-                       hipStream_t stream, hipEvent_t ev_mid) {
+                       hipStream_t stream, LaunchTiming* timing) {
     InlineTables storage;
     const InlineTables* tables = nullptr;
     if (inline_tables) {
@@ -1112,11 +1120,11 @@ hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Pie
         return hipErrorInvalidValue;
     }
     if (head_dim == 128)
-        return f16 ? launch_attn_d<128, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, ev_mid)
-                   : launch_attn_d<128, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, ev_mid);
+        return f16 ? launch_attn_d<128, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing)
+                   : launch_attn_d<128, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing);
     if (head_dim == 64)
-        return f16 ? launch_attn_d<64, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, ev_mid)
-                   : launch_attn_d<64, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, ev_mid);
+        return f16 ? launch_attn_d<64, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing)
+                   : launch_attn_d<64, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing);
     return hipErrorInvalidValue;
 }
 

@@ -71,7 +71,8 @@ struct spin_ctx {
     spin::Plan plan;
     std::vector<int32_t> row_off_host;
     // kernel timing (spin_profile_begin / _end): three events per timed call
-    std::vector<hipEvent_t> prof_attn, prof_accept;
+    std::vector<hipEvent_t> prof_attn, prof_accept;        // four per timed call: start and end of its two kernels
+    std::vector<uint8_t> prof_attn_second, prof_accept_second;   // the call launched a second kernel
     int prof_attn_used = 0, prof_accept_used = 0;
     int64_t prof_attn_seen = 0, prof_accept_seen = 0;   // calls seen while armed
     int32_t prof_every = 1;                              // every n-th of them is timed
@@ -101,8 +102,8 @@ void free_profile(spin_ctx* c) {
 
 // Events of the next timed call, or null when the context is not armed / has run out of slots.
 hipEvent_t* prof_slot(spin_ctx* c, std::vector<hipEvent_t>& pool, int& used, int64_t& seen) {
-    if (!c->prof_on || (seen++ % c->prof_every) != 0 || (size_t)(used + 1) * 3 > pool.size()) return nullptr;
-    hipEvent_t* p = pool.data() + (size_t)used * 3;
+    if (!c->prof_on || (seen++ % c->prof_every) != 0 || (size_t)(used + 1) * 4 > pool.size()) return nullptr;
+    hipEvent_t* p = pool.data() + (size_t)used * 4;
     ++used;
     return p;
 }
@@ -526,12 +527,13 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     jp.max_pairs = sp.max_pairs;
     jp.inline_tables = sp.in_place ? 1 : 0;
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used, ctx->prof_attn_seen);
-    if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    spin::LaunchTiming timing = {};
+    if (pe) memcpy(timing.ev, pe, sizeof timing.ev);
     e = spin::launch_attn(kv->head_dim, kv->dtype == SPIN_DTYPE_F16, ap, pieces_dev, waves_dev, sp.n_waves_launch, sp.n_queued,
                           (int32_t*)(blob + sp.off_queues), jp, sp.in_place ? ctx->h_stage[slot] : nullptr, sp.bytes, stream,
-                          pe ? pe[1] : nullptr);
+                          pe ? &timing : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
-    if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    if (pe) ctx->prof_attn_second[ctx->prof_attn_used - 1] = timing.second;
     if (!sp.in_place) {   // (tables passed in the arguments were copied at the launch: their staging buffer is free at once)
         e = hipEventRecord(ctx->ev_done[slot], stream);
         if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
@@ -691,10 +693,11 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     p.vocab = vocab;
     p.mode = mode;
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_accept, ctx->prof_accept_used, ctx->prof_accept_seen);
-    if (pe && (e = hipEventRecord(pe[0], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    e = spin::launch_accept(p, max_draft, ctx->row_off_host.data(), stream, pe ? pe[1] : nullptr);
+    spin::LaunchTiming timing = {};
+    if (pe) memcpy(timing.ev, pe, sizeof timing.ev);
+    e = spin::launch_accept(p, max_draft, ctx->row_off_host.data(), stream, pe ? &timing : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "acceptance launch");
-    if (pe && (e = hipEventRecord(pe[2], stream)) != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+    if (pe) ctx->prof_accept_second[ctx->prof_accept_used - 1] = timing.second;
     e = hipEventRecord(ctx->ev[slot], stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
     ctx->ev_pending[slot] = true;
@@ -801,7 +804,8 @@ int spin_profile_begin(spin_ctx* ctx, int32_t max_calls) {
     free_profile(ctx);
     for (int k = 0; k < 2; ++k) {
         std::vector<hipEvent_t>& pool = k ? ctx->prof_accept : ctx->prof_attn;
-        for (int64_t i = 0; i < (int64_t)max_calls * 3; ++i) {
+        (k ? ctx->prof_accept_second : ctx->prof_attn_second).assign((size_t)max_calls, 0);
+        for (int64_t i = 0; i < (int64_t)max_calls * 4; ++i) {
             hipEvent_t ev;
             e = hipEventCreate(&ev);
             if (e != hipSuccess) {
@@ -824,12 +828,13 @@ int spin_profile_end(spin_ctx* ctx, double ms[4], int32_t calls[2]) {
     for (int k = 0; k < 2 && rc == SPIN_OK; ++k) {
         std::vector<hipEvent_t>& pool = k ? ctx->prof_accept : ctx->prof_attn;
         const int used = k ? ctx->prof_accept_used : ctx->prof_attn_used;
+        const std::vector<uint8_t>& second = k ? ctx->prof_accept_second : ctx->prof_attn_second;
         for (int i = 0; i < used; ++i) {
-            hipEvent_t* p = pool.data() + (size_t)i * 3;
-            hipError_t e = hipEventSynchronize(p[2]);
+            hipEvent_t* p = pool.data() + (size_t)i * 4;
+            hipError_t e = hipEventSynchronize(second[i] ? p[3] : p[1]);
             float a = 0.f, b = 0.f;
             if (e == hipSuccess) e = hipEventElapsedTime(&a, p[0], p[1]);
-            if (e == hipSuccess) e = hipEventElapsedTime(&b, p[1], p[2]);
+            if (e == hipSuccess && second[i]) e = hipEventElapsedTime(&b, p[2], p[3]);
             if (e != hipSuccess) { rc = fail_hip(ctx, e, "reading profile events"); break; }
             ms[2 * k] += a;
             ms[2 * k + 1] += b;

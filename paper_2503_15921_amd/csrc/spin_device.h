@@ -4,6 +4,7 @@
 #define SPIN_DEVICE_H
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "spin_internal.h"
@@ -54,16 +55,24 @@ struct JoinParams {
     int32_t inline_tables;       // the (*) fields are offsets into the InlineTables argument
 };
 
+// Timing of one call's kernels: the first kernel's start and end are written to ev[0], ev[1], the second kernel's
+// -- when the call launches one, which `second` then says -- to ev[2], ev[3].  The time stamps are those of the kernels'
+// own dispatch records (events handed to the launch itself): nothing extra is put on the stream.
+struct LaunchTiming {
+    hipEvent_t ev[4];
+    bool second;
+};
+
 // Wavefronts of the attention kernel of class `cls` (0, 1, 2) and head dim that fit on the device at once.
 hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves);
 
-// n_waves[c] wavefronts stream the pieces of class c; ev_mid (may be null) is recorded between the
-// attention kernels and the join kernel.  inline_tables (may be null): the tables themselves, at most
+// n_waves[c] wavefronts stream the pieces of class c; timing (may be null) receives the time stamps of the
+// attention kernel (first) and the join kernel (second).  inline_tables (may be null): the tables themselves, at most
 // kInlineTableBytes of them, to be passed in the kernel arguments (base.inline_tables / jp.inline_tables set).
 hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Piece* const pieces_dev[3],
                        const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
                        int32_t* queues_dev, const JoinParams& jp, const void* inline_tables, size_t inline_bytes,
-                       hipStream_t stream, hipEvent_t ev_mid);
+                       hipStream_t stream, LaunchTiming* timing);
 
 struct AppendParams {
     const int64_t* dst_slot;   // [R] page * page_size + slot of every packed row
@@ -96,7 +105,6 @@ struct AcceptParams {
     int32_t draw_parts;            // parts the vocabulary is cut into by the next-token draw (set by launch_accept)
 };
 
-// ev_mid (may be null) is recorded after the first kernel.
 // Largest vocabulary the next-token search handles (its per-run sums live in LDS).
 constexpr int kMaxVocab = 1 << 20;
 
@@ -104,9 +112,9 @@ constexpr int kMaxVocab = 1 << 20;
 // launch.  Otherwise the row statistics, then -- rejection mode with counters and the run table p.draw_runs --
 // the next-token draw spread over eight workgroups per request, else one workgroup per request.
 // row_off_host (may be null): the offsets p.row_off points at, as the host holds them; small batches pass
-// them to the kernel by value.
+// them to the kernel by value.  timing (may be null) receives the time stamps of the first and the second kernel.
 hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* row_off_host, hipStream_t stream,
-                         hipEvent_t ev_mid);
+                         LaunchTiming* timing);
 
 // Bytes of p.draw_runs (returned) and p.draw_last for batches of up to n_req requests.
 size_t accept_draw_scratch_bytes(int64_t n_req, size_t* last_bytes);
