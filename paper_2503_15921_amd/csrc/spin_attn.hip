@@ -1027,7 +1027,9 @@ __global__ __launch_bounds__(256) void append_kv_kernel(AppendParams P) {
         const int head = cc / per_head, col = (cc - head * per_head) * 8;
         const uint16_t* src = (is_v ? P.v_new : P.k_new) + src0 + (int64_t)cc * 8;
         uint16_t* dst = (is_v ? P.v_pool : P.k_pool) + dst0 + head * P.head_stride + col;
-        *(u32x4*)dst = *(const u32x4*)src;
+        // (non-temporal: rows left behind as dirty cache lines are written back in the middle of the attention
+        // kernel's stream, which costs it more than the whole scatter takes)
+        __builtin_nontemporal_store(*(const u32x4*)src, (u32x4*)dst);
     }
 }
 
