@@ -859,19 +859,33 @@ hipError_t launch_accept_tree(const AcceptParams& p, const int32_t* parent, int3
 // Vocabularies up to this size are handled in one launch.
 constexpr int kSmallVocab = 8192;
 
+// The path launch_accept takes: one launch (0), row statistics + spread draw (1), row statistics + one workgroup
+// per request (2).  Only the last reads the row offsets from memory when the host's copy of them is at hand.
+static int accept_path(const AcceptParams& p, int max_draft) {
+    const bool counters = p.arrive && p.n_req <= 65535;
+    if (counters && max_draft >= 1 && p.vocab <= kSmallVocab) return 0;
+    if (counters && p.mode == SPIN_ACCEPT_REJECTION && p.vocab <= kDrawBlocks * 256 && p.draw_runs && p.draw_last) return 1;
+    return 2;
+}
+
+bool accept_reads_row_off(const AcceptParams& p, int max_draft) {
+    return p.n_req > kInlineReqs || accept_path(p, max_draft) == 2;
+}
+
 hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* row_off_host, hipStream_t stream, LaunchTiming* timing) {
     if (timing) timing->second = false;
     if (p.n_req <= 0) return hipSuccess;
+    const int path = accept_path(p, max_draft);
     hipEvent_t t0 = timing ? timing->ev[0] : nullptr, t1 = timing ? timing->ev[1] : nullptr;
     hipEvent_t t2 = timing ? timing->ev[2] : nullptr, t3 = timing ? timing->ev[3] : nullptr;
-    const bool counters = p.arrive && p.n_req <= 65535;
     const bool inl = row_off_host && p.n_req <= kInlineReqs;
+    if (!inl && !p.row_off) return hipErrorInvalidValue;
     InlineOffsets io;
     io.off[0] = 0;
     if (inl) memcpy(io.off, row_off_host, (size_t)(p.n_req + 1) * 4);
     const dim3 block(kStatThreads);
     hipError_t e;
-    if (counters && max_draft >= 1 && p.vocab <= kSmallVocab) {
+    if (path == 0) {
         const int slots = p.mode == SPIN_ACCEPT_GREEDY ? max_draft + 1 : 2 * max_draft + 1;
         const dim3 grid(slots, p.n_req);
         if (inl) hipExtLaunchKernelGGL(accept_small_kernel<true>, grid, block, 0, stream, t0, t1, 0, p, io);
@@ -882,7 +896,7 @@ hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* ro
     hipExtLaunchKernelGGL(row_stats_kernel, dim3(n_stat_rows), block, 0, stream, t0, t1, 0, p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (counters && p.mode == SPIN_ACCEPT_REJECTION && p.vocab <= kDrawBlocks * 256 && p.draw_runs && p.draw_last) {
+    if (path == 1) {
         // as many parts per request as keep every workgroup of the launch resident at once: a second round of
         // workgroups would double the length of what is a chain of dependent memory round trips
         static std::atomic<int> resident{0};
@@ -901,6 +915,7 @@ hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* ro
         if (inl) hipExtLaunchKernelGGL(accept_draw_kernel<true>, dgrid, block, 0, stream, t2, t3, 0, pd, io);
         else hipExtLaunchKernelGGL(accept_draw_kernel<false>, dgrid, block, 0, stream, t2, t3, 0, pd, io);
     } else {
+        if (!p.row_off) return hipErrorInvalidValue;
         hipExtLaunchKernelGGL(accept_finish_kernel, dim3(p.n_req), dim3(kFinishThreads), 0, stream, t2, t3, 0, p);
     }
     e = hipGetLastError();

@@ -11,7 +11,13 @@
 
 namespace {
 
-constexpr int kStages = 4;   // pinned staging buffers cycled between calls
+constexpr int kStages = 8;   // pinned staging buffers (and device copies of the tables) cycled between calls
+// A device copy of the tables may be overwritten only after the kernels that read it have finished.  An event
+// record between two kernels holds the second one up for several microseconds, so the library does not record
+// one behind every attention call: every kMarkEvery-th call leaves a marker on its stream, and an upload waits
+// for the first marker that lies behind the last reader of its slot (recording one on the spot if there is none).
+constexpr int kMarks = 4;
+constexpr int kMarkEvery = 4;
 
 inline size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
@@ -48,11 +54,17 @@ struct spin_ctx {
     int64_t cap_req = 0, cap_rows = 0, cap_pages = 0, cap_items = 0, cap_slots = 0;
     int64_t need_req = 0, need_rows = 0, need_pages = 0, need_items = 0, need_slots = 0;
     // device workspace
-    char* d_blob[kStages] = {nullptr, nullptr, nullptr, nullptr};   // tables of a call (items, orders, offsets, page table)
+    char* d_blob[kStages] = {};   // tables of a call (items, orders, offsets, page table)
     size_t blob_bytes = 0;
     hipStream_t copy_stream = nullptr;   // table uploads run here, beside the previous call's kernels
-    hipEvent_t ev_done[kStages] = {nullptr, nullptr, nullptr, nullptr};   // kernels reading d_blob[s] have finished
-    bool done_pending[kStages] = {false, false, false, false};
+    int64_t gen = 0;                       // attention calls launched from a device copy of their tables, so far
+    int64_t slot_gen[kStages];             // the latest of them that read d_blob[s] (-1: none) ...
+    hipStream_t slot_stream[kStages] = {}; // ... and the stream its kernels run on
+    hipEvent_t ev_mark[kMarks] = {};       // markers: all calls up to mark_gen[k] launched on mark_stream[k] have finished
+    int64_t mark_gen[kMarks];
+    hipStream_t mark_stream[kMarks] = {};
+    int64_t n_marks = 0;                   // markers recorded so far (the next one goes to n_marks % kMarks)
+    int64_t marked_gen = -1;               // the latest call behind which a marker was recorded
     uint16_t* d_part_o = nullptr;
     float* d_part_ml = nullptr;
     float* d_row_max = nullptr;    // acceptance row statistics
@@ -62,9 +74,9 @@ struct spin_ctx {
     double* d_draw_runs = nullptr; // run masses and last ids of the next-token draw
     int32_t* d_draw_last = nullptr;
     // pinned staging ring
-    char* h_stage[kStages] = {nullptr, nullptr, nullptr, nullptr};
-    hipEvent_t ev[kStages] = {nullptr, nullptr, nullptr, nullptr};
-    bool ev_pending[kStages] = {false, false, false, false};
+    char* h_stage[kStages] = {};
+    hipEvent_t ev[kStages] = {};
+    bool ev_pending[kStages] = {};
     int stage = 0;
     StagedPlan staged;
     bool reuse_plans = true;
@@ -142,6 +154,43 @@ size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
            2 * align16((req + 1) * 4) + align16(pages * 4) + align16(rows * 16) + 128;
 }
 
+// Leave a marker on `stream` behind everything launched so far.
+hipError_t record_marker(spin_ctx* c, hipStream_t stream, hipEvent_t* out) {
+    const int k = (int)(c->n_marks % kMarks);
+    hipError_t e = hipEventRecord(c->ev_mark[k], stream);
+    if (e != hipSuccess) return e;
+    c->mark_gen[k] = c->gen - 1;
+    c->mark_stream[k] = stream;
+    c->marked_gen = c->gen - 1;
+    ++c->n_marks;
+    if (out) *out = c->ev_mark[k];
+    return hipSuccess;
+}
+
+// Make the upload stream wait until the kernels that read d_blob[slot] have finished.
+hipError_t wait_for_readers(spin_ctx* c, int slot) {
+    const int64_t g0 = c->slot_gen[slot];
+    if (g0 < 0) return hipSuccess;
+    hipEvent_t m = nullptr;
+    int64_t best = INT64_MAX;
+    for (int k = 0; k < kMarks; ++k)   // the earliest marker behind that call, on its stream
+        if (c->mark_gen[k] >= g0 && c->mark_gen[k] < best && c->mark_stream[k] == c->slot_stream[slot]) {
+            best = c->mark_gen[k];
+            m = c->ev_mark[k];
+        }
+    if (!m) {
+        hipError_t e = record_marker(c, c->slot_stream[slot], &m);
+        if (e != hipSuccess) {
+            // (the stream is gone: whatever ran on it is waited for the plain way)
+            (void)hipGetLastError();
+            c->slot_gen[slot] = -1;
+            return hipDeviceSynchronize();
+        }
+    }
+    c->slot_gen[slot] = -1;
+    return hipStreamWaitEvent(c->copy_stream, m, 0);
+}
+
 // Next pinned staging buffer; waits until the copy that last used it has left the host.
 int next_stage(spin_ctx* c, char** out) {
     c->stage = (c->stage + 1) % kStages;
@@ -171,9 +220,10 @@ int spin_create(spin_ctx** out, int device_id) {
     spin_ctx* c = new spin_ctx();
     c->device = device_id;
     bool ok = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
-    for (int s = 0; s < kStages && ok; ++s)
-        ok = hipEventCreateWithFlags(&c->ev[s], hipEventDisableTiming) == hipSuccess &&
-             hipEventCreateWithFlags(&c->ev_done[s], hipEventDisableTiming) == hipSuccess;
+    for (int s = 0; s < kStages; ++s) c->slot_gen[s] = -1;
+    for (int k = 0; k < kMarks; ++k) c->mark_gen[k] = -1;
+    for (int s = 0; s < kStages && ok; ++s) ok = hipEventCreateWithFlags(&c->ev[s], hipEventDisableTiming) == hipSuccess;
+    for (int k = 0; k < kMarks && ok; ++k) ok = hipEventCreateWithFlags(&c->ev_mark[k], hipEventDisableTiming) == hipSuccess;
     ok = ok && spin::resolve_static_scratch() == hipSuccess;
     if (!ok) {
         spin_destroy(c);
@@ -189,10 +239,10 @@ void spin_destroy(spin_ctx* ctx) {
     (void)hipDeviceSynchronize();
     free_workspace(ctx);
     free_profile(ctx);
-    for (int s = 0; s < kStages; ++s) {
+    for (int s = 0; s < kStages; ++s)
         if (ctx->ev[s]) (void)hipEventDestroy(ctx->ev[s]);
-        if (ctx->ev_done[s]) (void)hipEventDestroy(ctx->ev_done[s]);
-    }
+    for (int k = 0; k < kMarks; ++k)
+        if (ctx->ev_mark[k]) (void)hipEventDestroy(ctx->ev_mark[k]);
     if (ctx->copy_stream) (void)hipStreamDestroy(ctx->copy_stream);
     delete ctx;
 }
@@ -235,7 +285,10 @@ int spin_reserve(spin_ctx* ctx, int64_t max_req, int64_t max_rows, int64_t max_p
     e = hipDeviceSynchronize();
     if (e != hipSuccess) return fail_hip(ctx, e, "hipDeviceSynchronize");
     free_workspace(ctx);
-    for (int s = 0; s < kStages; ++s) ctx->ev_pending[s] = ctx->done_pending[s] = false;
+    for (int s = 0; s < kStages; ++s) {   // (the device has just been synchronised: nothing reads the old copies)
+        ctx->ev_pending[s] = false;
+        ctx->slot_gen[s] = -1;
+    }
     ctx->cap_req = ctx->cap_rows = ctx->cap_pages = ctx->cap_items = ctx->cap_slots = 0;
     const size_t blob = blob_size(max_req, max_rows, max_pages, max_items);
     const int64_t stat_rows = 2 * max_rows + max_req + 1;
@@ -435,10 +488,8 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
         sp.bytes = off;
         sp.in_place = off <= kInPlaceBytes && sp.n_queued[0] + sp.n_queued[1] + sp.n_queued[2] == 0;
         if (!sp.in_place) {
-            if (ctx->done_pending[sp.slot]) {
-                e = hipStreamWaitEvent(ctx->copy_stream, ctx->ev_done[sp.slot], 0);
-                if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
-            }
+            e = wait_for_readers(ctx, sp.slot);
+            if (e != hipSuccess) return fail_hip(ctx, e, "waiting for the previous readers of the table copy");
             e = hipMemcpyAsync(ctx->d_blob[sp.slot], h, off, hipMemcpyHostToDevice, ctx->copy_stream);
             if (e != hipSuccess) return fail_hip(ctx, e, "hipMemcpyAsync");
             e = hipEventRecord(ctx->ev[sp.slot], ctx->copy_stream);
@@ -475,9 +526,14 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     const int slot = sp.slot;
     // (with inline tables the table pointers below are offsets into the kernels' inline-table argument)
     const uintptr_t blob = sp.in_place ? 0 : (uintptr_t)ctx->d_blob[slot];
-    if (!sp.in_place) {
-        e = hipStreamWaitEvent(stream, ctx->ev[slot], 0);   // the upload (long done on a hit)
-        if (e != hipSuccess) return fail_hip(ctx, e, "hipStreamWaitEvent");
+    if (!sp.in_place && ctx->ev_pending[slot]) {
+        // The upload must have landed before the kernels start.  The host waits for it here (some ten
+        // microseconds, while the GPU is busy with earlier calls) instead of making the stream wait: a wait
+        // for another stream's event, put between two kernels, holds the second one up for several microseconds
+        // even when the event has long passed.
+        e = hipEventSynchronize(ctx->ev[slot]);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventSynchronize");
+        ctx->ev_pending[slot] = false;
     }
     int pshift = 0;
     while ((1 << pshift) < kv->page_size) ++pshift;
@@ -534,10 +590,13 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
                           pe ? &timing : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
     if (pe) ctx->prof_attn_second[ctx->prof_attn_used - 1] = timing.second;
-    if (!sp.in_place) {   // (tables passed in the arguments were copied at the launch: their staging buffer is free at once)
-        e = hipEventRecord(ctx->ev_done[slot], stream);
-        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-        ctx->done_pending[slot] = true;
+    if (!sp.in_place) {   // (tables passed in the arguments were copied at the launch: nothing on the device to protect)
+        ctx->slot_gen[slot] = ctx->gen++;
+        ctx->slot_stream[slot] = stream;
+        if (ctx->gen - 1 - ctx->marked_gen >= kMarkEvery) {
+            e = record_marker(ctx, stream, nullptr);
+            if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+        }
     }
     return SPIN_OK;
 }
@@ -661,20 +720,8 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
     hipStream_t stream = (hipStream_t)hip_stream;
-    char* h = nullptr;
-    int rc = next_stage(ctx, &h);
-    if (rc) return rc;
-    // The per-request row offsets (two ints per workgroup) are read by the kernel straight from this
-    // pinned, device-mapped buffer: no copy, no bubble on the stream.  The buffer is reused only after
-    // the event recorded behind the kernels has passed.
-    memcpy(h, ctx->row_off_host.data(), (size_t)(n_req + 1) * 4);
-    void* row_off_dev = nullptr;
-    e = hipHostGetDevicePointer(&row_off_dev, h, 0);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
-    const int slot = ctx->stage;
 
     spin::AcceptParams p = {};
-    p.row_off = (const int32_t*)row_off_dev;
     p.draft_tokens = draft_tokens_dev;
     p.target_logits = target_logits_dev;
     p.draft_logits = draft_logits_dev;
@@ -692,15 +739,34 @@ int spin_accept(spin_ctx* ctx, int32_t mode, int32_t n_req, const int32_t* draft
     p.n_rows = (int32_t)rows;
     p.vocab = vocab;
     p.mode = mode;
+    // The per-request row offsets travel in the kernels' arguments where the kernels take them there (batches
+    // of up to 959 requests on the usual paths).  Otherwise the kernels read them (two ints per workgroup)
+    // straight from a pinned, device-mapped staging buffer, which is reused only after an event recorded behind
+    // the kernels has passed -- an event record on the stream costs the next kernel several microseconds, which
+    // is why the first form goes without.
+    int slot = -1;
+    if (spin::accept_reads_row_off(p, max_draft)) {
+        char* h = nullptr;
+        int rc = next_stage(ctx, &h);
+        if (rc) return rc;
+        memcpy(h, ctx->row_off_host.data(), (size_t)(n_req + 1) * 4);
+        void* row_off_dev = nullptr;
+        e = hipHostGetDevicePointer(&row_off_dev, h, 0);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
+        p.row_off = (const int32_t*)row_off_dev;
+        slot = ctx->stage;
+    }
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_accept, ctx->prof_accept_used, ctx->prof_accept_seen);
     spin::LaunchTiming timing = {};
     if (pe) memcpy(timing.ev, pe, sizeof timing.ev);
     e = spin::launch_accept(p, max_draft, ctx->row_off_host.data(), stream, pe ? &timing : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "acceptance launch");
     if (pe) ctx->prof_accept_second[ctx->prof_accept_used - 1] = timing.second;
-    e = hipEventRecord(ctx->ev[slot], stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    ctx->ev_pending[slot] = true;
+    if (slot >= 0) {
+        e = hipEventRecord(ctx->ev[slot], stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+        ctx->ev_pending[slot] = true;
+    }
     return SPIN_OK;
 }
 

@@ -116,6 +116,10 @@ constexpr int kMaxVocab = 1 << 20;
 hipError_t launch_accept(const AcceptParams& p, int max_draft, const int32_t* row_off_host, hipStream_t stream,
                          LaunchTiming* timing);
 
+// Whether the kernels launch_accept would launch for p read p.row_off (else the offsets travel in the kernel
+// arguments and p.row_off may be null).
+bool accept_reads_row_off(const AcceptParams& p, int max_draft);
+
 // Bytes of p.draw_runs (returned) and p.draw_last for batches of up to n_req requests.
 size_t accept_draw_scratch_bytes(int64_t n_req, size_t* last_bytes);
 
