@@ -591,6 +591,14 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");
     if (pe) ctx->prof_attn_second[ctx->prof_attn_used - 1] = timing.second;
     if (!sp.in_place) {   // (tables passed in the arguments were copied at the launch: nothing on the device to protect)
+        if (ctx->slot_gen[slot] >= 0 && ctx->slot_stream[slot] != stream) {
+            // The same copy was last read on another stream (a reused plan): that stream gets a marker and this one
+            // waits for it, so that the markers of this stream stand for the earlier readers as well.
+            hipEvent_t m = nullptr;
+            e = record_marker(ctx, ctx->slot_stream[slot], &m);
+            if (e == hipSuccess) e = hipStreamWaitEvent(stream, m, 0);
+            if (e != hipSuccess) return fail_hip(ctx, e, "ordering two streams that read the same tables");
+        }
         ctx->slot_gen[slot] = ctx->gen++;
         ctx->slot_stream[slot] = stream;
         if (ctx->gen - 1 - ctx->marked_gen >= kMarkEvery) {

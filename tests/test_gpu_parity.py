@@ -1272,6 +1272,48 @@ def test_plan_reuse_with_queued_chunks_and_other_calls_between(ctx):
         assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
 
 
+def test_many_calls_in_flight_keep_their_tables(ctx):
+    """Forty calls with three different request tables, queued without a pause: the host runs many calls ahead of the
+    GPU, so every device copy of a call's tables is overwritten several times while earlier calls are still queued
+    (the library must hold each upload back until the kernels that read the previous copy have finished), and
+    calls on a second stream share those copies (reused plans).  Every output must be what the call gives alone."""
+    cfg = make_cfg("ring", 24, 8, 4, 128)
+    rng = np.random.default_rng(5)
+    batches = []
+    for k in range(3):
+        prefix = rng.integers(200, 3000, 24); draft = rng.integers(1, 9, 24)
+        batches.append(si.make_verify_batch(cfg, 80 + k, device="cuda", prefix_len=prefix, draft_len=draft))
+    tabs = [ctx.make_table(b.table.prefix_len, b.table.draft_len, b.table.q_offset, b.table.pt_offset, b.table.page_table)
+            for b in batches]
+    alone = [hip_attention(ctx, b) for b in batches]
+    for b, a in zip(batches, alone):
+        assert_close(a, oracle_attention(b, 0.0), "ring: alone")
+    side = torch.cuda.Stream()
+    outs = []
+    torch.cuda.synchronize()
+    for call in range(40):
+        k = (call * 7 + call // 5) % 3
+        b = batches[k]
+        out = torch.full_like(b.q, float("nan"))
+        # every fifth call repeats the previous tables (a reused plan), every tenth on the other stream
+        if call % 5 == 4:
+            k = outs[-1][0]
+            b = batches[k]
+            out = torch.full_like(b.q, float("nan"))
+        if call % 10 == 9:
+            # (calls of one context must not overlap -- they share its partial-result workspace -- so the two streams
+            # hand over to each other; what is tested is that the table copies stay intact across the change)
+            side.wait_stream(torch.cuda.current_stream())
+            ctx.verify_attn(tabs[k], b.k_pool, b.v_pool, b.q, out, cfg.n_q_heads, stream=side)
+            torch.cuda.current_stream().wait_stream(side)
+        else:
+            ctx.verify_attn(tabs[k], b.k_pool, b.v_pool, b.q, out, cfg.n_q_heads)
+        outs.append((k, out))
+    torch.cuda.synchronize()
+    for call, (k, out) in enumerate(outs):
+        assert torch.equal(out.view(torch.int16), alone[k].view(torch.int16)), f"call {call} (tables {k})"
+
+
 def test_two_contexts_on_two_streams(ctx):
     """Calls of two contexts queued on two streams with nothing in between give what each gives alone."""
     import paper_2503_15921_amd as spin
