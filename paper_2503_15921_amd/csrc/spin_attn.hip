@@ -38,6 +38,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
+
+#include <algorithm>
 #include <string.h>
 
 #include "spin_device.h"
@@ -1014,9 +1016,7 @@ __global__ __launch_bounds__(64 * kJoinWaves) void join_partials_small_kernel(Jo
 
 // Scatter the draft tokens' K and V rows into their page slots: one workgroup per packed row, 16
 // bytes per lane and step, over all KV heads of K and then of V.
-__global__ __launch_bounds__(256) void append_kv_kernel(AppendParams P) {
-    const int row = blockIdx.x;
-    const int64_t slot = P.dst_slot[row];
+__device__ __forceinline__ void append_kv_body(const AppendParams& P, int row, int64_t slot) {
     const int64_t page = slot >> P.page_shift, in_page = slot & ((1 << P.page_shift) - 1);
     const int per_head = P.head_dim >> 3, per_pool = P.n_kv_heads * per_head;
     const int64_t dst0 = page * P.page_stride + in_page * P.token_stride;
@@ -1033,9 +1033,35 @@ __global__ __launch_bounds__(256) void append_kv_kernel(AppendParams P) {
     }
 }
 
-hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
+__global__ __launch_bounds__(256) void append_kv_kernel(AppendParams P) {
+    append_kv_body(P, blockIdx.x, P.dst_slot[blockIdx.x]);
+}
+// the same with the destination slots in the kernel arguments (batches of up to kInlineAppendRows draft rows)
+struct InlineSlots {
+    int32_t slot[kInlineAppendRows];
+};
+__global__ __launch_bounds__(256) void append_kv_small_kernel(AppendParams P, InlineSlots s, int row0) {
+    append_kv_body(P, row0 + blockIdx.x, s.slot[blockIdx.x]);
+}
+
+hipError_t launch_append(const AppendParams& p, const int64_t* dst_slot_host, hipStream_t stream) {
     if (p.n_rows <= 0) return hipSuccess;
-    hipLaunchKernelGGL(append_kv_kernel, dim3((unsigned)p.n_rows), dim3(256), 0, stream, p);
+    if (dst_slot_host && p.n_rows <= kInlineAppendRows * kInlineAppendLaunches) {
+        // (kernels launched back to back start without a gap; an event record between two kernels costs more
+        // than a second launch)
+        for (int row0 = 0; row0 < p.n_rows; row0 += kInlineAppendRows) {
+            const int n = std::min(kInlineAppendRows, p.n_rows - row0);
+            InlineSlots s;
+            for (int i = 0; i < n; ++i) {
+                if (dst_slot_host[row0 + i] < 0 || dst_slot_host[row0 + i] > INT32_MAX) return hipErrorInvalidValue;
+                s.slot[i] = (int32_t)dst_slot_host[row0 + i];
+            }
+            hipLaunchKernelGGL(append_kv_small_kernel, dim3((unsigned)n), dim3(256), 0, stream, p, s, row0);
+        }
+    } else {
+        if (!p.dst_slot) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(append_kv_kernel, dim3((unsigned)p.n_rows), dim3(256), 0, stream, p);
+    }
     return hipGetLastError();
 }
 

@@ -78,6 +78,7 @@ struct spin_ctx {
     hipEvent_t ev[kStages] = {};
     bool ev_pending[kStages] = {};
     int stage = 0;
+    std::vector<int64_t> slot_host;   // destination slots of spin_append_kv when they travel in the kernel's arguments
     StagedPlan staged;
     bool reuse_plans = true;
     spin::Plan plan;
@@ -653,11 +654,19 @@ int spin_append_kv(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* 
     hipError_t e = hipSetDevice(ctx->device);
     if (e != hipSuccess) return fail_hip(ctx, e, "hipSetDevice");
     hipStream_t stream = (hipStream_t)hip_stream;
-    // destination slot of every packed row, read by the kernel from the pinned, device-mapped buffer
+    // Destination slot of every packed row.  Small batches carry them in the kernel's arguments; otherwise the
+    // kernel reads them from a pinned, device-mapped staging buffer, which needs an event behind the kernel before
+    // it is reused (and an event record on the stream costs the attention kernel that follows several microseconds).
+    const bool inline_slots = n_rows <= spin::kInlineAppendRows * spin::kInlineAppendLaunches &&
+                              (int64_t)kv->n_pages * kv->page_size <= INT32_MAX;
     char* h = nullptr;
-    rc = next_stage(ctx, &h);
-    if (rc) return rc;
-    int64_t* dst = (int64_t*)h;
+    if (inline_slots) {
+        ctx->slot_host.resize((size_t)n_rows);
+    } else {
+        rc = next_stage(ctx, &h);
+        if (rc) return rc;
+    }
+    int64_t* dst = inline_slots ? ctx->slot_host.data() : (int64_t*)h;
     for (int64_t i = 0; i < n_req; ++i) {
         const int32_t* pt = table->page_table + table->pt_offset[i];
         for (int32_t t = 0; t < table->draft_len[i]; ++t) {
@@ -666,8 +675,10 @@ int spin_append_kv(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* 
         }
     }
     void* dst_dev = nullptr;
-    e = hipHostGetDevicePointer(&dst_dev, h, 0);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
+    if (!inline_slots) {
+        e = hipHostGetDevicePointer(&dst_dev, h, 0);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipHostGetDevicePointer");
+    }
     const int slot = ctx->stage;
     spin::AppendParams p = {};
     p.dst_slot = (const int64_t*)dst_dev;
@@ -684,11 +695,13 @@ int spin_append_kv(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table* 
     int pshift = 0;
     while ((1 << pshift) < kv->page_size) ++pshift;
     p.page_shift = pshift;
-    e = spin::launch_append(p, stream);
+    e = spin::launch_append(p, inline_slots ? dst : nullptr, stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "append launch");
-    e = hipEventRecord(ctx->ev[slot], stream);
-    if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
-    ctx->ev_pending[slot] = true;
+    if (!inline_slots) {
+        e = hipEventRecord(ctx->ev[slot], stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "hipEventRecord");
+        ctx->ev_pending[slot] = true;
+    }
     return SPIN_OK;
 }
 

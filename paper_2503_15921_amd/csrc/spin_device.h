@@ -84,7 +84,12 @@ struct AppendParams {
     int32_t n_rows, n_kv_heads, head_dim, page_shift;
 };
 
-hipError_t launch_append(const AppendParams& p, hipStream_t stream);
+// Batches of up to kInlineAppendRows * kInlineAppendLaunches draft rows whose slots fit 32 bits bring their
+// destination slots in the kernel arguments, kInlineAppendRows per launch (dst_slot_host: the slots as the host
+// holds them; p.dst_slot may then be null); larger ones are read by the kernel from p.dst_slot.
+constexpr int kInlineAppendRows = 960;
+constexpr int kInlineAppendLaunches = 4;
+hipError_t launch_append(const AppendParams& p, const int64_t* dst_slot_host, hipStream_t stream);
 
 struct AcceptParams {
     const int32_t* row_off;        // [n_req+1] first draft row of each request (device)

@@ -621,6 +621,23 @@ def test_append_kv_bit_exact(ctx, name, seed, page):
     assert np.array_equal(si.bf16_bits(b.v_pool), want_v)
 
 
+@pytest.mark.parametrize("n_req", [61, 130, 300])
+def test_append_kv_many_rows(ctx, n_req):
+    # 16 draft rows per request: 976, 2080 and 4800 rows -- two and three launches with the destination slots in the
+    # kernel arguments, and (beyond 3840 rows) the kernel that reads them from the staging buffer
+    cfg = make_cfg(f"append-rows-{n_req}", n_req, 2, 2, 64)
+    rng = np.random.default_rng(n_req)
+    b = si.make_verify_batch(cfg, 43, device="cuda", prefix_len=rng.integers(0, 70, n_req), draft_len=np.full(n_req, 16),
+                             poison_unused=True)
+    k_new, v_new = new_rows(b, 143)
+    want_k, want_v = oracle_append(b, k_new, v_new)
+    t = b.table
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    ctx.append_kv(tab, b.k_pool, b.v_pool, k_new, v_new)
+    torch.cuda.synchronize()
+    assert np.array_equal(si.bf16_bits(b.k_pool), want_k) and np.array_equal(si.bf16_bits(b.v_pool), want_v)
+
+
 def test_append_then_verify_on_one_stream(ctx):
     """Append and attention queued back to back with no synchronisation in between."""
     cfg = make_cfg("append-verify", 6, 8, 2, 128)
