@@ -179,7 +179,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", default="13b")
     ap.add_argument("--seed", type=int, default=3)
     ap.add_argument("--page-size", type=int, default=0, help="tokens per KV page (0 = the configuration's, 16)")
