@@ -103,6 +103,7 @@ __device__ __forceinline__ void use_inline_tables(AttnParams& P) {
     const char* base = inline_tables_base<AttnParams>();
     rebase(P.pieces, base);
     rebase(P.wave_begin, base);
+    rebase(P.share_first, base);
     rebase(P.page_table, base);
     if (TREE) rebase(P.tree_rows, base);
 }
@@ -255,16 +256,23 @@ __device__ __forceinline__ void verify_attn_body(const AttnParams& P) {
         a = (const char*)(pool + (int64_t)pga * P.page_stride + head_off + (int64_t)(kb & pmask) * P.token_stride);
         b = (const char*)(pool + (int64_t)pgb * P.page_stride + head_off + (int64_t)((kb + 16) & pmask) * P.token_stride);
     };
+    auto load_k_runs = [&](const char* a, const char* b) {   // K of a block given as two runs of 16 rows
+        constexpr int KPI = 64 / DCH;            // keys per load instruction
+#pragma unroll
+        for (int i = 0; i < KLOADS; ++i) {
+            const int key = i * KPI;             // first key of this instruction within the block
+            Kr[i] = stream_load((key < 16 ? a : b) + (int64_t)(key & 15) * ts2, k_lane_off);
+        }
+    };
+    auto load_v_runs = [&](const char* a, const char* b) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) Vr[j] = stream_load((j < 4 ? a : b) + (int64_t)(j & 3) * ts2, v_lane_off);
+    };
     auto load_k = [&](int buf, int pg0, int k1, int64_t head_off, int kb) {
         if (tile_layout && !(kb & 31) && kb + 32 <= k1) {
             const char *a, *b;
             page_bases(P.k_pool, buf, pg0, head_off, kb, a, b);
-            constexpr int KPI = 64 / DCH;            // keys per load instruction
-#pragma unroll
-            for (int i = 0; i < KLOADS; ++i) {
-                const int key = i * KPI;             // first key of this instruction within the block
-                Kr[i] = stream_load((key < 16 ? a : b) + (int64_t)(key & 15) * ts2, k_lane_off);
-            }
+            load_k_runs(a, b);
         } else {
 #pragma unroll
             for (int i = 0; i < KLOADS; ++i) {
@@ -277,8 +285,7 @@ __device__ __forceinline__ void verify_attn_body(const AttnParams& P) {
         if (tile_layout && !(kb & 31) && kb + 32 <= k1) {
             const char *a, *b;
             page_bases(P.v_pool, buf, pg0, head_off, kb, a, b);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) Vr[j] = stream_load((j < 4 ? a : b) + (int64_t)(j & 3) * ts2, v_lane_off);
+            load_v_runs(a, b);
         } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -288,7 +295,21 @@ __device__ __forceinline__ void verify_attn_body(const AttnParams& P) {
         }
     };
 
-    // ---- start-up: the first four descriptors, page ids of the first three pieces in LDS
+    // ---- start-up.  The share's first K/V block is requested at once when the host has resolved it (its page ids
+    // come with the share): the descriptors, page ids and queries that the rest needs take three dependent round
+    // trips, and the block arrives while they are made.
+    typedef const int32_t __attribute__((address_space(4)))* ConstInts;
+    const ConstInts first = (ConstInts)(uintptr_t)(P.share_first + (int64_t)share * 4);
+    const int first_pga = first[0], first_pgb = first[1], first_kvh = first[2], first_k0 = first[3];
+    const bool ahead = first_k0 >= 0;
+    if (ahead) {
+        const int64_t head_off = (int64_t)first_kvh * P.head_stride;
+        const int64_t oa = (int64_t)first_pga * P.page_stride + head_off + (int64_t)(first_k0 & pmask) * P.token_stride;
+        const int64_t ob = (int64_t)first_pgb * P.page_stride + head_off + (int64_t)((first_k0 + 16) & pmask) * P.token_stride;
+        load_k_runs((const char*)(P.k_pool + oa), (const char*)(P.k_pool + ob));
+        load_v_runs((const char*)(P.v_pool + oa), (const char*)(P.v_pool + ob));
+    }
+    // The first four descriptors, page ids of the first three pieces in LDS
     Piece cp, p1, p2, p3;
     fetch_piece(0, cp);
     fetch_piece(1, p1);
@@ -312,7 +333,7 @@ __device__ __forceinline__ void verify_attn_body(const AttnParams& P) {
     uint64_t anc[NT];   // TREE: draft keys (bit u = key prefix + u) each row may see
     int pfx = 0;        // TREE: the request's prefix length
     int cb = 0;   // LDS page-id buffer of the current piece; the next piece's is (cb + 1) % 3
-    {
+    if (!ahead) {
         const int64_t head = (int64_t)(cp.head_flags & kPieceHeadMask) * P.head_stride;
         load_k(cb, cp.k0 >> pshift, cp.k1, head, cp.k0);
         load_v(cb, cp.k0 >> pshift, cp.k1, head, cp.k0);
@@ -1093,7 +1114,8 @@ hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves) {
 
 template <int D, class E>
 static hipError_t launch_attn_d(const AttnParams& base, const Piece* const pieces_dev[3],
-                                const int32_t* const wave_begin_dev[3], const int32_t n_waves[3],
+                                const int32_t* const wave_begin_dev[3], const int32_t* const share_first_dev[3],
+                                const int32_t n_waves[3],
                                 const int32_t n_queued[3], int32_t* queues_dev, const JoinParams& jp,
                                 const InlineTables* tables, hipStream_t stream, LaunchTiming* timing) {
     int first_cls = -1, last_cls = -1;   // (one class per call in practice; with several, the time spans them all)
@@ -1108,6 +1130,7 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
         AttnParams p = base;
         p.pieces = pieces_dev[cls];
         p.wave_begin = wave_begin_dev[cls];
+        p.share_first = share_first_dev[cls];
         p.queue = queues_dev + cls;
         p.n_queued = n_queued[cls];
         if (cls == 2 && p.n_queued != 0) return hipErrorInvalidValue;   // the grouped-query kernel takes no queued chunks
@@ -1135,7 +1158,8 @@ static hipError_t launch_attn_d(const AttnParams& base, const Piece* const piece
 }
 
 hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Piece* const pieces_dev[3],
-                       const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
+                       const int32_t* const wave_begin_dev[3], const int32_t* const share_first_dev[3],
+                       const int32_t n_waves[3], const int32_t n_queued[3],
                        int32_t* queues_dev, const JoinParams& jp, const void* inline_tables, size_t inline_bytes,
                        hipStream_t stream, LaunchTiming* timing) {
     InlineTables storage;
@@ -1148,11 +1172,11 @@ hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Pie
         return hipErrorInvalidValue;
     }
     if (head_dim == 128)
-        return f16 ? launch_attn_d<128, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing)
-                   : launch_attn_d<128, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing);
+        return f16 ? launch_attn_d<128, F16>(base, pieces_dev, wave_begin_dev, share_first_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing)
+                   : launch_attn_d<128, Bf16>(base, pieces_dev, wave_begin_dev, share_first_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing);
     if (head_dim == 64)
-        return f16 ? launch_attn_d<64, F16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing)
-                   : launch_attn_d<64, Bf16>(base, pieces_dev, wave_begin_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing);
+        return f16 ? launch_attn_d<64, F16>(base, pieces_dev, wave_begin_dev, share_first_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing)
+                   : launch_attn_d<64, Bf16>(base, pieces_dev, wave_begin_dev, share_first_dev, n_waves, n_queued, queues_dev, jp, tables, stream, timing);
     return hipErrorInvalidValue;
 }
 

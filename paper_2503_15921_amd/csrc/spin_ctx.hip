@@ -39,7 +39,7 @@ struct StagedPlan {
     std::vector<spin_subreq> subs;
     std::vector<uint64_t> tree;
     // launch data
-    size_t off_pieces = 0, off_waves[3] = {0, 0, 0}, off_queues = 0, off_ppos = 0, off_strips = 0, off_qoff = 0,
+    size_t off_pieces = 0, off_waves[3] = {0, 0, 0}, off_first[3] = {0, 0, 0}, off_queues = 0, off_ppos = 0, off_strips = 0, off_qoff = 0,
            off_tasks = 0, off_pt = 0, off_tree = 0;
     int32_t n_waves_launch[3] = {0, 0, 0}, n_queued[3] = {0, 0, 0}, class_piece_begin[3] = {0, 0, 0};
     int32_t n_tasks = 0, max_pairs = 0;
@@ -151,7 +151,7 @@ constexpr int kMaxWaves = 16384;   // wavefronts per launch the staging buffers 
 // pieces | per-class wavefront ranges | (strip, head) piece ranges | strip ranges | row offsets | tasks | page table
 size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
     // every share holds at least one piece, so there are at most `items` share boundaries in all
-    return align16(items * sizeof(spin::Piece)) + align16(items * 4) + 3 * 32 + 2 * align16(items * 8) +
+    return align16(items * sizeof(spin::Piece)) + align16(items * 4) + align16(items * 16) + 6 * 32 + 2 * align16(items * 8) +
            2 * align16((req + 1) * 4) + align16(pages * 4) + align16(rows * 16) + 128;
 }
 
@@ -452,6 +452,7 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
             sp.n_queued[c] = n_shares - plan.n_static[c];
             sp.class_piece_begin[c] = plan.class_piece_begin[c];
             sp.off_waves[c] = put(plan.wave_begin[c].data(), plan.wave_begin[c].size() * 4);
+            sp.off_first[c] = put(plan.share_first[c].data(), plan.share_first[c].size() * 4);
         }
         const int32_t zero_queues[4] = {0, 0, 0, 0};   // the chunk queues start at zero
         sp.off_queues = put(zero_queues, sizeof zero_queues);
@@ -564,9 +565,11 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
 
     const spin::Piece* pieces_dev[3];
     const int32_t* waves_dev[3];
+    const int32_t* first_dev[3];
     for (int c = 0; c < 3; ++c) {
         pieces_dev[c] = (const spin::Piece*)(blob + sp.off_pieces) + sp.class_piece_begin[c];
         waves_dev[c] = (const int32_t*)(blob + sp.off_waves[c]);
+        first_dev[c] = (const int32_t*)(blob + sp.off_first[c]);
     }
     spin::JoinParams jp = {};
     jp.pieces = (const spin::Piece*)(blob + sp.off_pieces);
@@ -586,7 +589,7 @@ int verify_attn_impl(spin_ctx* ctx, const spin_kv_desc* kv, const spin_req_table
     hipEvent_t* pe = prof_slot(ctx, ctx->prof_attn, ctx->prof_attn_used, ctx->prof_attn_seen);
     spin::LaunchTiming timing = {};
     if (pe) memcpy(timing.ev, pe, sizeof timing.ev);
-    e = spin::launch_attn(kv->head_dim, kv->dtype == SPIN_DTYPE_F16, ap, pieces_dev, waves_dev, sp.n_waves_launch, sp.n_queued,
+    e = spin::launch_attn(kv->head_dim, kv->dtype == SPIN_DTYPE_F16, ap, pieces_dev, waves_dev, first_dev, sp.n_waves_launch, sp.n_queued,
                           (int32_t*)(blob + sp.off_queues), jp, sp.in_place ? ctx->h_stage[slot] : nullptr, sp.bytes, stream,
                           pe ? &timing : nullptr);
     if (e != hipSuccess) return fail_hip(ctx, e, "attention launch");

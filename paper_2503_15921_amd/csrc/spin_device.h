@@ -28,6 +28,8 @@ struct AttnParams {
     const uint16_t* q;
     const Piece* pieces;         // (*) pieces of one column-tile class, in streaming order
     const int32_t* wave_begin;   // (*) [n_shares + 1] pieces of each share: gridDim.x per-wavefront shares, then queued chunks
+    const int32_t* share_first;  // (*) [n_shares][4] first block of each share: page ids of its two 16-key halves, KV head, first
+                                 // key (-1: the block is not requested ahead); single-wavefront kernels only
     int32_t* queue;              // next queued chunk to hand out (zero at launch)
     int32_t n_queued;
     const int32_t* page_table;   // (*)
@@ -70,7 +72,8 @@ hipError_t attn_resident_waves(int head_dim, int cls, int* n_waves);
 // attention kernel (first) and the join kernel (second).  inline_tables (may be null): the tables themselves, at most
 // kInlineTableBytes of them, to be passed in the kernel arguments (base.inline_tables / jp.inline_tables set).
 hipError_t launch_attn(int head_dim, bool f16, const AttnParams& base, const Piece* const pieces_dev[3],
-                       const int32_t* const wave_begin_dev[3], const int32_t n_waves[3], const int32_t n_queued[3],
+                       const int32_t* const wave_begin_dev[3], const int32_t* const share_first_dev[3],
+                       const int32_t n_waves[3], const int32_t n_queued[3],
                        int32_t* queues_dev, const JoinParams& jp, const void* inline_tables, size_t inline_bytes,
                        hipStream_t stream, LaunchTiming* timing);
 

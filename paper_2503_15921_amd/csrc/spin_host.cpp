@@ -281,6 +281,7 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
         plan.class_piece_begin[c] = (int32_t)plan.pieces.size();
         std::vector<int32_t>& wb = plan.wave_begin[c];
         wb.clear();
+        plan.share_first[c].clear();
         const int64_t T = plan.class_blocks[c];
         if (T == 0) continue;
         const int64_t W = std::max<int64_t>(1, std::min<int64_t>(n_waves[c], T / kMinBlocksPerWave));
@@ -381,6 +382,19 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
             }
         }
         while ((int64_t)wb.size() < n_shares + 1) wb.push_back((int32_t)(plan.pieces.size() - plan.class_piece_begin[c]));
+        // What a wavefront needs to request the first K/V block of a share before it has read anything else.
+        std::vector<int32_t>& sf = plan.share_first[c];
+        sf.assign((size_t)n_shares * 4, 0);
+        for (int64_t s = 0; s < n_shares; ++s) {
+            sf[s * 4 + 3] = -1;
+            if (wb[s] >= wb[s + 1] || !t->pt_offset || !t->page_table || page_size < 16) continue;
+            const Piece& pc = plan.pieces[(size_t)plan.class_piece_begin[c] + wb[s]];
+            if ((pc.k0 & 31) || pc.k0 + 32 > pc.k1) continue;
+            sf[s * 4 + 0] = t->page_table[pc.pt_base + pc.k0 / page_size];
+            sf[s * 4 + 1] = t->page_table[pc.pt_base + (pc.k0 + 16) / page_size];
+            sf[s * 4 + 2] = pc.head_flags & kPieceHeadMask;
+            sf[s * 4 + 3] = pc.k0;
+        }
     }
     plan.class_piece_begin[3] = (int32_t)plan.pieces.size();
     plan.part_slots = slots;
