@@ -24,7 +24,10 @@
  *     them, the library never frees or resizes them and never writes to an input.
  *   - Calls that take a stream only enqueue work on it (HIP stream handle passed as void*;
  *     NULL = the default stream).  All errors the host can see are reported before anything is
- *     launched.  Outputs are valid once the stream has been synchronised.
+ *     launched.  Outputs are valid once the stream has been synchronised.  The calls do not wait
+ *     for the stream; spin_verify_attn may hold the host for the few microseconds its own upload
+ *     of the call's tables (a copy on a stream of the context) takes, so that nothing but kernels
+ *     has to go onto the caller's stream.
  *   - Request i has prefix length p_i >= 0 (tokens whose K/V are cached and that ask nothing)
  *     and draft length g_i >= 1 (tokens whose K/V are ALSO already in the cache, at positions
  *     p_i .. p_i+g_i-1, and which each issue one query row).  Draft row t sees keys 0 .. p_i+t.
