@@ -1331,6 +1331,29 @@ def test_many_calls_in_flight_keep_their_tables(ctx):
         assert torch.equal(out.view(torch.int16), alone[k].view(torch.int16)), f"call {call} (tables {k})"
 
 
+def test_host_far_ahead_of_the_gpu_keeps_tables_apart(ctx):
+    """Forty-eight calls of 7B-shaped batches with three different tables: each call's kernels run longer than the
+    host needs to plan the next, so the host fills the whole ring of table copies and has to wait for slots."""
+    batches = [si.make_verify_batch(si.CONFIGS["7b"], 20 + k, device="cuda") for k in range(3)]
+    tabs = [ctx.make_table(b.table.prefix_len, b.table.draft_len, b.table.q_offset, b.table.pt_offset, b.table.page_table)
+            for b in batches]
+    alone = [hip_attention(ctx, b) for b in batches]
+    ctx.set_plan_reuse(False)
+    try:
+        outs = []
+        torch.cuda.synchronize()
+        for call in range(48):
+            k = (call * 5 + call // 7) % 3
+            out = torch.full_like(batches[k].q, float("nan"))
+            ctx.verify_attn(tabs[k], batches[k].k_pool, batches[k].v_pool, batches[k].q, out, batches[k].cfg.n_q_heads)
+            outs.append((k, out))
+        torch.cuda.synchronize()
+    finally:
+        ctx.set_plan_reuse(True)
+    for call, (k, out) in enumerate(outs):
+        assert torch.equal(out.view(torch.int16), alone[k].view(torch.int16)), f"call {call} (tables {k})"
+
+
 def test_two_contexts_on_two_streams(ctx):
     """Calls of two contexts queued on two streams with nothing in between give what each gives alone."""
     import paper_2503_15921_amd as spin
