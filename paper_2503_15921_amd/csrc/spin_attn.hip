@@ -642,11 +642,9 @@ __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
         struct RegSet {
             u32x4 Kr[KLOADS], Vr[8];
         };
-        auto load_kv = [&](RegSet& R, int buf, int pg0, int k1, int64_t head_off, int kb) {
-            const int kw = kb + 32 * w;
-            if (tile_layout && !(kb & 31) && kb + BK <= k1) {
-                const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][(kw >> pshift) - pg0]);
-                const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][((kw + 16) >> pshift) - pg0]);
+        // this wavefront's 32 keys kw.. of a block as two runs of 16 rows in pages pga, pgb
+        auto load_kv_runs = [&](RegSet& R, int pga, int pgb, int64_t head_off, int kw) {
+            {
                 const int64_t oa = (int64_t)pga * P.page_stride + head_off + (int64_t)(kw & pmask) * P.token_stride;
                 const int64_t ob = (int64_t)pgb * P.page_stride + head_off + (int64_t)((kw + 16) & pmask) * P.token_stride;
                 const char *ka = (const char*)(P.k_pool + oa), *kb_ = (const char*)(P.k_pool + ob);
@@ -659,6 +657,14 @@ __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
                 }
 #pragma unroll
                 for (int j = 0; j < 8; ++j) R.Vr[j] = stream_load((j < 4 ? va : vb) + (int64_t)(j & 3) * ts2, v_lane_off);
+            }
+        };
+        auto load_kv = [&](RegSet& R, int buf, int pg0, int k1, int64_t head_off, int kb) {
+            const int kw = kb + 32 * w;
+            if (tile_layout && !(kb & 31) && kb + BK <= k1) {
+                const int pga = __builtin_amdgcn_readfirstlane(sPT[buf][(kw >> pshift) - pg0]);
+                const int pgb = __builtin_amdgcn_readfirstlane(sPT[buf][((kw + 16) >> pshift) - pg0]);
+                load_kv_runs(R, pga, pgb, head_off, kw);
             } else {
 #pragma unroll
                 for (int i = 0; i < KLOADS; ++i) {
@@ -693,6 +699,15 @@ __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
         // next block's first key.  Page ids of the piece three ahead are requested while the last block
         // of c0 is issued (ahead of that block's K/V loads, so that the K/V loads stay the youngest) and
         // stored one step later into the buffer c0 has just left.
+        // The share's first block is requested at once when the host has resolved it (its page ids come with the
+        // share), as in the single-wavefront kernel: it arrives while the descriptors and page ids are fetched.
+        RegSet A, B;
+        typedef const int32_t __attribute__((address_space(4)))* ConstInts;
+        const ConstInts first = (ConstInts)(uintptr_t)(P.share_first + (int64_t)share * 10);
+        const int wu = __builtin_amdgcn_readfirstlane(w);
+        const int first_pga = first[2 * wu], first_pgb = first[2 * wu + 1], first_kvh = first[8], first_k0 = first[9];
+        bool ahead = first_k0 >= 0;
+        if (ahead) load_kv_runs(A, first_pga, first_pgb, (int64_t)first_kvh * P.head_stride, first_k0 + 32 * w);
         Piece c0, c1, c2, c3;
         fetch_piece(0, c0);
         fetch_piece(1, c1);
@@ -719,7 +734,8 @@ __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
                 load_pages(c3, pr);
                 pr_pending = true;
             }
-            load_kv(R, cb, c0.k0 >> pshift, c0.k1, (int64_t)(c0.head_flags & kPieceHeadMask) * P.head_stride, kb);
+            if (!ahead) load_kv(R, cb, c0.k0 >> pshift, c0.k1, (int64_t)(c0.head_flags & kPieceHeadMask) * P.head_stride, kb);
+            ahead = false;
             if (!last) {
                 kb += BK;
             } else if (c1.k1 > c1.k0) {
@@ -733,7 +749,6 @@ __device__ __forceinline__ void verify_attn_group_body(const AttnParams& P) {
         };
         // (a barrier after each of the first two issues as well: a page-id buffer is rewritten one step
         // after the cursor has left it, and every step must be over in all four wavefronts by then)
-        RegSet A, B;
         issue(A);
         __syncthreads();                 // barrier 1
         issue(B);

@@ -151,7 +151,7 @@ constexpr int kMaxWaves = 16384;   // wavefronts per launch the staging buffers 
 // pieces | per-class wavefront ranges | (strip, head) piece ranges | strip ranges | row offsets | tasks | page table
 size_t blob_size(int64_t req, int64_t rows, int64_t pages, int64_t items) {
     // every share holds at least one piece, so there are at most `items` share boundaries in all
-    return align16(items * sizeof(spin::Piece)) + align16(items * 4) + align16(items * 16) + 6 * 32 + 2 * align16(items * 8) +
+    return align16(items * sizeof(spin::Piece)) + align16(items * 4) + align16(items * 40) + 6 * 32 + 2 * align16(items * 8) +
            2 * align16((req + 1) * 4) + align16(pages * 4) + align16(rows * 16) + 128;
 }
 

@@ -28,8 +28,8 @@ struct AttnParams {
     const uint16_t* q;
     const Piece* pieces;         // (*) pieces of one column-tile class, in streaming order
     const int32_t* wave_begin;   // (*) [n_shares + 1] pieces of each share: gridDim.x per-wavefront shares, then queued chunks
-    const int32_t* share_first;  // (*) [n_shares][4] first block of each share: page ids of its two 16-key halves, KV head, first
-                                 // key (-1: the block is not requested ahead); single-wavefront kernels only
+    const int32_t* share_first;  // (*) first block of each share: page ids of its 16-key halves (two; eight for the grouped-query
+                                 // kernel's blocks), KV head, first key (-1: the block is not requested ahead)
     int32_t* queue;              // next queued chunk to hand out (zero at launch)
     int32_t n_queued;
     const int32_t* page_table;   // (*)

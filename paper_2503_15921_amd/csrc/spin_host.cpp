@@ -383,17 +383,19 @@ int build_plan(const spin_req_table* t, const spin_subreq* subs, int32_t n_sub, 
         }
         while ((int64_t)wb.size() < n_shares + 1) wb.push_back((int32_t)(plan.pieces.size() - plan.class_piece_begin[c]));
         // What a wavefront needs to request the first K/V block of a share before it has read anything else.
+        // Per share: the page ids of the block's 16-key halves (two for the single-wavefront kernels, eight for the
+        // grouped-query kernel's block of 128 keys), the KV head and the first key (-1: nothing is requested ahead).
         std::vector<int32_t>& sf = plan.share_first[c];
-        sf.assign((size_t)n_shares * 4, 0);
+        const int halves = bk / 16, rec = halves + 2;
+        sf.assign((size_t)n_shares * rec, 0);
         for (int64_t s = 0; s < n_shares; ++s) {
-            sf[s * 4 + 3] = -1;
+            sf[s * rec + halves + 1] = -1;
             if (wb[s] >= wb[s + 1] || !t->pt_offset || !t->page_table || page_size < 16) continue;
             const Piece& pc = plan.pieces[(size_t)plan.class_piece_begin[c] + wb[s]];
-            if ((pc.k0 & 31) || pc.k0 + 32 > pc.k1) continue;
-            sf[s * 4 + 0] = t->page_table[pc.pt_base + pc.k0 / page_size];
-            sf[s * 4 + 1] = t->page_table[pc.pt_base + (pc.k0 + 16) / page_size];
-            sf[s * 4 + 2] = pc.head_flags & kPieceHeadMask;
-            sf[s * 4 + 3] = pc.k0;
+            if ((pc.k0 & 31) || pc.k0 + bk > pc.k1) continue;
+            for (int h = 0; h < halves; ++h) sf[s * rec + h] = t->page_table[pc.pt_base + (pc.k0 + 16 * h) / page_size];
+            sf[s * rec + halves] = pc.head_flags & kPieceHeadMask;
+            sf[s * rec + halves + 1] = pc.k0;
         }
     }
     plan.class_piece_begin[3] = (int32_t)plan.pieces.size();

@@ -73,7 +73,7 @@ struct Plan {
     std::vector<int32_t> wave_begin[3];   // [n_shares+1] pieces (index within the class) of each share:
                                           // first the n_static per-wavefront shares, then the queued chunks
     int32_t n_static[3] = {0, 0, 0};
-    std::vector<int32_t> share_first[3];  // [n_shares][4] first block of each share: page ids of its two 16-key halves,
+    std::vector<int32_t> share_first[3];  // first block of each share: page ids of its 16-key halves (2, or 8 for class 2),
                                           // KV head, first key (-1: not a whole block on a 32-key boundary, or pages under 16 tokens)
     std::vector<int64_t> bounds;
     std::vector<int64_t> unit_ends;       // scratch: cumulative block count at the end of every (strip, head)
