@@ -184,8 +184,9 @@ def main():
     ap.add_argument("--seed", type=int, default=3)
     ap.add_argument("--page-size", type=int, default=0, help="tokens per KV page (0 = the configuration's, 16)")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"], help="element type of Q, K, V and the output")
-    ap.add_argument("--kv-layout", default="hnd", choices=["hnd", "nhd"],
-                    help="memory order of a KV page: [head][token][dim] (default) or [token][head][dim]")
+    ap.add_argument("--kv-layout", default="hnd", choices=["hnd", "nhd", "paired", "paired-head"],
+                    help="memory order of a KV page: [head][token][dim] (default), [token][head][dim], or K and V pages of the first kind "
+                         "paired in one allocation ([page][K|V][head][token][dim])")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per attention launch (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true", help="skip the pass over the other four configurations")
@@ -247,12 +248,25 @@ def main():
             # same logical [page][head][token][dim] tensors over [page][token][head][dim] memory: the library reads the strides
             batch.k_pool = batch.k_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
             batch.v_pool = batch.v_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        if args.kv_layout == "paired":
+            # one allocation, [page][K|V][head][token][dim]: the K and V of a (page, head) are 2 x 4 KiB side by side
+            both = torch.stack([batch.k_pool, batch.v_pool], dim=1).contiguous()
+            batch.k_pool, batch.v_pool = both[:, 0], both[:, 1]
+        if args.kv_layout == "paired-head":
+            # one allocation, [page][head][K|V][token][dim]: the K and V of a (page, head) are 8 KiB in one piece
+            both = torch.stack([batch.k_pool, batch.v_pool], dim=2).contiguous()
+            batch.k_pool, batch.v_pool = both[:, :, 0], both[:, :, 1]
         t = batch.table
         # Batches whose K/V is smaller than the chip's last-level cache would be flattered by it: every step reads another
         # copy of the pools, enough copies that 2 GB pass between two uses of the same bytes (one copy for 13b and 70b_gqa).
         kv_once = si.algorithmic_kv_bytes(t, cfg.n_kv_heads, cfg.head_dim)
         n_copies = max(1, min(16, -(-(2 << 30) // max(kv_once, 1))))
-        pools = [(batch.k_pool, batch.v_pool)] + [(batch.k_pool.clone(), batch.v_pool.clone()) for _ in range(n_copies - 1)]
+        if args.kv_layout == "paired":
+            pools = [(batch.k_pool, batch.v_pool)] + [(b[:, 0], b[:, 1]) for b in (both.clone() for _ in range(n_copies - 1))]
+        elif args.kv_layout == "paired-head":
+            pools = [(batch.k_pool, batch.v_pool)] + [(b[:, :, 0], b[:, :, 1]) for b in (both.clone() for _ in range(n_copies - 1))]
+        else:
+            pools = [(batch.k_pool, batch.v_pool)] + [(batch.k_pool.clone(), batch.v_pool.clone()) for _ in range(n_copies - 1)]
         step_no = [0]
         ab = si.make_accept_batch(t.draft_len, cfg.vocab, cfg.logit_sigma, args.seed, device=dev, rho=rho)
         M = max(1, args.microbatches)
