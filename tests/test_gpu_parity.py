@@ -275,6 +275,31 @@ def test_other_cache_layout_via_strides(ctx, hq, hkv, d):
     assert_close(out, oracle_attention(b, 0.0), "token-major cache layout")
 
 
+@pytest.mark.parametrize("dim", [1, 2])
+@pytest.mark.parametrize("hq,hkv,d", [(4, 2, 128), (16, 2, 128), (16, 2, 64)])
+def test_k_and_v_paired_in_one_allocation(ctx, hq, hkv, d, dim):
+    # one buffer holds both caches, [page][K|V][head][slot][dim] (dim 1) or [page][head][K|V][slot][dim] (dim 2): the
+    # pools are two views into it, with a doubled page (and head) stride; append first, then attention over the result
+    cfg = make_cfg("paired", 4, hq, hkv, d)
+    prefix = np.array([40, 333, 5, 800]); draft = np.array([5, 2, 8, 3])
+    b = si.make_verify_batch(cfg, 23, device="cuda", prefix_len=prefix, draft_len=draft)
+    k_new, v_new = new_rows(b, 123)
+    want_k, want_v = oracle_append(b, k_new, v_new)
+    both = torch.stack([b.k_pool, b.v_pool], dim=dim).contiguous()
+    kv, vv = (both[:, 0], both[:, 1]) if dim == 1 else (both[:, :, 0], both[:, :, 1])
+    assert kv.stride() == vv.stride() and kv.stride()[0] == 2 * b.k_pool.stride()[0]
+    t = b.table
+    tab = ctx.make_table(t.prefix_len, t.draft_len, t.q_offset, t.pt_offset, t.page_table)
+    ctx.append_kv(tab, kv, vv, k_new, v_new)
+    out = torch.empty_like(b.q)
+    ctx.verify_attn(tab, kv, vv, b.q, out, cfg.n_q_heads)
+    torch.cuda.synchronize()
+    assert np.array_equal(si.bf16_bits(kv.contiguous()), want_k) and np.array_equal(si.bf16_bits(vv.contiguous()), want_v)
+    b.k_pool = torch.from_numpy(want_k.view(np.int16)).view(torch.bfloat16).to("cuda")
+    b.v_pool = torch.from_numpy(want_v.view(np.int16)).view(torch.bfloat16).to("cuda")
+    assert_close(out, oracle_attention(b, 0.0), f"K and V paired along dimension {dim}")
+
+
 def test_small_pages(ctx):
     cfg = make_cfg("page4", 4, 2, 2, 64, page=4)
     prefix = np.array([9, 130, 0, 61]); draft = np.array([3, 5, 2, 1])
