@@ -187,6 +187,8 @@ def main():
     ap.add_argument("--kv-layout", default="hnd", choices=["hnd", "nhd", "paired", "paired-head"],
                     help="memory order of a KV page: [head][token][dim] (default), [token][head][dim], or K and V pages of the first kind "
                          "paired in one allocation ([page][K|V][head][token][dim])")
+    ap.add_argument("--pages-in-order", action="store_true",
+                    help="every request's pages consecutive in the pool (default: a shuffled pool, as after long service)")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per attention launch (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true", help="skip the pass over the other four configurations")
@@ -243,7 +245,7 @@ def main():
     def run_config(cfg, repeats, keep_inputs=False, rho=None, decomp=None):
         """Warm up, then time 1 + repeats regions of args.steps steps of `cfg`'s batch.  Returns a dict of figures
         (region 0 is the one a headline is taken from) and, on request, the inputs for the CPU baseline."""
-        batch = si.make_verify_batch(cfg, args.seed, device=dev, dtype=elem)
+        batch = si.make_verify_batch(cfg, args.seed, device=dev, dtype=elem, shuffle_pages=not args.pages_in_order)
         if args.kv_layout == "nhd":
             # same logical [page][head][token][dim] tensors over [page][token][head][dim] memory: the library reads the strides
             batch.k_pool = batch.k_pool.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
