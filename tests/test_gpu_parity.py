@@ -1356,6 +1356,44 @@ def test_many_calls_in_flight_keep_their_tables(ctx):
         assert torch.equal(out.view(torch.int16), alone[k].view(torch.int16)), f"call {call} (tables {k})"
 
 
+def test_long_run_of_mixed_calls(ctx):
+    """Two thousand attention + acceptance calls over three shapes in random order, the host up to 64 calls ahead of
+    the GPU: the counters behind the ring of table copies and its markers wrap many times.  Every output of every call
+    is compared, bit for bit, with what the same call gives alone (which is checked against the oracle)."""
+    import paper_2503_15921_amd as spin
+    rng = np.random.default_rng(11)
+    items = []
+    for k, (n, hq, hkv, d) in enumerate([(24, 8, 4, 128), (6, 32, 4, 128), (40, 4, 4, 64)]):
+        cfg = make_cfg(f"long{k}", n, hq, hkv, d)
+        b = si.make_verify_batch(cfg, 300 + k, device="cuda", prefix_len=rng.integers(100, 2500, n), draft_len=rng.integers(1, 9, n))
+        tab = ctx.make_table(b.table.prefix_len, b.table.draft_len, b.table.q_offset, b.table.pt_offset, b.table.page_table)
+        ab = si.make_accept_batch(b.table.draft_len, 4096 + 1000 * k, 2.0, 400 + k, device="cuda")
+        ref_o = hip_attention(ctx, b)
+        assert_close(ref_o, oracle_attention(b, 0.0), f"long run, shape {k}: alone")
+        ref_n, ref_x = hip_accept(ctx, spin.ACCEPT_REJECTION, ab)
+        want = oracle_accept(spin.ACCEPT_REJECTION, ab)
+        assert np.array_equal(ref_n, want[0]) and np.array_equal(ref_x, want[1])
+        items.append((cfg, b, tab, ab, ref_o, ref_n, ref_x))
+    pending = []
+    for call in range(2048):
+        k = int(rng.integers(0, 3))
+        cfg, b, tab, ab, ref_o, ref_n, ref_x = items[k]
+        out = torch.full_like(b.q, float("nan"))
+        n_acc = torch.full((len(ab.draft_len),), -7, dtype=torch.int32, device="cuda")
+        nxt = torch.full_like(n_acc, -7)
+        ctx.verify_attn(tab, b.k_pool, b.v_pool, b.q, out, cfg.n_q_heads)
+        ctx.accept(spin.ACCEPT_REJECTION, ab.draft_len, ab.draft_tokens, ab.target_logits, ab.draft_logits, ab.u_accept,
+                   ab.u_sample, n_acc, nxt)
+        pending.append((call, k, out, n_acc, nxt))
+        if len(pending) == 64 or call == 2047:
+            torch.cuda.synchronize()
+            for c, kk, o, na, nx in pending:
+                assert torch.equal(o.view(torch.int16), items[kk][4].view(torch.int16)), f"attention of call {c} (shape {kk})"
+                assert np.array_equal(na.cpu().numpy(), items[kk][5]) and np.array_equal(nx.cpu().numpy(), items[kk][6]), \
+                    f"acceptance of call {c} (shape {kk})"
+            pending = []
+
+
 def test_host_far_ahead_of_the_gpu_keeps_tables_apart(ctx):
     """Forty-eight calls of 7B-shaped batches with three different tables: each call's kernels run longer than the
     host needs to plan the next, so the host fills the whole ring of table copies and has to wait for slots."""
